@@ -1,0 +1,216 @@
+/*
+ * liborbit — batched GQA decode attention over a paged KV cache whose (request, layer) blocks
+ * are split between HBM and pinned host memory, for one AMD MI355X (gfx950).
+ *
+ * The calls follow the paper's problem statement (Section 3.3.1): a batch of requests with
+ * context lengths, L layers, a binary placement matrix x[r,l] (1 = KV of request r at layer l
+ * stays on the GPU, 0 = it is held in host memory and fetched before the layer runs) and a GPU
+ * block budget B_GPU bounded by Eq. (1).  The KV manager semantics (block tables, minimal
+ * data movement on a new placement, new KV of offloaded layers written straight to the host,
+ * a contiguous prefetch buffer) are those of Section 3.2, "KV Manager".
+ *
+ * Conventions
+ *  - Every call returns ORBIT_OK (0) or a negative ORBIT_E_* code; orbit_last_error() gives
+ *    the text.  No exception or abort crosses this boundary.
+ *  - "device" pointers are HIP device memory; "host" pointers are ordinary host memory unless
+ *    "pinned" is stated.  The library never frees or reallocates caller memory.
+ *  - All GPU work is enqueued on the two caller-owned streams and is asynchronous to the host
+ *    unless a call says it synchronises.  One context must be driven by one thread at a time.
+ *  - bf16 everywhere for Q, K, V and the output; accumulation is fp32.
+ *
+ * KV block ("page") layout, bf16 elements, P = page_tokens = 16, D = head_dim = 128:
+ *    page   = [K tile head 0]..[K tile head Hkv-1][V tile head 0]..[V tile head Hkv-1]
+ *    K tile : (tok, dim) at (dim/8)*(P*8) + tok*8 + dim%8
+ *    V tile : (tok, dim) at ((((dim/32)*(P/4) + tok/4)*16 + dim%16)*2 + (dim/16)%2)*4 + tok%4
+ * (each tile is 4 KiB; a page is Hkv*8 KiB).  Host-resident (request, layer) blocks use the
+ * same page layout in one contiguous run of pages.
+ */
+#ifndef ORBIT_H_
+#define ORBIT_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ORBIT_API __attribute__((visibility("default")))
+
+#define ORBIT_OK               0
+#define ORBIT_E_INVAL         -1  /* bad argument                                              */
+#define ORBIT_E_CAPACITY      -2  /* Eq. (1) violated: the planner's "infeasible"              */
+#define ORBIT_E_HOST_CAPACITY -3  /* pinned host arena too small                               */
+#define ORBIT_E_NOT_FOUND     -4  /* unknown request id                                        */
+#define ORBIT_E_STATE         -5  /* call not valid now (no plan, window expired, ...)         */
+#define ORBIT_E_HIP           -6  /* a HIP runtime call failed                                 */
+
+#define ORBIT_MAX_LAYERS   128
+#define ORBIT_MAX_REQUESTS 256
+
+/* flags */
+#define ORBIT_FLAG_HOST_ONLY 1    /* run only the host logic (tables, schedules); no GPU call is
+                                     made and the arenas may be NULL.  For CPU-side tests.      */
+
+typedef struct orbit_ctx orbit_ctx;
+
+typedef struct {
+  int32_t n_layers;               /* L, 1..ORBIT_MAX_LAYERS                                    */
+  int32_t n_q_heads;              /* Hq                                                         */
+  int32_t n_kv_heads;             /* Hkv; Hq % Hkv == 0 and Hq/Hkv <= 16                        */
+  int32_t head_dim;               /* must be 128                                                */
+  int32_t page_tokens;            /* must be 16 (16-token KV blocks, Section 2.3)               */
+  int32_t max_requests;           /* 1..ORBIT_MAX_REQUESTS                                      */
+  int64_t max_tokens_per_request; /* upper bound of any request's length                        */
+  float   softmax_scale;          /* <= 0 selects 1/sqrt(head_dim)                              */
+  int32_t prefetch_slots;         /* k >= 1: staging region = k * B_buf blocks; 1 = the paper's
+                                     single prefetch buffer of Eq. (1)                          */
+  int32_t chunk_tokens;           /* split-K chunk, multiple of 32; 0 selects the default       */
+  int32_t decode_window;          /* Delta >= 0: tokens each request may grow under one plan
+                                     (the decode window of Section 3.3.1); Eq. (1) is checked
+                                     with b_r = ceil((ctx_len + Delta)/16)                      */
+  int32_t flags;                  /* ORBIT_FLAG_*                                               */
+  void   *hbm_arena;              /* device, caller-owned, 256-byte aligned                     */
+  int64_t hbm_arena_bytes;
+  void   *host_arena;             /* pinned host (hipHostMalloc / torch pin_memory), caller-owned */
+  int64_t host_arena_bytes;
+  void   *compute_stream;         /* hipStream_t, caller-owned                                  */
+  void   *copy_stream;            /* hipStream_t, caller-owned, must differ from compute_stream */
+} orbit_config;
+
+/* Filled by orbit_step when requested; times in milliseconds from HIP events. */
+typedef struct {
+  float   step_ms;                       /* first enqueue to last kernel on compute_stream     */
+  float   attn_ms_total;                 /* sum of attn_ms                                      */
+  float   copy_ms_total;                 /* sum of copy_ms                                      */
+  float   stall_ms_total;                /* compute_stream time spent waiting for prefetches    */
+  int64_t hbm_kv_bytes;                  /* KV bytes attended from resident blocks              */
+  int64_t link_kv_bytes;                 /* KV bytes moved host -> staging this step            */
+  int64_t hbm_blocks_reserved;           /* resident blocks + staging region (left of Eq. (1))  */
+  int64_t hbm_blocks_budget;             /* B_GPU                                               */
+  float   attn_ms[ORBIT_MAX_LAYERS];     /* split-K attention kernel, per layer                 */
+  float   combine_ms[ORBIT_MAX_LAYERS];  /* combine kernel, per layer                           */
+  float   copy_ms[ORBIT_MAX_LAYERS];     /* host -> staging copies of that layer                */
+  float   stall_ms[ORBIT_MAX_LAYERS];
+  int64_t link_bytes[ORBIT_MAX_LAYERS];
+} orbit_step_stats;
+
+/* Static description of the installed plan (host integers). */
+typedef struct {
+  int64_t page_bytes;
+  int64_t budget_blocks;          /* B_GPU                                                      */
+  int64_t resident_blocks;        /* sum_r sum_l b_r x[r,l]                                     */
+  int64_t buffer_blocks;          /* B_buf = max_l sum_r (1 - x[r,l]) b_r                       */
+  int64_t staging_first_page;     /* the staging region is [first, first + staging_blocks)      */
+  int64_t staging_blocks;         /* prefetch_slots * B_buf                                     */
+  int64_t host_blocks;            /* blocks held in the pinned host arena                       */
+  int64_t moved_to_host_blocks;   /* data movement of the last orbit_plan_load (Section 3.2:    */
+  int64_t moved_to_hbm_blocks;    /*   only the delta between the two layouts is moved)         */
+  int64_t relocated_blocks;       /* resident blocks moved out of the new staging region        */
+  int32_t n_requests;
+  int32_t chunk_tokens;
+} orbit_plan_info;
+
+/* ---- lifetime (ancillary) ------------------------------------------------------------------ */
+
+/* Creates a context.  Allocates the library's own small device tables (page table, lengths,
+ * work list, split partials).  Fails with ORBIT_E_INVAL on an unsupported shape. */
+ORBIT_API int orbit_create(const orbit_config *cfg, orbit_ctx **out);
+/* Synchronises both streams, frees the library's own memory.  Caller arenas are untouched. */
+ORBIT_API int orbit_destroy(orbit_ctx *ctx);
+/* Text of the last error on this context (or of the last failed orbit_create if ctx is NULL). */
+ORBIT_API const char *orbit_last_error(orbit_ctx *ctx);
+
+/* ---- a1: plan install (Section 3.3.1: x[r,l], b_r, Eq. (1); Section 3.2: KV Manager) -------- */
+
+/* Pure function, no context: evaluates Eq. (1) for a placement.
+ * placement_bitmap: host, row-major [n_req][ceil(L/8)], bit l (LSB first) = x[r,l].
+ * out4 (host): {resident blocks, B_buf, resident + prefetch_slots*B_buf, host blocks}. */
+ORBIT_API int orbit_plan_check(int32_t n_req, int32_t n_layers, int32_t page_tokens, const int32_t *ctx_len,
+                     const uint8_t *placement_bitmap, int32_t prefetch_slots, int32_t decode_window,
+                     int64_t *out4);
+
+/* Installs a placement for the batch {req_ids}.  All pointers are host memory.
+ *   req_ids[n_req]  distinct ids; ids not listed are dropped and their blocks freed; ids not
+ *                   known yet are created holding ctx_len tokens of undefined content (write
+ *                   them with orbit_kv_fill).
+ *   ctx_len[n_req]  tokens held now; for a known request it must equal its current length.
+ *   placement_bitmap as in orbit_plan_check.
+ *   hbm_budget_bytes  B_GPU = floor(min(budget, arena) / page bytes).
+ * Checks Eq. (1) (ORBIT_E_CAPACITY) and the host arena (ORBIT_E_HOST_CAPACITY); on any error
+ * NOTHING changes.  On success it moves only the blocks whose tier changed, plus resident
+ * blocks that sit where the new contiguous staging region goes, rebuilds the tables, and
+ * returns after both streams have drained (this call synchronises). */
+ORBIT_API int orbit_plan_load(orbit_ctx *ctx, int32_t n_req, const int64_t *req_ids, const int32_t *ctx_len,
+                    const uint8_t *placement_bitmap, int64_t hbm_budget_bytes);
+
+ORBIT_API int orbit_get_plan_info(orbit_ctx *ctx, orbit_plan_info *out);
+
+/* ---- a3: KV writes (Section 2.3 block growth; Section 3.2 direct-to-host writes) ------------ */
+
+/* Bulk write (the product of prefill): tokens [first_token, first_token + n_tokens) of
+ * (req_id, layer), k and v device pointers, token-major [n_tokens][Hkv][D] bf16, read
+ * asynchronously on compute_stream.  The range must lie inside the request's current length. */
+ORBIT_API int orbit_kv_fill(orbit_ctx *ctx, int64_t req_id, int32_t layer, int64_t first_token,
+                  int64_t n_tokens, const void *k, const void *v);
+
+/* Gather back to token-major (diagnostic; bit-exact inverse of orbit_kv_fill/append).
+ * k_out, v_out: device [n_tokens][Hkv][D] bf16.  Asynchronous on compute_stream. */
+ORBIT_API int orbit_kv_read(orbit_ctx *ctx, int64_t req_id, int32_t layer, int64_t first_token,
+                  int64_t n_tokens, void *k_out, void *v_out);
+
+/* Appends ONE token to (req_id, layer): k, v device [Hkv][D] bf16, read asynchronously on
+ * compute_stream.  A new block is started only when the length is a multiple of 16; it comes
+ * from the blocks the plan reserved (ORBIT_E_STATE once the decode window is used up).  For an
+ * offloaded layer the token is written straight to its host slot, and also into the staging
+ * copy if that layer is currently prefetched.  Lengths are kept per (request, layer). */
+ORBIT_API int orbit_kv_append(orbit_ctx *ctx, int64_t req_id, int32_t layer, const void *k, const void *v);
+
+/* ---- a4/a5: prefetch and gating (Section 3.3.1, "Scheduling KV Prefetching") ---------------- */
+
+/* Enqueues, on copy_stream, the host -> staging copies of every offloaded request of `layer`
+ * (smallest first) and records that layer's "ready" event.  A staging range is reused only
+ * after the layer that read it has been enqueued and has finished (stream-side wait, never a
+ * host wait).  No-op for a layer with nothing offloaded or already prefetched.
+ * ORBIT_E_STATE if the range is still needed by a prefetched layer not yet attended. */
+ORBIT_API int orbit_kv_prefetch(orbit_ctx *ctx, int32_t layer);
+
+/* ---- a6/a7: attention ---------------------------------------------------------------------- */
+
+/* Batched decode attention of one layer over the stored lengths of that layer.
+ * q: device [n_req][Hq][D] bf16 in plan order; out: device [n_req][Hq][D] bf16;
+ * out_f32: optional device [n_req][Hq][D] fp32 (same values before the bf16 rounding), or NULL.
+ * Prefetches the layer if needed, waits for it stream-side, runs split-K attention and the
+ * combine on compute_stream.  ORBIT_E_INVAL if any request of the plan holds no token. */
+ORBIT_API int orbit_decode_attention(orbit_ctx *ctx, int32_t layer, const void *q, void *out, float *out_f32);
+
+/* ---- a8: one decode step -------------------------------------------------------------------- */
+
+/* For l = 0..L-1 in order: append k_new[l], v_new[l] to every request, then attend q[l] over
+ * the grown cache into out[l]; prefetches run ahead on copy_stream.
+ * q, out: device [L][n_req][Hq][D] bf16; k_new, v_new: device [L][n_req][Hkv][D] bf16.
+ * stats: NULL, or host memory to fill; filling it blocks until the step has finished. */
+ORBIT_API int orbit_step(orbit_ctx *ctx, const void *q, const void *k_new, const void *v_new, void *out,
+               orbit_step_stats *stats);
+
+/* ---- host-side introspection (integers only; used by tests) --------------------------------- */
+
+/* Page ids that attention reads for (req_id, layer): arena ids for a resident block list,
+ * staging-region ids for an offloaded one.  Writes up to cap ids, returns the reserved count
+ * (or a negative error).  tier: 1 = HBM, 0 = host; host_first_page: index of the run's first
+ * page in the host arena (or -1); length: tokens stored. */
+ORBIT_API int64_t orbit_get_pages(orbit_ctx *ctx, int64_t req_id, int32_t layer, int32_t *tier,
+                        int64_t *host_first_page, int32_t *length, int32_t *pages_out, int64_t cap);
+
+/* Split-K work items of `layer` for the current lengths: rows {request index, kv head, chunk
+ * index, partial slot}.  Returns the item count. */
+ORBIT_API int64_t orbit_get_work_items(orbit_ctx *ctx, int32_t layer, int32_t *items_out, int64_t cap);
+
+/* Copy schedule of the installed plan: rows {layer, request index, staging first page,
+ * reserved pages, position of the layer's range in the staging region}, in issue order.
+ * Returns the row count. */
+ORBIT_API int64_t orbit_get_copy_schedule(orbit_ctx *ctx, int32_t *rows_out, int64_t cap);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ORBIT_H_ */

@@ -1,0 +1,729 @@
+// C ABI of liborbit (see include/orbit.h): ties the host state (orbit_host.hpp) to the gfx950
+// kernels (orbit_kernels.hip) and to the two caller streams.  There is no CPU fallback: without
+// a GPU every call that needs one returns ORBIT_E_HIP (ORBIT_FLAG_HOST_ONLY contexts run the
+// integer host logic only and never produce attention output).
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <memory>
+#include <string>
+#include <vector>
+
+#include "../../include/orbit.h"
+#include "orbit_host.hpp"
+#include "orbit_kernels.h"
+
+using namespace orbit;
+
+namespace {
+std::string g_create_error;
+constexpr int kDefaultChunkTokens = 512;
+}  // namespace
+
+struct orbit_ctx {
+  orbit_config cfg{};
+  HostState hs;
+  bool host_only = false;
+  hipStream_t cs = nullptr, xs = nullptr;  // compute, copy
+  uint8_t *arena = nullptr;
+  uint8_t *host_dev = nullptr;  // device-visible address of the pinned host arena
+  int32_t *d_table = nullptr, *d_len = nullptr, *d_items = nullptr;
+  float *d_pacc = nullptr, *d_pml = nullptr;
+  BlitOp *d_ops = nullptr;
+  size_t d_ops_cap = 0;
+  int32_t *h_items_pinned[2] = {nullptr, nullptr};
+  hipEvent_t ev_items[2] = {nullptr, nullptr};
+  int items_buf = 0;
+  int64_t slots = 0;
+  std::vector<hipEvent_t> ev_ready, ev_done;
+  hipEvent_t ev_tmp = nullptr;
+  std::vector<hipEvent_t> t_wait0, t_wait1, t_attn0, t_attn1, t_comb1, t_copy0, t_copy1;
+  hipEvent_t t_step0 = nullptr, t_step1 = nullptr;
+  std::vector<uint8_t> host_dirty;    // per layer: host pages written since the last ordering point
+  std::vector<uint8_t> copy_timed;    // per layer: t_copy0/1 recorded in this step
+  std::vector<int64_t> copy_bytes;    // per layer, last prefetch
+  std::vector<int32_t> items_nchunks; // cache key of the uploaded work list
+  int64_t n_items = 0;
+  bool items_valid = false;
+  float scale_log2 = 0.f;
+  int variant = 0;
+  bool timing = false;
+  std::string err;
+};
+
+namespace {
+
+int set_err(orbit_ctx *c, int code, const std::string &msg) {
+  c->err = msg;
+  return code;
+}
+int hip_fail(orbit_ctx *c, hipError_t e, const char *what) {
+  c->err = std::string(what) + ": " + hipGetErrorString(e);
+  return ORBIT_E_HIP;
+}
+#define HIPCHECK(c, x)                                  \
+  do {                                                  \
+    hipError_t e_ = (x);                                \
+    if (e_ != hipSuccess) return hip_fail((c), e_, #x); \
+  } while (0)
+
+int make_events(orbit_ctx *c, std::vector<hipEvent_t> &v, int n, bool timing) {
+  v.assign(n, nullptr);
+  for (int i = 0; i < n; ++i)
+    HIPCHECK(c, hipEventCreateWithFlags(&v[i], timing ? hipEventDefault : hipEventDisableTiming));
+  return ORBIT_OK;
+}
+void drop_events(std::vector<hipEvent_t> &v) {
+  for (auto e : v)
+    if (e) (void)hipEventDestroy(e);
+  v.clear();
+}
+
+LiveBlock *find_live(orbit_ctx *c, int layer) {
+  for (auto &lb : c->hs.live)
+    if (lb.layer == layer) return &lb;
+  return nullptr;
+}
+
+// 0 = issued (or nothing to do), 1 = blocked by a prefetched layer not yet attended, <0 = error
+int prefetch_impl(orbit_ctx *c, int layer) {
+  HostState &hs = c->hs;
+  const int b = hs.block_of_layer[layer];
+  if (b < 0) return 0;
+  LiveBlock *mine = find_live(c, layer);
+  if (mine && !mine->consumed) return 0;
+  const StageBlock &blk = hs.blocks[b];
+  const int32_t p0 = blk.p0, p1 = blk.p0 + blk.n;
+  for (auto &lb : hs.live)
+    if (lb.p0 < p1 && p0 < lb.p1 && !lb.consumed) return 1;
+  for (size_t i = 0; i < hs.live.size();) {
+    LiveBlock &lb = hs.live[i];
+    if (lb.p0 < p1 && p0 < lb.p1) {
+      if (!c->host_only) HIPCHECK(c, hipStreamWaitEvent(c->xs, c->ev_done[lb.layer], 0));
+      hs.live.erase(hs.live.begin() + i);
+    } else {
+      ++i;
+    }
+  }
+  if (c->host_dirty[layer]) {
+    if (!c->host_only) {
+      HIPCHECK(c, hipEventRecord(c->ev_tmp, c->cs));
+      HIPCHECK(c, hipStreamWaitEvent(c->xs, c->ev_tmp, 0));
+    }
+    c->host_dirty[layer] = 0;
+  }
+  if (c->timing && !c->host_only) HIPCHECK(c, hipEventRecord(c->t_copy0[layer], c->xs));
+  int64_t bytes = 0;
+  for (const CopyItem &ci : blk.copies) {
+    const LayerKV &lk = hs.reqs[ci.req].layers[layer];
+    const int64_t used = ceil_div(lk.len, hs.sh.P);
+    if (used == 0) continue;
+    const int64_t nbytes = used * hs.sh.page_bytes;
+    bytes += nbytes;
+    if (!c->host_only)
+      HIPCHECK(c, hipMemcpyAsync(c->arena + (int64_t)ci.stage_page0 * hs.sh.page_bytes,
+                                 (const uint8_t *)c->cfg.host_arena + lk.host_page0 * hs.sh.page_bytes, (size_t)nbytes,
+                                 hipMemcpyHostToDevice, c->xs));
+  }
+  c->copy_bytes[layer] = bytes;
+  if (!c->host_only) {
+    if (c->timing) {
+      HIPCHECK(c, hipEventRecord(c->t_copy1[layer], c->xs));
+      c->copy_timed[layer] = 1;
+    }
+    HIPCHECK(c, hipEventRecord(c->ev_ready[layer], c->xs));
+  }
+  hs.live.push_back({layer, p0, p1, false});
+  return 0;
+}
+
+int ensure_work_items(orbit_ctx *c, int layer) {
+  HostState &hs = c->hs;
+  const int nreq = (int)hs.reqs.size();
+  std::vector<int32_t> key(nreq);
+  for (int r = 0; r < nreq; ++r) {
+    const int32_t n = hs.reqs[r].layers[layer].len;
+    if (n < 1) return set_err(c, ORBIT_E_INVAL, "a request holds no token in this layer");
+    key[r] = (int32_t)ceil_div(n, hs.sh.chunk_tokens);
+  }
+  if (c->items_valid && key == c->items_nchunks) return ORBIT_OK;
+  std::vector<int32_t> items;
+  int rc = hs.build_work_items(layer, items);
+  if (rc) return set_err(c, rc, hs.err);
+  c->n_items = (int64_t)items.size() / 4;
+  if (!c->host_only) {
+    const int b = c->items_buf ^= 1;
+    HIPCHECK(c, hipEventSynchronize(c->ev_items[b]));  // last upload from this buffer is long done
+    std::memcpy(c->h_items_pinned[b], items.data(), items.size() * sizeof(int32_t));
+    HIPCHECK(c, hipMemcpyAsync(c->d_items, c->h_items_pinned[b], items.size() * sizeof(int32_t),
+                               hipMemcpyHostToDevice, c->cs));
+    HIPCHECK(c, hipEventRecord(c->ev_items[b], c->cs));
+  }
+  c->items_nchunks = std::move(key);
+  c->items_valid = true;
+  return ORBIT_OK;
+}
+
+// Waits for the layer's staging data (prefetching it first if nobody did), then attention + combine.
+int attention_impl(orbit_ctx *c, int layer, const void *q, void *out, float *out_f32, bool wait_done_already) {
+  HostState &hs = c->hs;
+  const Shape &sh = hs.sh;
+  const int nreq = (int)hs.reqs.size();
+  int rc = ensure_work_items(c, layer);
+  if (rc) return rc;
+  const bool staged = hs.block_of_layer[layer] >= 0;
+  if (staged && !wait_done_already) {
+    LiveBlock *lb = find_live(c, layer);
+    if (!lb || lb->consumed) {
+      rc = prefetch_impl(c, layer);
+      if (rc == 1) return set_err(c, ORBIT_E_STATE, "staging range still needed by a prefetched layer not yet attended");
+      if (rc) return rc;
+      lb = find_live(c, layer);
+    }
+    if (!c->host_only) HIPCHECK(c, hipStreamWaitEvent(c->cs, c->ev_ready[layer], 0));
+    lb->consumed = true;
+  }
+  if (!c->host_only) {
+    if (c->timing) HIPCHECK(c, hipEventRecord(c->t_attn0[layer], c->cs));
+    AttnParams ap{};
+    ap.arena = c->arena;
+    ap.table = c->d_table;
+    ap.lens = c->d_len;
+    ap.items = c->d_items;
+    ap.q = (const uint16_t *)q;
+    ap.pacc = c->d_pacc;
+    ap.pml = c->d_pml;
+    ap.page_bytes = sh.page_bytes;
+    ap.L = sh.L;
+    ap.layer = layer;
+    ap.cap_pages = sh.cap_pages;
+    ap.Hq = sh.Hq;
+    ap.Hkv = sh.Hkv;
+    ap.G = sh.G;
+    ap.chunk_tokens = sh.chunk_tokens;
+    ap.n_items = (int32_t)c->n_items;
+    ap.scale_log2 = c->scale_log2;
+    ap.variant = c->variant;
+    HIPCHECK(c, launch_attention(ap, c->cs));
+    if (c->timing) HIPCHECK(c, hipEventRecord(c->t_attn1[layer], c->cs));
+    CombineParams cp{};
+    cp.pacc = c->d_pacc;
+    cp.pml = c->d_pml;
+    cp.lens = c->d_len;
+    cp.out = (uint16_t *)out;
+    cp.out_f32 = out_f32;
+    cp.L = sh.L;
+    cp.layer = layer;
+    cp.Hq = sh.Hq;
+    cp.Hkv = sh.Hkv;
+    cp.G = sh.G;
+    cp.chunk_tokens = sh.chunk_tokens;
+    cp.max_chunks = sh.max_chunks;
+    cp.n_req = nreq;
+    HIPCHECK(c, launch_combine(cp, c->cs));
+    if (c->timing) HIPCHECK(c, hipEventRecord(c->t_comb1[layer], c->cs));
+    if (staged) HIPCHECK(c, hipEventRecord(c->ev_done[layer], c->cs));
+  }
+  return ORBIT_OK;
+}
+
+int check_layer(orbit_ctx *c, int layer) {
+  if (!c) return ORBIT_E_INVAL;
+  if (!c->hs.has_plan) return set_err(c, ORBIT_E_STATE, "no plan installed");
+  if (layer < 0 || layer >= c->hs.sh.L) return set_err(c, ORBIT_E_INVAL, "layer out of range");
+  return ORBIT_OK;
+}
+
+int run_phases(orbit_ctx *c, const std::vector<std::vector<PageOp>> &phases) {
+  const HostState &hs = c->hs;
+  size_t total = 0;
+  for (auto &ph : phases) total += ph.size();
+  if (total == 0 || c->host_only) return ORBIT_OK;
+  if (total > c->d_ops_cap) {
+    if (c->d_ops) HIPCHECK(c, hipFree(c->d_ops));
+    c->d_ops = nullptr;
+    c->d_ops_cap = 0;
+    HIPCHECK(c, hipMalloc((void **)&c->d_ops, total * sizeof(BlitOp)));
+    c->d_ops_cap = total;
+  }
+  std::vector<BlitOp> ops;
+  ops.reserve(total);
+  const int64_t pb = hs.sh.page_bytes;
+  auto hbm = [&](int64_t p) { return (uint64_t)(uintptr_t)(c->arena + p * pb); };
+  auto hst = [&](int64_t p) { return (uint64_t)(uintptr_t)(c->host_dev + p * pb); };
+  for (auto &ph : phases)
+    for (const PageOp &op : ph) {
+      BlitOp b{};
+      switch (op.kind) {
+        case OP_HBM_TO_HOST: b.src = hbm(op.src); b.dst = hst(op.dst); break;
+        case OP_HOST_TO_HBM: b.src = hst(op.src); b.dst = hbm(op.dst); break;
+        case OP_HBM_TO_HBM: b.src = hbm(op.src); b.dst = hbm(op.dst); break;
+        default: b.src = hst(op.src); b.dst = hst(op.dst); break;
+      }
+      ops.push_back(b);
+    }
+  HIPCHECK(c, hipMemcpy(c->d_ops, ops.data(), total * sizeof(BlitOp), hipMemcpyHostToDevice));
+  size_t at = 0;
+  for (auto &ph : phases) {
+    if (ph.empty()) continue;
+    HIPCHECK(c, launch_blit(c->d_ops + at, (int64_t)ph.size(), pb, c->xs));  // phases run in stream order
+    at += ph.size();
+  }
+  HIPCHECK(c, hipStreamSynchronize(c->xs));
+  return ORBIT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *orbit_last_error(orbit_ctx *ctx) { return ctx ? ctx->err.c_str() : g_create_error.c_str(); }
+
+int orbit_plan_check(int32_t n_req, int32_t n_layers, int32_t page_tokens, const int32_t *ctx_len,
+                     const uint8_t *placement_bitmap, int32_t prefetch_slots, int32_t decode_window, int64_t *out4) {
+  if (n_req < 0 || n_layers < 1 || page_tokens < 1 || prefetch_slots < 1 || decode_window < 0 || !out4) return ORBIT_E_INVAL;
+  if (n_req > 0 && (!ctx_len || !placement_bitmap)) return ORBIT_E_INVAL;
+  std::vector<int64_t> b(n_req);
+  std::vector<uint8_t> x((size_t)n_req * n_layers);
+  for (int r = 0; r < n_req; ++r) {
+    if (ctx_len[r] < 0) return ORBIT_E_INVAL;
+    b[r] = ceil_div((int64_t)ctx_len[r] + decode_window, page_tokens);
+    for (int l = 0; l < n_layers; ++l) x[(size_t)r * n_layers + l] = bitmap_get(placement_bitmap, n_layers, r, l);
+  }
+  Eq1 e = eq1_eval(n_req, n_layers, b, x);
+  out4[0] = e.resident;
+  out4[1] = e.buffer;
+  out4[2] = e.resident + (int64_t)prefetch_slots * e.buffer;
+  out4[3] = e.host;
+  return ORBIT_OK;
+}
+
+int orbit_create(const orbit_config *cfg, orbit_ctx **out) {
+  auto bad = [&](const char *m) {
+    g_create_error = m;
+    return ORBIT_E_INVAL;
+  };
+  if (!cfg || !out) return bad("null argument");
+  *out = nullptr;
+  if (cfg->n_layers < 1 || cfg->n_layers > ORBIT_MAX_LAYERS) return bad("n_layers out of range");
+  if (cfg->head_dim != 128) return bad("head_dim must be 128");
+  if (cfg->page_tokens != 16) return bad("page_tokens must be 16");
+  if (cfg->n_kv_heads < 1 || cfg->n_q_heads < 1 || cfg->n_q_heads % cfg->n_kv_heads) return bad("bad head counts");
+  if (cfg->n_q_heads / cfg->n_kv_heads > 16) return bad("more than 16 query heads per kv head");
+  if (cfg->max_requests < 1 || cfg->max_requests > ORBIT_MAX_REQUESTS) return bad("max_requests out of range");
+  if (cfg->max_tokens_per_request < 1 || cfg->max_tokens_per_request > (1 << 24)) return bad("max_tokens_per_request out of range");
+  if (cfg->prefetch_slots < 1 || cfg->prefetch_slots > 16) return bad("prefetch_slots out of range");
+  if (cfg->decode_window < 0) return bad("negative decode_window");
+  const int ch = cfg->chunk_tokens == 0 ? kDefaultChunkTokens : cfg->chunk_tokens;
+  if (ch < 32 || ch % 32 || ch > 65536) return bad("chunk_tokens must be a multiple of 32");
+  const bool host_only = (cfg->flags & ORBIT_FLAG_HOST_ONLY) != 0;
+  if (cfg->hbm_arena_bytes < 0 || cfg->host_arena_bytes < 0) return bad("negative arena size");
+  if (!host_only) {
+    if (!cfg->hbm_arena || ((uintptr_t)cfg->hbm_arena & 255)) return bad("hbm_arena must be a 256-byte aligned device pointer");
+    if (cfg->host_arena_bytes > 0 && !cfg->host_arena) return bad("host_arena is NULL");
+    if (cfg->compute_stream == cfg->copy_stream) return bad("compute_stream and copy_stream must differ");
+  }
+
+  std::unique_ptr<orbit_ctx> c(new orbit_ctx());
+  c->cfg = *cfg;
+  c->host_only = host_only;
+  Shape sh;
+  sh.L = cfg->n_layers;
+  sh.Hq = cfg->n_q_heads;
+  sh.Hkv = cfg->n_kv_heads;
+  sh.G = sh.Hq / sh.Hkv;
+  sh.D = 128;
+  sh.P = 16;
+  sh.max_req = cfg->max_requests;
+  sh.max_tokens = cfg->max_tokens_per_request;
+  sh.page_bytes = (int64_t)2 * sh.Hkv * sh.P * sh.D * 2;
+  sh.cap_pages = (int)((ceil_div(sh.max_tokens, sh.P) + 1) & ~(int64_t)1);
+  sh.chunk_tokens = ch;
+  sh.max_chunks = (int)ceil_div(sh.max_tokens, ch);
+  sh.window = cfg->decode_window;
+  sh.slots = cfg->prefetch_slots;
+  const int64_t arena_pages = cfg->hbm_arena_bytes / sh.page_bytes;
+  if (arena_pages > 0x7FFFFFF0) return bad("hbm arena has too many pages");
+  c->hs.init(sh, arena_pages, cfg->host_arena_bytes / sh.page_bytes);
+  c->host_dirty.assign(sh.L, 0);
+  c->copy_timed.assign(sh.L, 0);
+  c->copy_bytes.assign(sh.L, 0);
+  const float scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)sh.D);
+  c->scale_log2 = (float)((double)scale * 1.4426950408889634);
+  c->slots = (int64_t)sh.max_req * sh.max_chunks * sh.Hkv;
+  if (const char *v = std::getenv("ORBIT_ATTN_VARIANT")) c->variant = std::atoi(v);
+
+  if (!host_only) {
+    orbit_ctx *p = c.get();
+    auto hipbad = [&](hipError_t e, const char *what) {
+      g_create_error = std::string(what) + ": " + hipGetErrorString(e);
+      return ORBIT_E_HIP;
+    };
+#define CREATE_CHECK(x)                                \
+  do {                                                 \
+    hipError_t e_ = (x);                               \
+    if (e_ != hipSuccess) return hipbad(e_, #x);       \
+  } while (0)
+    p->cs = (hipStream_t)cfg->compute_stream;
+    p->xs = (hipStream_t)cfg->copy_stream;
+    p->arena = (uint8_t *)cfg->hbm_arena;
+    if (cfg->host_arena_bytes > 0) {
+      void *dp = nullptr;
+      CREATE_CHECK(hipHostGetDevicePointer(&dp, cfg->host_arena, 0));
+      p->host_dev = (uint8_t *)dp;
+    }
+    CREATE_CHECK(hipMalloc((void **)&p->d_table, c->hs.h_table.size() * sizeof(int32_t)));
+    CREATE_CHECK(hipMalloc((void **)&p->d_len, c->hs.h_len.size() * sizeof(int32_t)));
+    CREATE_CHECK(hipMalloc((void **)&p->d_items, (size_t)c->slots * 4 * sizeof(int32_t)));
+    CREATE_CHECK(hipMalloc((void **)&p->d_pacc, (size_t)c->slots * sh.G * 128 * sizeof(float)));
+    CREATE_CHECK(hipMalloc((void **)&p->d_pml, (size_t)c->slots * 32 * sizeof(float)));
+    CREATE_CHECK(hipMemset(p->d_table, 0, c->hs.h_table.size() * sizeof(int32_t)));
+    CREATE_CHECK(hipMemset(p->d_len, 0, c->hs.h_len.size() * sizeof(int32_t)));
+    for (int b = 0; b < 2; ++b) {
+      CREATE_CHECK(hipHostMalloc((void **)&p->h_items_pinned[b], (size_t)c->slots * 4 * sizeof(int32_t), hipHostMallocDefault));
+      CREATE_CHECK(hipEventCreateWithFlags(&p->ev_items[b], hipEventDisableTiming));
+    }
+    CREATE_CHECK(hipEventCreateWithFlags(&p->ev_tmp, hipEventDisableTiming));
+    CREATE_CHECK(hipEventCreate(&p->t_step0));
+    CREATE_CHECK(hipEventCreate(&p->t_step1));
+#undef CREATE_CHECK
+    int rc = 0;
+    if ((rc = make_events(p, p->ev_ready, sh.L, false)) || (rc = make_events(p, p->ev_done, sh.L, false)) ||
+        (rc = make_events(p, p->t_wait0, sh.L, true)) || (rc = make_events(p, p->t_wait1, sh.L, true)) ||
+        (rc = make_events(p, p->t_attn0, sh.L, true)) || (rc = make_events(p, p->t_attn1, sh.L, true)) ||
+        (rc = make_events(p, p->t_comb1, sh.L, true)) || (rc = make_events(p, p->t_copy0, sh.L, true)) ||
+        (rc = make_events(p, p->t_copy1, sh.L, true))) {
+      g_create_error = p->err;
+      orbit_destroy(c.release());
+      return rc;
+    }
+  }
+  *out = c.release();
+  return ORBIT_OK;
+}
+
+int orbit_destroy(orbit_ctx *c) {
+  if (!c) return ORBIT_E_INVAL;
+  if (!c->host_only) {
+    if (c->cs || c->xs) {
+      (void)hipStreamSynchronize(c->cs);
+      (void)hipStreamSynchronize(c->xs);
+    }
+    (void)hipFree(c->d_table);
+    (void)hipFree(c->d_len);
+    (void)hipFree(c->d_items);
+    (void)hipFree(c->d_pacc);
+    (void)hipFree(c->d_pml);
+    (void)hipFree(c->d_ops);
+    for (int b = 0; b < 2; ++b) {
+      if (c->h_items_pinned[b]) (void)hipHostFree(c->h_items_pinned[b]);
+      if (c->ev_items[b]) (void)hipEventDestroy(c->ev_items[b]);
+    }
+    if (c->ev_tmp) (void)hipEventDestroy(c->ev_tmp);
+    if (c->t_step0) (void)hipEventDestroy(c->t_step0);
+    if (c->t_step1) (void)hipEventDestroy(c->t_step1);
+    drop_events(c->ev_ready);
+    drop_events(c->ev_done);
+    drop_events(c->t_wait0);
+    drop_events(c->t_wait1);
+    drop_events(c->t_attn0);
+    drop_events(c->t_attn1);
+    drop_events(c->t_comb1);
+    drop_events(c->t_copy0);
+    drop_events(c->t_copy1);
+  }
+  delete c;
+  return ORBIT_OK;
+}
+
+int orbit_plan_load(orbit_ctx *c, int32_t n_req, const int64_t *req_ids, const int32_t *ctx_len,
+                    const uint8_t *placement_bitmap, int64_t hbm_budget_bytes) {
+  if (!c) return ORBIT_E_INVAL;
+  if (!c->host_only) {
+    HIPCHECK(c, hipStreamSynchronize(c->cs));
+    HIPCHECK(c, hipStreamSynchronize(c->xs));
+  }
+  std::vector<std::vector<PageOp>> phases;
+  int rc = c->hs.plan_load(n_req, req_ids, ctx_len, placement_bitmap, hbm_budget_bytes, phases);
+  if (rc) return set_err(c, rc, c->hs.err);
+  c->items_valid = false;
+  std::fill(c->host_dirty.begin(), c->host_dirty.end(), 0);
+  if ((rc = run_phases(c, phases))) return rc;
+  if (!c->host_only && n_req > 0) {
+    const Shape &sh = c->hs.sh;
+    HIPCHECK(c, hipMemcpy(c->d_table, c->hs.h_table.data(), (size_t)n_req * sh.L * sh.cap_pages * sizeof(int32_t),
+                          hipMemcpyHostToDevice));
+    HIPCHECK(c, hipMemcpy(c->d_len, c->hs.h_len.data(), (size_t)n_req * sh.L * sizeof(int32_t), hipMemcpyHostToDevice));
+  }
+  return ORBIT_OK;
+}
+
+int orbit_get_plan_info(orbit_ctx *c, orbit_plan_info *out) {
+  if (!c || !out) return ORBIT_E_INVAL;
+  if (!c->hs.has_plan) return set_err(c, ORBIT_E_STATE, "no plan installed");
+  *out = c->hs.info;
+  return ORBIT_OK;
+}
+
+static int fill_or_read(orbit_ctx *c, bool write, int64_t req_id, int32_t layer, int64_t first, int64_t n, void *k, void *v) {
+  int rc = check_layer(c, layer);
+  if (rc) return rc;
+  const int r = c->hs.find(req_id);
+  if (r < 0) return set_err(c, ORBIT_E_NOT_FOUND, "unknown request id");
+  LayerKV &lk = c->hs.reqs[r].layers[layer];
+  if (first < 0 || n < 0 || first + n > lk.len) return set_err(c, ORBIT_E_INVAL, "token range outside the stored length");
+  if (n == 0) return ORBIT_OK;
+  if (!k || !v) return set_err(c, ORBIT_E_INVAL, "null argument");
+  if (write && lk.tier == 0) {
+    LiveBlock *lb = find_live(c, layer);
+    if (lb && !lb->consumed) return set_err(c, ORBIT_E_STATE, "layer is prefetched; attend it before rewriting its host blocks");
+    c->host_dirty[layer] = 1;
+  }
+  if (c->host_only) return ORBIT_OK;
+  const Shape &sh = c->hs.sh;
+  FillParams fp{};
+  fp.arena = c->arena;
+  if (lk.tier == 1) fp.row = c->d_table + ((int64_t)r * sh.L + layer) * sh.cap_pages;
+  else fp.host_run = c->host_dev + lk.host_page0 * sh.page_bytes;
+  fp.k = (uint16_t *)k;
+  fp.v = (uint16_t *)v;
+  fp.len_slot = nullptr;
+  fp.page_bytes = sh.page_bytes;
+  fp.first_token = first;
+  fp.n_tokens = n;
+  fp.Hkv = sh.Hkv;
+  HIPCHECK(c, write ? launch_fill(fp, c->cs) : launch_gather(fp, c->cs));
+  return ORBIT_OK;
+}
+
+int orbit_kv_fill(orbit_ctx *c, int64_t req_id, int32_t layer, int64_t first_token, int64_t n_tokens, const void *k,
+                  const void *v) {
+  return fill_or_read(c, true, req_id, layer, first_token, n_tokens, (void *)k, (void *)v);
+}
+
+int orbit_kv_read(orbit_ctx *c, int64_t req_id, int32_t layer, int64_t first_token, int64_t n_tokens, void *k_out,
+                  void *v_out) {
+  return fill_or_read(c, false, req_id, layer, first_token, n_tokens, k_out, v_out);
+}
+
+// Bookkeeping of one appended token; returns the kernel item.
+static int append_item(orbit_ctx *c, int r, int layer, AppendItem &item) {
+  HostState &hs = c->hs;
+  LayerKV &lk = hs.reqs[r].layers[layer];
+  const int64_t pi = lk.len / hs.sh.P;
+  if (pi >= hs.reqs[r].reserved)
+    return set_err(c, ORBIT_E_STATE, "decode window used up: the request needs a block the plan did not reserve");
+  item.tok = lk.len;
+  if (lk.tier == 1) {
+    item.page = lk.pages[pi];
+    item.host_page = 0;
+  } else {
+    LiveBlock *lb = find_live(c, layer);
+    item.page = (lb && !lb->consumed) ? (int32_t)(lk.stage_page0 + pi) : -1;  // live staging copy gets the token too
+    item.host_page = c->host_only ? 1 : (uint64_t)(uintptr_t)(c->host_dev + (lk.host_page0 + pi) * hs.sh.page_bytes);
+  }
+  lk.len += 1;
+  hs.h_len[(size_t)r * hs.sh.L + layer] = lk.len;
+  return ORBIT_OK;
+}
+
+int orbit_kv_append(orbit_ctx *c, int64_t req_id, int32_t layer, const void *k, const void *v) {
+  int rc = check_layer(c, layer);
+  if (rc) return rc;
+  if (!k || !v) return set_err(c, ORBIT_E_INVAL, "null argument");
+  const int r = c->hs.find(req_id);
+  if (r < 0) return set_err(c, ORBIT_E_NOT_FOUND, "unknown request id");
+  AppendParams ap{};
+  if ((rc = append_item(c, r, layer, ap.items[0]))) return rc;
+  if (c->hs.reqs[r].layers[layer].tier == 0) c->host_dirty[layer] = 1;
+  if (c->host_only) return ORBIT_OK;
+  const Shape &sh = c->hs.sh;
+  ap.arena = c->arena;
+  ap.lens = c->d_len;
+  ap.k = (const uint16_t *)k;
+  ap.v = (const uint16_t *)v;
+  ap.page_bytes = sh.page_bytes;
+  ap.L = sh.L;
+  ap.layer = layer;
+  ap.Hkv = sh.Hkv;
+  ap.n = 1;
+  ap.r0 = r;
+  HIPCHECK(c, launch_append(ap, c->cs));
+  return ORBIT_OK;
+}
+
+int orbit_kv_prefetch(orbit_ctx *c, int32_t layer) {
+  int rc = check_layer(c, layer);
+  if (rc) return rc;
+  rc = prefetch_impl(c, layer);
+  if (rc == 1) return set_err(c, ORBIT_E_STATE, "staging range still needed by a prefetched layer not yet attended");
+  return rc;
+}
+
+int orbit_decode_attention(orbit_ctx *c, int32_t layer, const void *q, void *out, float *out_f32) {
+  int rc = check_layer(c, layer);
+  if (rc) return rc;
+  if (c->hs.reqs.empty()) return set_err(c, ORBIT_E_STATE, "the plan has no request");
+  if (!c->host_only && (!q || !out)) return set_err(c, ORBIT_E_INVAL, "null argument");
+  c->timing = false;
+  return attention_impl(c, layer, q, out, out_f32, false);
+}
+
+int orbit_step(orbit_ctx *c, const void *q, const void *k_new, const void *v_new, void *out, orbit_step_stats *stats) {
+  if (!c) return ORBIT_E_INVAL;
+  HostState &hs = c->hs;
+  if (!hs.has_plan || hs.reqs.empty()) return set_err(c, ORBIT_E_STATE, "no plan (or an empty one) installed");
+  if (!c->host_only && (!q || !k_new || !v_new || !out)) return set_err(c, ORBIT_E_INVAL, "null argument");
+  const Shape &sh = hs.sh;
+  const int nreq = (int)hs.reqs.size();
+  for (int r = 0; r < nreq; ++r)
+    for (int l = 0; l < sh.L; ++l)
+      if (hs.reqs[r].layers[l].len / sh.P >= hs.reqs[r].reserved)
+        return set_err(c, ORBIT_E_STATE, "decode window used up: load a new plan before this step");
+  for (auto &lb : hs.live)
+    if (!lb.consumed) return set_err(c, ORBIT_E_STATE, "a prefetched layer was never attended; finish it before orbit_step");
+  c->timing = stats != nullptr && !c->host_only;
+  std::fill(c->copy_timed.begin(), c->copy_timed.end(), 0);
+  std::fill(c->copy_bytes.begin(), c->copy_bytes.end(), 0);
+
+  size_t next_pf = 0;
+  auto pump = [&]() -> int {
+    while (next_pf < hs.blocks.size()) {
+      int rc = prefetch_impl(c, hs.blocks[next_pf].layer);
+      if (rc == 1) break;
+      if (rc) return rc;
+      ++next_pf;
+    }
+    return ORBIT_OK;
+  };
+  int rc = pump();
+  if (rc) return rc;
+  if (c->timing) HIPCHECK(c, hipEventRecord(c->t_step0, c->cs));
+  int64_t hbm_bytes = 0;
+  const int64_t tok_bytes = sh.page_bytes / sh.P;
+  const int64_t q_stride = (int64_t)nreq * sh.Hq * sh.D, kv_stride = (int64_t)nreq * sh.Hkv * sh.D;
+  for (int l = 0; l < sh.L; ++l) {
+    const int b = hs.block_of_layer[l];
+    if (b >= 0) {
+      LiveBlock *lb = find_live(c, l);
+      if (!lb || lb->consumed) {
+        if ((rc = pump())) return rc;
+        lb = find_live(c, l);
+        if (!lb || lb->consumed) return set_err(c, ORBIT_E_STATE, "internal: staging schedule cannot make progress");
+      }
+      if (!c->host_only) {
+        if (c->timing) HIPCHECK(c, hipEventRecord(c->t_wait0[l], c->cs));
+        HIPCHECK(c, hipStreamWaitEvent(c->cs, c->ev_ready[l], 0));
+        if (c->timing) HIPCHECK(c, hipEventRecord(c->t_wait1[l], c->cs));
+      }
+    }
+    // a3: append this layer's new token of every request (the staging copy is live: it gets the token too)
+    for (int r0 = 0; r0 < nreq; r0 += kAppendBatch) {
+      AppendParams ap{};
+      const int n = std::min(kAppendBatch, nreq - r0);
+      for (int i = 0; i < n; ++i)
+        if ((rc = append_item(c, r0 + i, l, ap.items[i]))) return rc;
+      if (c->host_only) continue;
+      ap.arena = c->arena;
+      ap.lens = c->d_len;
+      ap.k = (const uint16_t *)k_new + l * kv_stride + (int64_t)r0 * sh.Hkv * sh.D;
+      ap.v = (const uint16_t *)v_new + l * kv_stride + (int64_t)r0 * sh.Hkv * sh.D;
+      ap.page_bytes = sh.page_bytes;
+      ap.L = sh.L;
+      ap.layer = l;
+      ap.Hkv = sh.Hkv;
+      ap.n = n;
+      ap.r0 = r0;
+      HIPCHECK(c, launch_append(ap, c->cs));
+    }
+    for (int r = 0; r < nreq; ++r)
+      if (hs.reqs[r].layers[l].tier == 1) hbm_bytes += (int64_t)hs.reqs[r].layers[l].len * tok_bytes;
+    if (b >= 0) find_live(c, l)->consumed = true;
+    rc = attention_impl(c, l, (const uint16_t *)q + l * q_stride, (uint16_t *)out + l * q_stride, nullptr, true);
+    if (rc) return rc;
+    if (b >= 0 && (rc = pump())) return rc;
+  }
+  if (stats) {
+    std::memset(stats, 0, sizeof(*stats));
+    stats->hbm_kv_bytes = hbm_bytes;
+    stats->hbm_blocks_budget = hs.info.budget_blocks;
+    stats->hbm_blocks_reserved = hs.info.resident_blocks + hs.info.staging_blocks;
+    for (int l = 0; l < sh.L; ++l) {
+      stats->link_bytes[l] = c->copy_bytes[l];
+      stats->link_kv_bytes += c->copy_bytes[l];
+    }
+    if (c->timing) {
+      HIPCHECK(c, hipEventRecord(c->t_step1, c->cs));
+      HIPCHECK(c, hipEventSynchronize(c->t_step1));
+      HIPCHECK(c, hipStreamSynchronize(c->xs));
+      HIPCHECK(c, hipEventElapsedTime(&stats->step_ms, c->t_step0, c->t_step1));
+      for (int l = 0; l < sh.L; ++l) {
+        HIPCHECK(c, hipEventElapsedTime(&stats->attn_ms[l], c->t_attn0[l], c->t_attn1[l]));
+        HIPCHECK(c, hipEventElapsedTime(&stats->combine_ms[l], c->t_attn1[l], c->t_comb1[l]));
+        stats->attn_ms_total += stats->attn_ms[l];
+        if (hs.block_of_layer[l] >= 0) {
+          HIPCHECK(c, hipEventElapsedTime(&stats->stall_ms[l], c->t_wait0[l], c->t_wait1[l]));
+          stats->stall_ms_total += stats->stall_ms[l];
+          if (c->copy_timed[l]) {
+            HIPCHECK(c, hipEventElapsedTime(&stats->copy_ms[l], c->t_copy0[l], c->t_copy1[l]));
+            stats->copy_ms_total += stats->copy_ms[l];
+          }
+        }
+      }
+    }
+  }
+  c->timing = false;
+  return ORBIT_OK;
+}
+
+int64_t orbit_get_pages(orbit_ctx *c, int64_t req_id, int32_t layer, int32_t *tier, int64_t *host_first_page,
+                        int32_t *length, int32_t *pages_out, int64_t cap) {
+  int rc = check_layer(c, layer);
+  if (rc) return rc;
+  const int r = c->hs.find(req_id);
+  if (r < 0) return set_err(c, ORBIT_E_NOT_FOUND, "unknown request id");
+  const LayerKV &lk = c->hs.reqs[r].layers[layer];
+  if (tier) *tier = lk.tier;
+  if (host_first_page) *host_first_page = lk.tier == 0 ? lk.host_page0 : -1;
+  if (length) *length = lk.len;
+  const int64_t n = c->hs.reqs[r].reserved;
+  const int32_t *row = c->hs.table_row(r, layer);
+  if (pages_out)
+    for (int64_t i = 0; i < n && i < cap; ++i) pages_out[i] = row[i];
+  return n;
+}
+
+int64_t orbit_get_work_items(orbit_ctx *c, int32_t layer, int32_t *items_out, int64_t cap) {
+  int rc = check_layer(c, layer);
+  if (rc) return rc;
+  std::vector<int32_t> items;
+  rc = c->hs.build_work_items(layer, items);
+  if (rc) return set_err(c, rc, c->hs.err);
+  const int64_t n = (int64_t)items.size() / 4;
+  if (items_out)
+    for (int64_t i = 0; i < n * 4 && i < cap * 4; ++i) items_out[i] = items[i];
+  return n;
+}
+
+int64_t orbit_get_copy_schedule(orbit_ctx *c, int32_t *rows_out, int64_t cap) {
+  if (!c) return ORBIT_E_INVAL;
+  if (!c->hs.has_plan) return set_err(c, ORBIT_E_STATE, "no plan installed");
+  int64_t n = 0;
+  for (const StageBlock &b : c->hs.blocks)
+    for (const CopyItem &ci : b.copies) {
+      if (rows_out && n < cap) {
+        int32_t *row = rows_out + n * 5;
+        row[0] = ci.layer;
+        row[1] = ci.req;
+        row[2] = ci.stage_page0;
+        row[3] = ci.reserved;
+        row[4] = b.p0 - (int32_t)c->hs.info.staging_first_page;
+      }
+      ++n;
+    }
+  return n;
+}
+
+}  // extern "C"

@@ -1,0 +1,465 @@
+// Host-side state of liborbit: block tables, allocators, Eq. (1), the staging-region schedule
+// and the split-K work list.  Pure integer logic, no HIP calls: it is also what runs under
+// ORBIT_FLAG_HOST_ONLY.
+//
+// Paper anchors: block counts b_r and the 16-token growth rule (Section 2.3); placement matrix
+// x[r,l], Eq. (1) and the prefetch buffer B_buf (Section 3.3.1, "GPU Capacity Bound"); delta
+// migration and the contiguous staging range (Section 3.2, "KV Manager"); one arena indexed by
+// a (request x layer) table (Section 4).
+#pragma once
+
+#include <algorithm>
+#include <cstdint>
+#include <map>
+#include <string>
+#include <unordered_map>
+#include <utility>
+#include <vector>
+
+#include "../../include/orbit.h"
+
+namespace orbit {
+
+struct Shape {
+  int L = 0, Hq = 0, Hkv = 0, D = 0, P = 0, G = 0;
+  int max_req = 0;
+  int64_t max_tokens = 0;
+  int64_t page_bytes = 0;
+  int cap_pages = 0;    // page-table row length (even)
+  int chunk_tokens = 0; // split-K chunk
+  int max_chunks = 0;   // per request
+  int window = 0;       // decode window (tokens)
+  int slots = 1;        // staging region = slots * B_buf
+};
+
+enum PageOpKind { OP_HBM_TO_HOST = 0, OP_HOST_TO_HBM = 1, OP_HBM_TO_HBM = 2, OP_HOST_TO_HOST = 3 };
+struct PageOp {
+  int kind;
+  int64_t src, dst;  // page index in the HBM arena or in the host arena, by kind
+};
+
+struct LayerKV {
+  uint8_t tier = 1;            // 1 = HBM, 0 = host
+  int32_t len = 0;             // tokens stored
+  std::vector<int32_t> pages;  // arena page ids (tier 1), `reserved` of them
+  int64_t host_page0 = -1;     // first page of the host run (tier 0)
+  int32_t host_cap = 0;        // pages in the host run
+  int32_t stage_page0 = -1;    // first staging page (tier 0)
+};
+
+struct Req {
+  int64_t id = 0;
+  int32_t reserved = 0;  // blocks per layer under the current plan: ceil((ctx_len + window) / P)
+  std::vector<LayerKV> layers;
+};
+
+// Lowest-free-page allocator over the HBM arena.
+struct HbmAlloc {
+  std::vector<uint8_t> used;
+  int64_t cursor = 0;
+  int32_t alloc_below(int64_t limit) {
+    if (limit > (int64_t)used.size()) limit = (int64_t)used.size();
+    while (cursor < limit && used[cursor]) ++cursor;
+    if (cursor >= limit) return -1;
+    used[cursor] = 1;
+    return (int32_t)cursor++;
+  }
+  void release(int64_t p) {
+    used[p] = 0;
+    if (p < cursor) cursor = p;
+  }
+};
+
+// First-fit allocator of contiguous page runs in the pinned host arena.
+struct RunAlloc {
+  std::map<int64_t, int64_t> free_;  // start -> length
+  void reset(int64_t n) {
+    free_.clear();
+    if (n > 0) free_[0] = n;
+  }
+  int64_t alloc(int64_t n) {
+    if (n <= 0) return 0;
+    for (auto it = free_.begin(); it != free_.end(); ++it) {
+      if (it->second >= n) {
+        int64_t s = it->first, len = it->second;
+        free_.erase(it);
+        if (len > n) free_[s + n] = len - n;
+        return s;
+      }
+    }
+    return -1;
+  }
+  void release(int64_t s, int64_t n) {
+    if (n <= 0) return;
+    auto nx = free_.lower_bound(s);
+    if (nx != free_.end() && s + n == nx->first) {
+      n += nx->second;
+      nx = free_.erase(nx);
+    }
+    if (nx != free_.begin()) {
+      auto pv = std::prev(nx);
+      if (pv->first + pv->second == s) {
+        pv->second += n;
+        return;
+      }
+    }
+    free_[s] = n;
+  }
+  int64_t total_free() const {
+    int64_t t = 0;
+    for (auto &kv : free_) t += kv.second;
+    return t;
+  }
+};
+
+struct CopyItem {
+  int layer, req;
+  int32_t stage_page0, reserved;
+};
+struct StageBlock {
+  int layer;
+  int32_t p0, n;  // absolute arena page range [p0, p0+n)
+  std::vector<CopyItem> copies;
+};
+struct LiveBlock {
+  int layer;
+  int32_t p0, p1;
+  bool consumed;
+};
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Eq. (1) pieces for a placement.  x is row-major [n_req][L] of 0/1.
+struct Eq1 {
+  int64_t resident = 0, buffer = 0, host = 0;
+};
+inline Eq1 eq1_eval(int n_req, int L, const std::vector<int64_t> &b, const std::vector<uint8_t> &x) {
+  Eq1 e;
+  for (int l = 0; l < L; ++l) {
+    int64_t off = 0;
+    for (int r = 0; r < n_req; ++r) {
+      if (x[(size_t)r * L + l]) e.resident += b[r];
+      else off += b[r];
+    }
+    e.host += off;
+    e.buffer = std::max(e.buffer, off);
+  }
+  return e;
+}
+
+inline bool bitmap_get(const uint8_t *bm, int L, int r, int l) {
+  return (bm[(size_t)r * ((L + 7) / 8) + l / 8] >> (l % 8)) & 1;
+}
+
+class HostState {
+ public:
+  Shape sh;
+  int64_t arena_pages = 0, host_pages = 0;
+  std::vector<Req> reqs;  // plan order
+  HbmAlloc hbm;
+  RunAlloc host;
+  bool has_plan = false;
+  orbit_plan_info info{};
+
+  std::vector<StageBlock> blocks;   // one per layer that has offloaded requests, in layer order
+  std::vector<int> block_of_layer;  // index into blocks or -1
+  std::vector<LiveBlock> live;      // staging ranges currently holding (or receiving) a layer
+
+  // host mirrors of the device tables
+  std::vector<int32_t> h_table;  // [max_req][L][cap_pages]
+  std::vector<int32_t> h_len;    // [max_req][L]
+
+  std::string err;
+
+  void init(const Shape &s, int64_t arena_pages_, int64_t host_pages_) {
+    sh = s;
+    arena_pages = arena_pages_;
+    host_pages = host_pages_;
+    hbm.used.assign((size_t)arena_pages, 0);
+    hbm.cursor = 0;
+    host.reset(host_pages);
+    h_table.assign((size_t)sh.max_req * sh.L * sh.cap_pages, 0);
+    h_len.assign((size_t)sh.max_req * sh.L, 0);
+    block_of_layer.assign(sh.L, -1);
+  }
+
+  int find(int64_t id) const {
+    for (size_t i = 0; i < reqs.size(); ++i)
+      if (reqs[i].id == id) return (int)i;
+    return -1;
+  }
+  int32_t *table_row(int r, int l) { return &h_table[((size_t)r * sh.L + l) * sh.cap_pages]; }
+
+  // ------------------------------------------------------------------------------ plan load
+  // On success fills `phases` with the page copies to run, in order (one blit per phase), and
+  // commits the new state.  On failure nothing is changed.
+  int plan_load(int32_t n_req, const int64_t *ids, const int32_t *ctx_len, const uint8_t *bitmap,
+                int64_t budget_bytes, std::vector<std::vector<PageOp>> &phases) {
+    phases.clear();
+    if (n_req < 0 || n_req > sh.max_req) return fail(ORBIT_E_INVAL, "n_req out of range");
+    if (n_req > 0 && (!ids || !ctx_len || !bitmap)) return fail(ORBIT_E_INVAL, "null argument");
+    if (budget_bytes < 0) return fail(ORBIT_E_INVAL, "negative budget");
+    const int L = sh.L, P = sh.P;
+    std::vector<int64_t> rb(n_req);
+    std::vector<uint8_t> x((size_t)n_req * L);
+    std::unordered_map<int64_t, int> seen;
+    for (int r = 0; r < n_req; ++r) {
+      if (!seen.emplace(ids[r], r).second) return fail(ORBIT_E_INVAL, "duplicate request id");
+      if (ctx_len[r] < 0 || (int64_t)ctx_len[r] + sh.window > sh.max_tokens)
+        return fail(ORBIT_E_INVAL, "ctx_len (+ decode window) exceeds max_tokens_per_request");
+      rb[r] = ceil_div((int64_t)ctx_len[r] + sh.window, P);
+      for (int l = 0; l < L; ++l) x[(size_t)r * L + l] = bitmap_get(bitmap, L, r, l);
+      int o = find(ids[r]);
+      if (o >= 0)
+        for (int l = 0; l < L; ++l)
+          if (reqs[o].layers[l].len != ctx_len[r])
+            return fail(ORBIT_E_STATE, "ctx_len differs from the stored length of a known request");
+    }
+    // Eq. (1)
+    Eq1 e = eq1_eval(n_req, L, rb, x);
+    const int64_t staging = (int64_t)sh.slots * e.buffer;
+    const int64_t b_gpu = std::min<int64_t>(budget_bytes / sh.page_bytes, arena_pages);
+    if (e.resident + staging > b_gpu)
+      return fail(ORBIT_E_CAPACITY, "Eq.(1) violated: resident " + std::to_string(e.resident) + " + staging " +
+                                        std::to_string(staging) + " blocks > budget " + std::to_string(b_gpu));
+    if (e.host > host_pages) return fail(ORBIT_E_HOST_CAPACITY, "host arena smaller than the offloaded blocks");
+    const int64_t ring_first = b_gpu - staging;
+
+    // work on copies; commit at the end
+    HbmAlloc A = hbm;
+    RunAlloc H = host;
+    std::vector<Req> old = reqs;
+    std::vector<Req> nw(n_req);
+    std::vector<int> old_of(n_req, -1);
+    std::vector<uint8_t> kept(old.size(), 0);
+    int64_t to_host = 0, to_hbm = 0, reloc = 0;
+
+    for (int r = 0; r < n_req; ++r) {
+      int o = find(ids[r]);
+      old_of[r] = o;
+      if (o >= 0) kept[o] = 1;
+    }
+    // (a) dropped requests: nothing to preserve
+    for (size_t o = 0; o < old.size(); ++o) {
+      if (kept[o]) continue;
+      for (auto &lk : old[o].layers) {
+        for (int32_t p : lk.pages) A.release(p);
+        if (lk.tier == 0) H.release(lk.host_page0, lk.host_cap);
+      }
+    }
+    for (int r = 0; r < n_req; ++r) {
+      if (old_of[r] >= 0) nw[r] = std::move(old[old_of[r]]);
+      else {
+        nw[r].id = ids[r];
+        nw[r].layers.assign(L, LayerKV());
+        for (auto &lk : nw[r].layers) { lk.len = ctx_len[r]; lk.tier = 2; /* unallocated */ }
+      }
+      nw[r].reserved = (int32_t)rb[r];
+    }
+    std::vector<int64_t> free_hbm;
+    std::vector<std::pair<int64_t, int64_t>> free_host;
+    auto end_phase = [&]() {
+      for (int64_t p : free_hbm) A.release(p);
+      for (auto &pr : free_host) H.release(pr.first, pr.second);
+      free_hbm.clear();
+      free_host.clear();
+    };
+    // (b) demotions HBM -> host
+    phases.emplace_back();
+    for (int r = 0; r < n_req; ++r)
+      for (int l = 0; l < L; ++l) {
+        LayerKV &lk = nw[r].layers[l];
+        if (lk.tier != 1 || x[(size_t)r * L + l]) continue;
+        int64_t run = H.alloc(rb[r]);
+        if (run < 0) return fail(ORBIT_E_HOST_CAPACITY, "host arena full or fragmented (demotion)");
+        int64_t used = ceil_div(lk.len, P);
+        for (int64_t i = 0; i < used; ++i) phases.back().push_back({OP_HBM_TO_HOST, lk.pages[i], run + i});
+        to_host += used;
+        for (int32_t p : lk.pages) free_hbm.push_back(p);
+        lk.pages.clear();
+        lk.tier = 0;
+        lk.host_page0 = run;
+        lk.host_cap = (int32_t)rb[r];
+      }
+    end_phase();
+    // (c) host runs that must grow
+    phases.emplace_back();
+    for (int r = 0; r < n_req; ++r)
+      for (int l = 0; l < L; ++l) {
+        LayerKV &lk = nw[r].layers[l];
+        if (lk.tier != 0 || x[(size_t)r * L + l] || lk.host_cap >= rb[r]) continue;
+        int64_t run = H.alloc(rb[r]);
+        if (run < 0) return fail(ORBIT_E_HOST_CAPACITY, "host arena full or fragmented (growth)");
+        int64_t used = ceil_div(lk.len, P);
+        for (int64_t i = 0; i < used; ++i) phases.back().push_back({OP_HOST_TO_HOST, lk.host_page0 + i, run + i});
+        free_host.push_back({lk.host_page0, lk.host_cap});
+        lk.host_page0 = run;
+        lk.host_cap = (int32_t)rb[r];
+      }
+    end_phase();
+    // (d) resident blocks sitting at or above the new staging region move below it
+    phases.emplace_back();
+    for (int r = 0; r < n_req; ++r)
+      for (int l = 0; l < L; ++l) {
+        LayerKV &lk = nw[r].layers[l];
+        if (lk.tier != 1 || !x[(size_t)r * L + l]) continue;
+        int64_t used = ceil_div(lk.len, P);
+        for (size_t i = 0; i < lk.pages.size(); ++i) {
+          if (lk.pages[i] < ring_first) continue;
+          int32_t np = A.alloc_below(ring_first);
+          if (np < 0) return fail(ORBIT_E_CAPACITY, "internal: no page below the staging region");
+          if ((int64_t)i < used) {
+            phases.back().push_back({OP_HBM_TO_HBM, lk.pages[i], np});
+            ++reloc;
+          }
+          free_hbm.push_back(lk.pages[i]);
+          lk.pages[i] = np;
+        }
+      }
+    end_phase();
+    // (e) growth of resident lists, promotions host -> HBM, new resident requests
+    phases.emplace_back();
+    for (int r = 0; r < n_req; ++r)
+      for (int l = 0; l < L; ++l) {
+        LayerKV &lk = nw[r].layers[l];
+        if (!x[(size_t)r * L + l]) continue;
+        int64_t used = ceil_div(lk.len, P);
+        bool promote = (lk.tier == 0);
+        if (lk.tier != 1) lk.pages.clear();
+        while ((int64_t)lk.pages.size() < rb[r]) {
+          int32_t np = A.alloc_below(ring_first);
+          if (np < 0) return fail(ORBIT_E_CAPACITY, "internal: resident allocation failed");
+          lk.pages.push_back(np);
+        }
+        if (promote) {
+          for (int64_t i = 0; i < used; ++i) phases.back().push_back({OP_HOST_TO_HBM, lk.host_page0 + i, lk.pages[i]});
+          to_hbm += used;
+          free_host.push_back({lk.host_page0, lk.host_cap});
+          lk.host_page0 = -1;
+          lk.host_cap = 0;
+        }
+        lk.tier = 1;
+        lk.stage_page0 = -1;
+      }
+    end_phase();
+    // (f) new offloaded requests
+    for (int r = 0; r < n_req; ++r)
+      for (int l = 0; l < L; ++l) {
+        LayerKV &lk = nw[r].layers[l];
+        if (lk.tier != 2) continue;
+        int64_t run = H.alloc(rb[r]);
+        if (run < 0) return fail(ORBIT_E_HOST_CAPACITY, "host arena full or fragmented (new request)");
+        lk.tier = 0;
+        lk.host_page0 = run;
+        lk.host_cap = (int32_t)rb[r];
+      }
+
+    // staging schedule: each layer's offloaded requests occupy one contiguous range; ranges are
+    // laid out round-robin over the staging region; inside a range, smallest request first.
+    std::vector<StageBlock> nb;
+    std::vector<int> bol(L, -1);
+    int64_t cursor = 0;
+    for (int l = 0; l < L; ++l) {
+      std::vector<int> off;
+      int64_t n = 0;
+      for (int r = 0; r < n_req; ++r)
+        if (!x[(size_t)r * L + l]) { off.push_back(r); n += rb[r]; }
+      if (off.empty()) continue;
+      std::stable_sort(off.begin(), off.end(), [&](int a, int b) { return rb[a] < rb[b]; });
+      if (cursor + n > staging) cursor = 0;
+      StageBlock sb;
+      sb.layer = l;
+      sb.p0 = (int32_t)(ring_first + cursor);
+      sb.n = (int32_t)n;
+      int64_t at = sb.p0;
+      for (int r : off) {
+        sb.copies.push_back({l, r, (int32_t)at, (int32_t)rb[r]});
+        nw[r].layers[l].stage_page0 = (int32_t)at;
+        at += rb[r];
+      }
+      cursor += n;
+      bol[l] = (int)nb.size();
+      nb.push_back(std::move(sb));
+    }
+
+    // commit
+    hbm = std::move(A);
+    host = std::move(H);
+    reqs = std::move(nw);
+    blocks = std::move(nb);
+    block_of_layer = std::move(bol);
+    live.clear();
+    has_plan = true;
+    info.page_bytes = sh.page_bytes;
+    info.budget_blocks = b_gpu;
+    info.resident_blocks = e.resident;
+    info.buffer_blocks = e.buffer;
+    info.staging_first_page = ring_first;
+    info.staging_blocks = staging;
+    info.host_blocks = e.host;
+    info.moved_to_host_blocks = to_host;
+    info.moved_to_hbm_blocks = to_hbm;
+    info.relocated_blocks = reloc;
+    info.n_requests = n_req;
+    info.chunk_tokens = sh.chunk_tokens;
+    rebuild_tables();
+    return ORBIT_OK;
+  }
+
+  void rebuild_tables() {
+    std::fill(h_len.begin(), h_len.end(), 0);
+    for (size_t r = 0; r < reqs.size(); ++r)
+      for (int l = 0; l < sh.L; ++l) {
+        const LayerKV &lk = reqs[r].layers[l];
+        int32_t *row = table_row((int)r, l);
+        for (int i = 0; i < sh.cap_pages; ++i) row[i] = 0;
+        if (lk.tier == 1)
+          for (size_t i = 0; i < lk.pages.size(); ++i) row[i] = lk.pages[i];
+        else
+          for (int i = 0; i < reqs[r].reserved; ++i) row[i] = lk.stage_page0 + i;
+        h_len[r * sh.L + l] = lk.len;
+      }
+  }
+
+  // ------------------------------------------------------------------------------ work list
+  // Items {request index, kv head, chunk, partial slot}: chunks are a function of the stored
+  // length and the fixed chunk size only, so results do not depend on the placement.  Order:
+  // full chunks of all requests first, ragged last chunks at the end; the 8 groups x Hkv heads
+  // of a 64-item span are interleaved so that the heads of one page range run on one XCD
+  // (workgroup i runs on XCD i mod 8).
+  int build_work_items(int layer, std::vector<int32_t> &items) {
+    items.clear();
+    std::vector<std::pair<int, int>> full, ragged;  // (request, chunk)
+    for (size_t r = 0; r < reqs.size(); ++r) {
+      int64_t n = reqs[r].layers[layer].len;
+      if (n < 1) return fail(ORBIT_E_INVAL, "a request holds no token in this layer");
+      int nc = (int)ceil_div(n, sh.chunk_tokens);
+      for (int c = 0; c < nc; ++c) {
+        bool is_full = (int64_t)(c + 1) * sh.chunk_tokens <= n;
+        (is_full ? full : ragged).push_back({(int)r, c});
+      }
+    }
+    full.insert(full.end(), ragged.begin(), ragged.end());
+    const int H = sh.Hkv;
+    const size_t ngroups = full.size();
+    for (size_t base = 0; base < ngroups; base += 8) {
+      size_t cnt = std::min<size_t>(8, ngroups - base);
+      for (int g = 0; g < H; ++g)
+        for (size_t k = 0; k < cnt; ++k) {
+          int r = full[base + k].first, c = full[base + k].second;
+          items.push_back(r);
+          items.push_back(g);
+          items.push_back(c);
+          items.push_back((r * sh.max_chunks + c) * H + g);
+        }
+    }
+    return ORBIT_OK;
+  }
+
+  int fail(int code, const std::string &msg) {
+    err = msg;
+    return code;
+  }
+};
+
+}  // namespace orbit

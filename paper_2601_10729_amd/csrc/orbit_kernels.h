@@ -1,0 +1,74 @@
+// Launch wrappers of the gfx950 kernels (defined in orbit_kernels.hip).  Plain C++; every
+// function only enqueues work on the given stream and returns the HIP status.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace orbit {
+
+constexpr int kAppendBatch = 64;  // requests per append launch (items travel as kernel arguments)
+
+struct AttnParams {
+  const uint8_t *arena;     // device, page 0 of the HBM arena
+  const int32_t *table;     // device [max_req][L][cap_pages] page ids
+  const int32_t *lens;      // device [max_req][L] stored tokens
+  const int32_t *items;     // device [n_items][4] {request, kv head, chunk, partial slot}
+  const uint16_t *q;        // device [n_req][Hq][128] bf16
+  float *pacc;              // device [slots][G][128] un-normalised partial outputs
+  float *pml;               // device [slots][2][16] partial (max, sum) in log2 units
+  int64_t page_bytes;
+  int32_t L, layer, cap_pages, Hq, Hkv, G, chunk_tokens, n_items;
+  float scale_log2;         // softmax scale * log2(e)
+  int32_t variant;          // kernel build to launch (tuning knob)
+};
+
+struct CombineParams {
+  const float *pacc;
+  const float *pml;
+  const int32_t *lens;
+  uint16_t *out;            // device [n_req][Hq][128] bf16
+  float *out_f32;           // optional
+  int32_t L, layer, Hq, Hkv, G, chunk_tokens, max_chunks, n_req;
+};
+
+struct AppendItem {
+  int32_t tok;              // position the new token takes (= length before the append)
+  int32_t page;             // arena page id to write (resident page or live staging page), or -1
+  uint64_t host_page;       // device-visible address of the host page to write, or 0
+};
+
+struct AppendParams {
+  uint8_t *arena;
+  int32_t *lens;
+  const uint16_t *k;        // device [.. n][Hkv][128] bf16, row i belongs to request r0 + i
+  const uint16_t *v;
+  int64_t page_bytes;
+  int32_t L, layer, Hkv, n, r0;
+  AppendItem items[kAppendBatch];
+};
+
+struct FillParams {
+  uint8_t *arena;           // HBM arena (resident destination) ...
+  const int32_t *row;       // ... through this device page-table row, or
+  uint8_t *host_run;        // device-visible address of the host run's first page (row == NULL)
+  uint16_t *k;              // token-major [n_tokens][Hkv][128] bf16 (source of fill, dest of read)
+  uint16_t *v;
+  int32_t *len_slot;        // device address of lens[r][l] (fill only; may be NULL)
+  int64_t page_bytes, first_token, n_tokens;
+  int32_t Hkv, new_len;
+};
+
+struct BlitOp {
+  uint64_t src, dst;        // device-visible addresses of one page each
+};
+
+hipError_t launch_attention(const AttnParams &p, hipStream_t s);
+hipError_t launch_combine(const CombineParams &p, hipStream_t s);
+hipError_t launch_append(const AppendParams &p, hipStream_t s);
+hipError_t launch_fill(const FillParams &p, hipStream_t s);
+hipError_t launch_gather(const FillParams &p, hipStream_t s);
+hipError_t launch_blit(const BlitOp *ops_dev, int64_t n_ops, int64_t page_bytes, hipStream_t s);
+hipError_t launch_set_i32(int32_t *dst, int32_t value, hipStream_t s);
+
+}  // namespace orbit

@@ -1,0 +1,475 @@
+// gfx950 (CDNA4, MI355X) kernels of liborbit.
+//
+//  attention : split-K GQA decode attention over paged K/V, one workgroup (4 wavefronts of 64)
+//              per (request, kv head, chunk).  The in-page tile order is chosen so that every
+//              16-byte per-lane global load lands directly in MFMA operand order:
+//                 S^T[tok][head] = K[tok][dim] . Q^T[dim][head]      v_mfma_f32_16x16x32_bf16
+//                 O^T[dim][head] = V^T[dim][tok] . P^T[tok][head]    v_mfma_f32_16x16x32_bf16
+//              The query-head group (G <= 16) is the N dimension, padded with zero columns.
+//              Online softmax in base 2, fp32, reduced across lanes with wavefront shuffles; the
+//              four wavefronts of a workgroup are merged through LDS in a fixed order.
+//  combine   : merges the chunks of a (request, query head) in fixed order and normalises.
+//  append    : scatters one new token per request into its page (HBM and/or mapped host page).
+//  fill/gather/blit : bulk token-major <-> page conversion and whole-page copies.
+//
+// Decode attention itself is only described in prose by the paper (Section 2.1); the block
+// size of 16 tokens is Section 2.3, the single arena addressed by a (request x layer) table is
+// Section 4.
+#include "orbit_kernels.h"
+
+namespace orbit {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kD = 128;         // head dim
+constexpr int kP = 16;          // tokens per page
+constexpr int kTileBytes = kP * kD * 2;  // one K or V tile of one head: 4 KiB
+constexpr int kWaves = 4;
+
+struct Tile {  // two pages of one kv head as they sit in registers: 64 VGPRs
+  u32x4_t k0[4], v0[4], k1[4], v1[4];
+};
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ uint32_t bf16_rne_bits(float f) {  // finite, non-NaN inputs only
+  uint32_t u = __builtin_bit_cast(uint32_t, f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __builtin_bit_cast(float, b << 16); }
+
+__device__ __forceinline__ float xor_max(float v, int mask) { return fmaxf(v, __shfl_xor(v, mask, 64)); }
+
+__device__ __forceinline__ void load_page(u32x4_t (&k)[4], u32x4_t (&v)[4], const uint8_t *ktile, const uint8_t *vtile,
+                                          uint32_t lane_off) {
+  // wave-uniform tile addresses + a 32-bit per-lane offset: scalar-base global loads, 1 KiB per instruction
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) k[kk] = *reinterpret_cast<const u32x4_t *>(ktile + (lane_off + kk * 1024u));
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) v[kk] = *reinterpret_cast<const u32x4_t *>(vtile + (lane_off + kk * 1024u));
+}
+
+__device__ __forceinline__ void zero_page(u32x4_t (&k)[4], u32x4_t (&v)[4]) {
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    k[kk] = u32x4_t{0, 0, 0, 0};
+    v[kk] = u32x4_t{0, 0, 0, 0};
+  }
+}
+
+// One 32-token tile: scores, online-softmax update, P.V.  `valid` = tokens of the tile that
+// exist (1..32); MASK = false promises valid == 32.
+template <bool MASK>
+__device__ __forceinline__ void process_tile(Tile &T, const bf16x8_t (&q)[4], f32x4_t (&acc)[8], float &m, float &l,
+                                             float scale_log2, int valid, int j) {
+  f32x4_t s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk)
+    s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, T.k0[kk]), q[kk], s0, 0, 0, 0);
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk)
+    s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, T.k1[kk]), q[kk], s1, 0, 0, 0);
+  // lane (j, n) now holds, for query head n, tokens 4j..4j+3 of page 0 (s0) and of page 1 (s1)
+  float x[8];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    x[i] = s0[i] * scale_log2;
+    x[4 + i] = s1[i] * scale_log2;
+  }
+  if (MASK) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int t = 4 * j + i;
+      if (t >= valid) x[i] = -INFINITY;
+      if (t + kP >= valid) x[4 + i] = -INFINITY;
+    }
+  }
+  float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+  mx = xor_max(mx, 16);
+  mx = xor_max(mx, 32);
+  const float mn = fmaxf(m, mx);  // finite: token 0 of the tile always exists
+  const float alpha = fast_exp2(m - mn);
+  uint32_t pb[8];
+  float psum = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    pb[i] = bf16_rne_bits(fast_exp2(x[i] - mn));
+    psum += bf16_bits_to_f32(pb[i]);  // normaliser uses the rounded weights that multiply V
+  }
+  l = l * alpha + psum;
+  m = mn;
+  u32x4_t pw = {pb[0] | (pb[1] << 16), pb[2] | (pb[3] << 16), pb[4] | (pb[5] << 16), pb[6] | (pb[7] << 16)};
+  const bf16x8_t pB = __builtin_bit_cast(bf16x8_t, pw);
+  if (MASK) {
+    // a slot past the stored length may hold anything (even Inf/NaN bits): clear it so that
+    // weight 0 times garbage cannot poison the accumulator
+    uint32_t mk0[2], mk1[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int t = 4 * j + 2 * h;
+      mk0[h] = (t < valid ? 0x0000FFFFu : 0u) | (t + 1 < valid ? 0xFFFF0000u : 0u);
+      mk1[h] = (t + kP < valid ? 0x0000FFFFu : 0u) | (t + 1 + kP < valid ? 0xFFFF0000u : 0u);
+    }
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      T.v0[kk] = T.v0[kk] & u32x4_t{mk0[0], mk0[1], mk0[0], mk0[1]};
+      T.v1[kk] = T.v1[kk] & u32x4_t{mk1[0], mk1[1], mk1[0], mk1[1]};
+    }
+  }
+#pragma unroll
+  for (int nb = 0; nb < 8; ++nb) {
+    acc[nb] *= alpha;
+    const int e = nb & 1;
+    u32x4_t a = {T.v0[nb >> 1][2 * e], T.v0[nb >> 1][2 * e + 1], T.v1[nb >> 1][2 * e], T.v1[nb >> 1][2 * e + 1]};
+    acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), pB, acc[nb], 0, 0, 0);
+  }
+}
+
+// PREFETCH = true keeps the next tile's loads in flight while the current one is processed
+// (two register tiles, 2 workgroups per CU); false relies on more resident wavefronts instead.
+template <bool PREFETCH, int MIN_BLOCKS>
+__global__ __launch_bounds__(256, MIN_BLOCKS) void attention_kernel(const AttnParams p) {
+  extern __shared__ float smem[];  // [3][G][128] accumulators of waves 1..3, then [4][2][16] (m, l)
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int j = lane >> 4, nn = lane & 15;
+  const uint32_t lane_off = (uint32_t)lane * 16u;
+
+  const int32_t *it = p.items + (int64_t)blockIdx.x * 4;
+  const int r = it[0], g = it[1], c = it[2], pslot = it[3];
+  const int n = p.lens[(int64_t)r * p.L + p.layer];
+  const int tok0 = c * p.chunk_tokens;
+  const int ntok = min(p.chunk_tokens, n - tok0);  // >= 1 by construction of the work list
+  const int ntiles = (ntok + 2 * kP - 1) / (2 * kP);
+  const int32_t *row = p.table + ((int64_t)r * p.L + p.layer) * p.cap_pages + tok0 / kP;
+  const int64_t v_off = (int64_t)p.Hkv * kTileBytes;
+  const uint8_t *head_base = p.arena + (int64_t)g * kTileBytes;
+
+  bf16x8_t q[4];
+  {
+    const uint16_t *qrow = p.q + ((int64_t)r * p.Hq + g * p.G + (nn < p.G ? nn : 0)) * kD;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      u32x4_t w = *reinterpret_cast<const u32x4_t *>(qrow + (4 * kk + j) * 8);
+      if (nn >= p.G) w = u32x4_t{0, 0, 0, 0};
+      q[kk] = __builtin_bit_cast(bf16x8_t, w);
+    }
+  }
+
+  f32x4_t acc[8];
+#pragma unroll
+  for (int nb = 0; nb < 8; ++nb) acc[nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  float m = -INFINITY, l = 0.f;
+
+  auto load_tile = [&](Tile &T, int t) {
+    const int valid = ntok - 2 * kP * t;
+    const int p0 = __builtin_amdgcn_readfirstlane(row[2 * t]);
+    const uint8_t *t0 = head_base + (int64_t)p0 * p.page_bytes;
+    load_page(T.k0, T.v0, t0, t0 + v_off, lane_off);
+    if (valid > kP) {
+      const int p1 = __builtin_amdgcn_readfirstlane(row[2 * t + 1]);
+      const uint8_t *t1 = head_base + (int64_t)p1 * p.page_bytes;
+      load_page(T.k1, T.v1, t1, t1 + v_off, lane_off);
+    } else {
+      zero_page(T.k1, T.v1);
+    }
+  };
+  auto run_tile = [&](Tile &T, int t) {
+    const int valid = ntok - 2 * kP * t;
+    if (valid >= 2 * kP) process_tile<false>(T, q, acc, m, l, p.scale_log2, 2 * kP, j);
+    else process_tile<true>(T, q, acc, m, l, p.scale_log2, valid, j);
+  };
+
+  if (PREFETCH) {
+    Tile A, B;
+    int t = wave;
+    if (t < ntiles) load_tile(A, t);
+    while (t < ntiles) {
+      int tn = t + kWaves;
+      if (tn < ntiles) load_tile(B, tn);
+      run_tile(A, t);
+      t = tn;
+      if (t >= ntiles) break;
+      tn = t + kWaves;
+      if (tn < ntiles) load_tile(A, tn);
+      run_tile(B, t);
+      t = tn;
+    }
+  } else {
+    Tile A;
+    for (int t = wave; t < ntiles; t += kWaves) {
+      load_tile(A, t);
+      run_tile(A, t);
+    }
+  }
+
+  // l holds this lane's share of the normaliser; fold the four token groups of each head
+  l += __shfl_xor(l, 16, 64);
+  l += __shfl_xor(l, 32, 64);
+
+  const int G = p.G;
+  float *sm_acc = smem;                      // [3][G][128]
+  float *sm_ml = smem + 3 * G * kD;          // [4][2][16]
+  if (j == 0) {
+    sm_ml[wave * 32 + nn] = m;
+    sm_ml[wave * 32 + 16 + nn] = l;
+  }
+  if (wave > 0 && nn < G) {
+    float *dst = sm_acc + ((wave - 1) * G + nn) * kD + 4 * j;
+#pragma unroll
+    for (int nb = 0; nb < 8; ++nb) *reinterpret_cast<f32x4_t *>(dst + 16 * nb) = acc[nb];
+  }
+  __syncthreads();
+  if (wave == 0 && nn < G) {
+    float mw[kWaves], lw[kWaves];
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      mw[w] = sm_ml[w * 32 + nn];
+      lw[w] = sm_ml[w * 32 + 16 + nn];
+    }
+    const float M = fmaxf(fmaxf(mw[0], mw[1]), fmaxf(mw[2], mw[3]));  // wave 0 always has a tile
+    float f[kWaves];
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) f[w] = fast_exp2(mw[w] - M);
+    float lt = lw[0] * f[0];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) lt += lw[w] * f[w];
+    float *out = p.pacc + ((int64_t)pslot * G + nn) * kD + 4 * j;
+#pragma unroll
+    for (int nb = 0; nb < 8; ++nb) {
+      f32x4_t o = acc[nb] * f[0];
+#pragma unroll
+      for (int w = 1; w < kWaves; ++w)
+        o += *reinterpret_cast<const f32x4_t *>(sm_acc + ((w - 1) * G + nn) * kD + 4 * j + 16 * nb) * f[w];
+      *reinterpret_cast<f32x4_t *>(out + 16 * nb) = o;
+    }
+    if (j == 0) {
+      p.pml[(int64_t)pslot * 32 + nn] = M;
+      p.pml[(int64_t)pslot * 32 + 16 + nn] = lt;
+    }
+  }
+}
+
+// One workgroup of 4 waves per (request, query head); lane handles dims 2*lane, 2*lane+1; wave w
+// takes chunks w, w+4, ...; the four partial sums are added in wave order.
+__global__ __launch_bounds__(256) void combine_kernel(const CombineParams p) {
+  __shared__ float sm[kWaves][kD + 1];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int r = blockIdx.x / p.Hq, h = blockIdx.x % p.Hq;
+  const int g = h / p.G, nn = h % p.G;
+  const int n = p.lens[(int64_t)r * p.L + p.layer];
+  const int nc = (n + p.chunk_tokens - 1) / p.chunk_tokens;
+  auto slot = [&](int c) { return (int64_t)(r * p.max_chunks + c) * p.Hkv + g; };
+
+  float M = -INFINITY;
+  for (int c = lane; c < nc; c += 64) M = fmaxf(M, p.pml[slot(c) * 32 + nn]);
+#pragma unroll
+  for (int s = 1; s < 64; s <<= 1) M = xor_max(M, s);
+
+  float o0 = 0.f, o1 = 0.f, lsum = 0.f;
+  for (int c = wave; c < nc; c += kWaves) {
+    const int64_t s = slot(c);
+    const float f = fast_exp2(p.pml[s * 32 + nn] - M);
+    lsum += p.pml[s * 32 + 16 + nn] * f;
+    const float2 a = *reinterpret_cast<const float2 *>(p.pacc + (s * p.G + nn) * kD + 2 * lane);
+    o0 += a.x * f;
+    o1 += a.y * f;
+  }
+  sm[wave][2 * lane] = o0;
+  sm[wave][2 * lane + 1] = o1;
+  if (lane == 0) sm[wave][kD] = lsum;
+  __syncthreads();
+  if (wave == 0) {
+    float t0 = sm[0][2 * lane], t1 = sm[0][2 * lane + 1], lt = sm[0][kD];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) {
+      t0 += sm[w][2 * lane];
+      t1 += sm[w][2 * lane + 1];
+      lt += sm[w][kD];
+    }
+    const float inv = 1.0f / lt;
+    t0 *= inv;
+    t1 *= inv;
+    const int64_t o = ((int64_t)r * p.Hq + h) * kD + 2 * lane;
+    *reinterpret_cast<uint32_t *>(p.out + o) = bf16_rne_bits(t0) | (bf16_rne_bits(t1) << 16);
+    if (p.out_f32) *reinterpret_cast<float2 *>(p.out_f32 + o) = float2{t0, t1};
+  }
+}
+
+__device__ __forceinline__ int v_elem_offset(int tok, int dim) {
+  return ((((dim >> 5) * (kP / 4) + (tok >> 2)) * 16 + (dim & 15)) * 2 + ((dim >> 4) & 1)) * 4 + (tok & 3);
+}
+
+__global__ __launch_bounds__(256) void append_kernel(const AppendParams p) {
+  const AppendItem item = p.items[blockIdx.x];
+  const int r = p.r0 + blockIdx.x;
+  const int slot = item.tok % kP;
+  const uint16_t *ksrc = p.k + (int64_t)blockIdx.x * p.Hkv * kD;
+  const uint16_t *vsrc = p.v + (int64_t)blockIdx.x * p.Hkv * kD;
+  uint8_t *dests[2] = {item.page >= 0 ? p.arena + (int64_t)item.page * p.page_bytes : nullptr,
+                       reinterpret_cast<uint8_t *>(item.host_page)};
+  for (int d = 0; d < 2; ++d) {
+    uint8_t *base = dests[d];
+    if (!base) continue;
+    for (int i = threadIdx.x; i < p.Hkv * 16; i += blockDim.x) {
+      const int g = i >> 4, c = i & 15;
+      const u32x4_t w = *reinterpret_cast<const u32x4_t *>(ksrc + g * kD + c * 8);
+      *reinterpret_cast<u32x4_t *>(base + (int64_t)g * kTileBytes + (c * kP + slot) * 16) = w;
+    }
+    uint16_t *vt = reinterpret_cast<uint16_t *>(base + (int64_t)p.Hkv * kTileBytes);
+    for (int i = threadIdx.x; i < p.Hkv * kD; i += blockDim.x) {
+      const int g = i / kD, dim = i % kD;
+      vt[g * (kTileBytes / 2) + v_elem_offset(slot, dim)] = vsrc[i];
+    }
+  }
+  if (threadIdx.x == 0) p.lens[(int64_t)r * p.L + p.layer] = item.tok + 1;
+}
+
+__device__ __forceinline__ uint8_t *fill_page_base(const FillParams &p, int64_t page_index) {
+  return p.row ? p.arena + (int64_t)p.row[page_index] * p.page_bytes : p.host_run + page_index * p.page_bytes;
+}
+
+// grid (pages touched, Hkv); token-major -> page tiles.
+__global__ __launch_bounds__(256) void fill_kernel(const FillParams p) {
+  const int64_t pi = p.first_token / kP + blockIdx.x;
+  const int g = blockIdx.y;
+  uint8_t *base = fill_page_base(p, pi);
+  const int64_t lo = p.first_token, hi = p.first_token + p.n_tokens;
+  const int tid = threadIdx.x;
+  {  // K: thread (c, t) moves one 16-byte chunk
+    const int c = tid >> 4, t = tid & 15;
+    const int64_t tok = pi * kP + t;
+    if (tok >= lo && tok < hi) {
+      const u32x4_t w = *reinterpret_cast<const u32x4_t *>(p.k + ((tok - lo) * p.Hkv + g) * kD + c * 8);
+      *reinterpret_cast<u32x4_t *>(base + (int64_t)g * kTileBytes + (c * kP + t) * 16) = w;
+    }
+  }
+  {  // V: thread owns the 16-byte chunk (nbp, j, m) = 2 dims x 4 tokens
+    const int nbp = tid >> 6, jq = (tid >> 4) & 3, mm = tid & 15;
+    uint16_t *dst = reinterpret_cast<uint16_t *>(base + (int64_t)(p.Hkv + g) * kTileBytes) + tid * 8;
+    const int64_t t0 = pi * kP + 4 * jq;
+    uint16_t w[8];
+    bool all = t0 >= lo && t0 + 3 < hi;
+#pragma unroll
+    for (int e = 0; e < 2; ++e)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int64_t tok = t0 + i;
+        const bool in = tok >= lo && tok < hi;
+        w[e * 4 + i] = in ? p.v[((tok - lo) * p.Hkv + g) * kD + (2 * nbp + e) * 16 + mm] : (uint16_t)0;
+      }
+    if (all) {
+      u32x4_t pk = {w[0] | ((uint32_t)w[1] << 16), w[2] | ((uint32_t)w[3] << 16), w[4] | ((uint32_t)w[5] << 16),
+                    w[6] | ((uint32_t)w[7] << 16)};
+      *reinterpret_cast<u32x4_t *>(dst) = pk;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 2; ++e)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int64_t tok = t0 + i;
+          if (tok >= lo && tok < hi) dst[e * 4 + i] = w[e * 4 + i];
+        }
+    }
+  }
+  if (p.len_slot && blockIdx.x == 0 && g == 0 && tid == 0) *p.len_slot = p.new_len;
+}
+
+// grid (pages touched, Hkv); page tiles -> token-major.
+__global__ __launch_bounds__(256) void gather_kernel(const FillParams p) {
+  const int64_t pi = p.first_token / kP + blockIdx.x;
+  const int g = blockIdx.y;
+  const uint8_t *base = fill_page_base(p, pi);
+  const int64_t lo = p.first_token, hi = p.first_token + p.n_tokens;
+  const int tid = threadIdx.x;
+  {
+    const int c = tid >> 4, t = tid & 15;
+    const int64_t tok = pi * kP + t;
+    if (tok >= lo && tok < hi) {
+      const u32x4_t w = *reinterpret_cast<const u32x4_t *>(base + (int64_t)g * kTileBytes + (c * kP + t) * 16);
+      *reinterpret_cast<u32x4_t *>(p.k + ((tok - lo) * p.Hkv + g) * kD + c * 8) = w;
+    }
+  }
+  {
+    const int nbp = tid >> 6, jq = (tid >> 4) & 3, mm = tid & 15;
+    const uint16_t *src = reinterpret_cast<const uint16_t *>(base + (int64_t)(p.Hkv + g) * kTileBytes) + tid * 8;
+    const int64_t t0 = pi * kP + 4 * jq;
+#pragma unroll
+    for (int e = 0; e < 2; ++e)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int64_t tok = t0 + i;
+        if (tok >= lo && tok < hi) p.v[((tok - lo) * p.Hkv + g) * kD + (2 * nbp + e) * 16 + mm] = src[e * 4 + i];
+      }
+  }
+}
+
+__global__ __launch_bounds__(256) void blit_kernel(const BlitOp *ops, int64_t units_per_page) {
+  const BlitOp op = ops[blockIdx.x];
+  const u32x4_t *s = reinterpret_cast<const u32x4_t *>(op.src);
+  u32x4_t *d = reinterpret_cast<u32x4_t *>(op.dst);
+  for (int64_t i = (int64_t)blockIdx.y * blockDim.x + threadIdx.x; i < units_per_page;
+       i += (int64_t)gridDim.y * blockDim.x)
+    d[i] = s[i];
+}
+
+__global__ void set_i32_kernel(int32_t *dst, int32_t value) { *dst = value; }
+
+// ------------------------------------------------------------------------------------ launches
+
+hipError_t launch_attention(const AttnParams &p, hipStream_t s) {
+  if (p.n_items <= 0) return hipSuccess;
+  const size_t lds = (size_t)(3 * p.G * kD + kWaves * 32) * sizeof(float);
+  if (p.variant == 1) hipLaunchKernelGGL((attention_kernel<true, 1>), dim3((unsigned)p.n_items), dim3(256), lds, s, p);
+  else if (p.variant == 2) hipLaunchKernelGGL((attention_kernel<false, 3>), dim3((unsigned)p.n_items), dim3(256), lds, s, p);
+  else hipLaunchKernelGGL((attention_kernel<false, 2>), dim3((unsigned)p.n_items), dim3(256), lds, s, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_combine(const CombineParams &p, hipStream_t s) {
+  if (p.n_req <= 0) return hipSuccess;
+  hipLaunchKernelGGL(combine_kernel, dim3((unsigned)(p.n_req * p.Hq)), dim3(256), 0, s, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_append(const AppendParams &p, hipStream_t s) {
+  if (p.n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(append_kernel, dim3((unsigned)p.n), dim3(256), 0, s, p);
+  return hipGetLastError();
+}
+
+static dim3 fill_grid(const FillParams &p) {
+  const int64_t first = p.first_token / kP, last = (p.first_token + p.n_tokens - 1) / kP;
+  return dim3((unsigned)(last - first + 1), (unsigned)p.Hkv);
+}
+
+hipError_t launch_fill(const FillParams &p, hipStream_t s) {
+  if (p.n_tokens <= 0) return hipSuccess;
+  hipLaunchKernelGGL(fill_kernel, fill_grid(p), dim3(256), 0, s, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_gather(const FillParams &p, hipStream_t s) {
+  if (p.n_tokens <= 0) return hipSuccess;
+  hipLaunchKernelGGL(gather_kernel, fill_grid(p), dim3(256), 0, s, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_blit(const BlitOp *ops_dev, int64_t n_ops, int64_t page_bytes, hipStream_t s) {
+  if (n_ops <= 0) return hipSuccess;
+  const int64_t units = page_bytes / 16;
+  const unsigned split = (unsigned)std::max<int64_t>(1, std::min<int64_t>(8, units / 1024));
+  hipLaunchKernelGGL(blit_kernel, dim3((unsigned)n_ops, split), dim3(256), 0, s, ops_dev, units);
+  return hipGetLastError();
+}
+
+hipError_t launch_set_i32(int32_t *dst, int32_t value, hipStream_t s) {
+  hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(1), 0, s, dst, value);
+  return hipGetLastError();
+}
+
+}  // namespace orbit

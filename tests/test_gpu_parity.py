@@ -1,0 +1,235 @@
+"""GPU parity: liborbit (through the C ABI) against the float64 CPU oracle, element by element,
+on the same seeded inputs.
+
+Tolerances (bf16 Q/K/V, fp32 accumulation, bf16 softmax weights on the matrix cores, bf16
+output): max abs error <= 1e-2 and relative L2 error <= 5e-3 for the bf16 output; the fp32
+output (no final rounding) must stay within 3e-3 relative L2.  Integer / gather work and
+outputs across placements must be bit-exact.
+"""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from workloads import make_workload, Workload
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS, REL_L2, REL_L2_F32 = 1e-2, 5e-3, 3e-3
+
+
+def _harness():
+    import harness
+    return harness
+
+
+def _custom(lens, L=1, Hq=8, Hkv=2, seed=0, placement=None, steps=0) -> Workload:
+    b = len(lens)
+    pl = np.ones((b, L), dtype=np.uint8) if placement is None else np.asarray(placement, dtype=np.uint8)
+    return Workload("custom", seed, L, Hq, Hkv, 128, 16, np.arange(b, dtype=np.int64) + 10,
+                    np.asarray(lens, dtype=np.int32), pl, steps=steps)
+
+
+def _check(got_bf16, got_f32, want):
+    h = _harness()
+    ma, rl = h.errors(got_bf16, want)
+    assert ma <= MAX_ABS and rl <= REL_L2, (ma, rl)
+    if got_f32 is not None:
+        ma32, rl32 = h.errors(got_f32, want)
+        assert rl32 <= REL_L2_F32, (ma32, rl32)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_tiny_decode_attention_matches_oracle(seed):
+    h = _harness()
+    w = make_workload("tiny", seed)
+    g = h.GpuRun(w)
+    o = h.OracleRun(w)
+    for layer in range(w.n_layers):          # layer 0 resident, layer 1 streamed from the host
+        out, out32 = g.attention(layer)
+        _check(out, out32, o.attention(layer))
+    g.close()
+
+
+def test_tiny_steps_append_then_attend():
+    h = _harness()
+    w = dataclasses.replace(make_workload("tiny", 0), steps=20)   # 17 -> 37 crosses two block boundaries
+    g = h.GpuRun(w)
+    o = h.OracleRun(w, extra_tokens=20)
+    for s in range(20):
+        out, _ = g.step(s)
+        o.append_all()
+        if s in (0, 1, 14, 15, 16, 19):
+            for layer in range(w.n_layers):
+                _check(out[layer], None, o.attention(layer, s))
+    # the grown cache reads back bit-exactly, both tiers
+    for layer in range(w.n_layers):
+        k, v = g.read_kv(0, layer, 0, 37)
+        ko, vo = o.store.read(int(w.req_ids[0]), layer, 0, 37)
+        assert np.array_equal(k.cpu().view(torch.int16).numpy().view(np.uint16), ko)
+        assert np.array_equal(v.cpu().view(torch.int16).numpy().view(np.uint16), vo)
+    g.close()
+
+
+@pytest.mark.parametrize("lens,chunk", [
+    ([1, 2, 15, 16, 17], 0),
+    ([31, 32, 33, 63, 64, 65], 0),
+    ([511, 512, 513, 1024, 1025], 0),
+    ([100, 129, 700, 3000], 64),        # many chunks, ragged tails, several tiles per wave
+    ([5000], 128),
+])
+def test_edge_lengths(lens, chunk):
+    h = _harness()
+    w = _custom(lens, L=1)
+    g = h.GpuRun(w, chunk_tokens=chunk)
+    o = h.OracleRun(w)
+    out, out32 = g.attention(0)
+    _check(out, out32, o.attention(0))
+    g.close()
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(32, 8), (64, 8), (8, 8), (16, 1)])
+def test_head_shapes(Hq, Hkv):
+    h = _harness()
+    w = _custom([40, 777, 2050], L=2, Hq=Hq, Hkv=Hkv, placement=[[1, 0], [0, 1], [1, 0]])
+    g = h.GpuRun(w)
+    o = h.OracleRun(w)
+    for layer in range(2):
+        out, out32 = g.attention(layer)
+        _check(out, out32, o.attention(layer))
+    g.close()
+
+
+def test_kv_roundtrip_and_page_layout_bit_exact():
+    h = _harness()
+    from oracle import reference as ref
+    from workloads import gen_kv
+    w = _custom([37, 300], L=2, placement=[[1, 0], [0, 1]])
+    g = h.GpuRun(w)
+    for r in range(2):
+        for layer in range(2):
+            n = int(w.ctx_len[r])
+            k, v = g.read_kv(r, layer, 3, n - 5)
+            kw, vw = gen_kv(w.seed, layer, int(w.req_ids[r]), 3, n - 5, w.n_kv_heads, w.head_dim, "cpu")
+            assert torch.equal(k.cpu(), kw) and torch.equal(v.cpu(), vw)
+    # raw bytes of a resident page equal the oracle's packing of the same tokens
+    info = g.ctx.get_pages(int(w.req_ids[0]), 0)
+    assert info["tier"] == 1
+    page = g.hbm.view(torch.int16)[int(info["pages"][1]) * (w.page_bytes // 2):][: w.page_bytes // 2]
+    st = ref.PagedStore(1, w.n_kv_heads, w.head_dim, 16, 4)
+    st.add_request(0)
+    kw, vw = gen_kv(w.seed, 0, int(w.req_ids[0]), 0, 32, w.n_kv_heads, w.head_dim, "cpu")
+    st.write(0, 0, 0, kw, vw)
+    want = st.arena[st.pages[(0, 0)][1]]
+    assert np.array_equal(page.cpu().numpy().view(np.uint16), want)
+    # ... and of a host-resident page
+    info = g.ctx.get_pages(int(w.req_ids[0]), 1)
+    assert info["tier"] == 0
+    hp = g.host.view(torch.int16)[(info["host_first_page"] + 1) * (w.page_bytes // 2):][: w.page_bytes // 2]
+    kw, vw = gen_kv(w.seed, 1, int(w.req_ids[0]), 0, 32, w.n_kv_heads, w.head_dim, "cpu")
+    st2 = ref.PagedStore(1, w.n_kv_heads, w.head_dim, 16, 4)
+    st2.add_request(0)
+    st2.write(0, 0, 0, kw, vw)
+    assert np.array_equal(hp.numpy().view(np.uint16), st2.arena[st2.pages[(0, 0)][1]])
+    g.close()
+
+
+def test_outputs_bit_exact_across_placements():
+    h = _harness()
+    w = dataclasses.replace(make_workload("tiny", 1), steps=3)
+    rng = np.random.default_rng(5)
+    plans = [w.placement, np.ones_like(w.placement), np.zeros_like(w.placement), 1 - w.placement,
+             rng.integers(0, 2, size=w.placement.shape).astype(np.uint8)]
+    ref_att, ref_steps = None, None
+    for i, pl in enumerate(plans):
+        g = h.GpuRun(w, placement=pl, prefetch_slots=1 + i % 2)
+        att = [g.attention(l)[0].cpu() for l in range(w.n_layers)]
+        steps = [g.step(s)[0].cpu() for s in range(3)]
+        if ref_att is None:
+            ref_att, ref_steps = att, steps
+        else:
+            for a, b in zip(att + steps, ref_att + ref_steps):
+                assert torch.equal(a.view(torch.int16), b.view(torch.int16)), f"plan {i} differs"
+        g.close()
+
+
+def test_repeated_steps_are_deterministic():
+    h = _harness()
+    w = _custom([300, 1200, 90], L=4, placement=[[1, 0, 1, 0], [0, 0, 1, 1], [0, 1, 0, 1]], steps=2)
+    outs = []
+    for _ in range(2):
+        g = h.GpuRun(w, prefetch_slots=1)
+        outs.append(torch.stack([g.step(s)[0] for s in range(2)]).cpu())
+        g.close()
+    assert torch.equal(outs[0].view(torch.int16), outs[1].view(torch.int16))
+
+
+def test_plan_switch_moves_only_the_delta_and_keeps_results():
+    h = _harness()
+    w = _custom([100, 900, 2000], L=4, placement=[[1, 1, 0, 0], [1, 0, 1, 0], [0, 0, 1, 1]])
+    g = h.GpuRun(w, extra_pages=300)
+    before = [g.attention(l)[0].cpu() for l in range(4)]
+    new_pl = np.array([[1, 0, 0, 1], [1, 0, 1, 0], [1, 1, 0, 0]], dtype=np.uint8)
+    g.ctx.plan_load(w.req_ids, w.ctx_len, new_pl)
+    info = g.ctx.get_plan_info()
+    b = w.blocks()
+    changed_to_host = int(((w.placement == 1) & (new_pl == 0)).astype(np.int64).T.dot(b).sum())
+    changed_to_hbm = int(((w.placement == 0) & (new_pl == 1)).astype(np.int64).T.dot(b).sum())
+    assert info["moved_to_host_blocks"] == changed_to_host
+    assert info["moved_to_hbm_blocks"] == changed_to_hbm
+    after = [g.attention(l)[0].cpu() for l in range(4)]
+    for a, c in zip(before, after):
+        assert torch.equal(a.view(torch.int16), c.view(torch.int16))
+    # dropping a request and adding a new one
+    w2 = _custom([100, 2000, 50], L=4, placement=[[1, 0, 0, 1], [1, 1, 0, 0], [0, 1, 0, 1]])
+    w2 = dataclasses.replace(w2, req_ids=np.array([10, 12, 99], dtype=np.int64))
+    g.ctx.plan_load(w2.req_ids, w2.ctx_len, w2.placement)
+    from workloads import gen_kv
+    for l in range(4):
+        k, v = gen_kv(w2.seed, l, 99, 0, 50, w2.n_kv_heads, w2.head_dim, g.dev)
+        torch.cuda.synchronize()
+        g.ctx.kv_fill(99, l, 0, k, v)
+    torch.cuda.synchronize()
+    g.w = w2
+    o = h.OracleRun(w2)
+    for l in range(4):
+        out, out32 = g.attention(l)
+        _check(out, out32, o.attention(l))
+    g.close()
+
+
+def test_infeasible_plan_is_rejected_and_old_plan_survives():
+    h = _harness()
+    from paper_2601_10729_amd import OrbitError, ORBIT_E_CAPACITY
+    w = _custom([500, 800], L=2, placement=[[1, 0], [0, 1]])
+    g = h.GpuRun(w, extra_pages=2)
+    before = g.attention(0)[0].cpu()
+    with pytest.raises(OrbitError) as e:
+        g.ctx.plan_load(w.req_ids, w.ctx_len, np.ones((2, 2), dtype=np.uint8),
+                        hbm_budget_bytes=(int(w.blocks().sum()) * 2 - 1) * w.page_bytes)
+    assert e.value.code == ORBIT_E_CAPACITY
+    assert torch.equal(g.attention(0)[0].cpu().view(torch.int16), before.view(torch.int16))
+    g.close()
+
+
+def test_full_size_launch_sampled_against_oracle():
+    """One resident and one streamed layer of the 8B-shaped batch-16 workload at its full
+    lengths (the launch shape the bench times), checked on sampled (request, kv head) groups."""
+    h = _harness()
+    w = make_workload("llama8b_b16", 0)
+    pl = np.zeros((w.n_req, 2), dtype=np.uint8)
+    pl[:, 0] = 1
+    pl[::3, :] = [0, 1]
+    w2 = dataclasses.replace(w, n_layers=2, placement=pl, steps=0)
+    g = h.GpuRun(w2, prefetch_slots=1)
+    G = w2.n_q_heads // w2.n_kv_heads
+    rng = np.random.default_rng(0)
+    for layer in range(2):
+        out, out32 = g.attention(layer)
+        assert torch.isfinite(out32).all()
+        for _ in range(3):
+            r, kvh = int(rng.integers(w2.n_req)), int(rng.integers(w2.n_kv_heads))
+            want = h.oracle_one_group(w2, r, layer, kvh, int(w2.ctx_len[r]))
+            _check(out[r, kvh * G:(kvh + 1) * G], out32[r, kvh * G:(kvh + 1) * G], want)
+    g.close()

@@ -8,6 +8,7 @@ from .synth import (  # noqa: F401
     Workload,
     gen_kv,
     gen_q,
+    gen_q_steps,
     gen_kv_new,
     make_workload,
     normal_bf16_table,

@@ -141,6 +141,13 @@ def gen_q(seed: int, layer: int, req_id: int, step: int, n_q_heads: int, head_di
     return _draw(key, idx)[0]
 
 
+def gen_q_steps(seed: int, layer: int, req_id: int, step0: int, n_steps: int, n_q_heads: int,
+                head_dim: int, device="cpu"):
+    """Queries ``[n_steps][n_q_heads][head_dim]`` of decode steps ``step0 .. step0+n_steps-1``."""
+    key = stream_key(seed, TENSOR_Q, layer, req_id)
+    return _draw(key, _elem_index(step0, n_steps, range(n_q_heads), n_q_heads, head_dim, device))
+
+
 def pack_bitmap(placement: np.ndarray) -> np.ndarray:
     """Placement matrix [B][L] of 0/1 -> row-major bitmap [B][ceil(L/8)], bit l LSB-first."""
     return np.packbits(np.asarray(placement, dtype=np.uint8), axis=1, bitorder="little")

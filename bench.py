@@ -84,6 +84,8 @@ def main():
     ap.add_argument("--n-req", type=int, default=None, help="truncate the batch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-resident-variant", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three plain 1 GiB device-to-device copies (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build drives exactly one GPU (no sharding, no collectives); run with --gpus 1",
@@ -220,6 +222,13 @@ def main():
                     "attention_frac_of_hbm_peak": res_launch_bytes / (res_attn * 1e-3) / 1e9 / HBM_PEAK_GBS,
                     "avg_launch_ms": res_attn}
     g.close()
+    if args.calibrate_copy:
+        a = torch.ones(1 << 30, dtype=torch.uint8, device=dev)
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
 
     cpu = None
     if not args.no_cpu_baseline:

@@ -1,0 +1,355 @@
+"""CPU-only tests of liborbit's host logic through the C ABI (ORBIT_FLAG_HOST_ONLY contexts make
+no GPU call): exported symbols, Eq. (1), block tables, delta migration, staging schedule and
+gating rules, split-K work list.  Expected values come from the oracle's capacity functions,
+from brute force written here, or from the numbers printed in the paper's example."""
+import itertools
+import json
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2601_10729_amd as orbit
+from paper_2601_10729_amd import OrbitContext, OrbitError, orbit_plan_check
+from oracle import reference as ref
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+PAGE = 2 * 8 * 16 * 128 * 2        # bytes of one block for 8 kv heads
+
+
+def ctx(L=4, Hq=32, Hkv=8, max_req=8, max_tokens=8192, hbm_pages=4096, host_pages=4096, slots=1, window=0,
+        chunk=0):
+    page = 2 * Hkv * 16 * 128 * 2
+    return OrbitContext(n_layers=L, n_q_heads=Hq, n_kv_heads=Hkv, max_requests=max_req,
+                        max_tokens_per_request=max_tokens, prefetch_slots=slots, decode_window=window,
+                        chunk_tokens=chunk, host_only=True, hbm_arena_bytes=hbm_pages * page,
+                        host_arena_bytes=host_pages * page)
+
+
+# ------------------------------------------------------------------ boundary
+
+def test_library_exports_every_declared_symbol():
+    with open(os.path.join(ROOT, "include", "orbit.h")) as f:
+        declared = re.findall(r"ORBIT_API[^;(]*?\b(orbit_[a-z0-9_]+)\s*\(", f.read())
+    assert len(declared) >= 15 and len(set(declared)) == len(declared)
+    L = orbit.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert sorted(declared) == sorted(orbit.EXPORTS)
+
+
+def test_create_rejects_unsupported_shapes():
+    for kw in (dict(head_dim=64), dict(page_tokens=32), dict(n_q_heads=30), dict(n_q_heads=136, n_kv_heads=8),
+               dict(chunk_tokens=100), dict(prefetch_slots=0), dict(max_requests=0)):
+        args = dict(n_layers=2, n_q_heads=32, n_kv_heads=8, max_requests=4, max_tokens_per_request=1024,
+                    host_only=True, hbm_arena_bytes=PAGE * 64, host_arena_bytes=PAGE * 64)
+        args.update(kw)
+        with pytest.raises(OrbitError) as e:
+            OrbitContext(**args)
+        assert e.value.code == orbit.ORBIT_E_INVAL
+
+
+def test_gpu_context_without_arena_is_an_error_not_a_fallback():
+    with pytest.raises(OrbitError):
+        OrbitContext(n_layers=2, n_q_heads=32, n_kv_heads=8, max_requests=4, max_tokens_per_request=1024)
+
+
+# ------------------------------------------------------------------ Eq. (1)
+
+def test_plan_check_reproduces_the_papers_example():
+    with open(os.path.join(HERE, "golden", "toy_example.json")) as f:
+        toy = json.load(f)
+    L = toy["n_layers"]
+
+    def x(off):
+        m = np.ones((2, L), dtype=np.uint8)
+        for r, layers in enumerate(off):
+            for l in layers:
+                m[r, l - 1] = 0
+        return m
+    n1 = [b * 16 for b in toy["step1"]["blocks_per_layer"]]
+    n16 = [b * 16 for b in toy["step16"]["blocks_per_layer"]]
+    A, B, C = x([[3, 6, 9], [3, 6, 9]]), x([[], [3, 6, 9]]), x([[4, 8], [3, 6, 9]])
+    assert orbit_plan_check(n1, A)[1:3] == (9, 63)
+    assert orbit_plan_check(n16, A)[1:3] == (10, 70)
+    assert orbit_plan_check(n1, x([[3, 6], [3, 6]]))[2] == 72
+    assert orbit_plan_check(n1, B)[2] == 69
+    assert orbit_plan_check(n16, B)[2] == toy["placement_B"]["gpu_blocks_used_step16"]
+    assert orbit_plan_check(n16, C)[2] == toy["gpu_blocks"]
+    # the same verdicts through orbit_plan_load with a 70-block budget (2 kv heads here)
+    page = 2 * 2 * 16 * 128 * 2
+    c = OrbitContext(n_layers=L, n_q_heads=8, n_kv_heads=2, max_requests=2, max_tokens_per_request=1024,
+                     host_only=True, hbm_arena_bytes=200 * page, host_arena_bytes=200 * page)
+    c.plan_load([1, 2], n1, B, hbm_budget_bytes=70 * page)
+    assert c.get_plan_info()["resident_blocks"] + c.get_plan_info()["staging_blocks"] == 69
+    c2 = OrbitContext(n_layers=L, n_q_heads=8, n_kv_heads=2, max_requests=2, max_tokens_per_request=1024,
+                      host_only=True, hbm_arena_bytes=200 * page, host_arena_bytes=200 * page)
+    with pytest.raises(OrbitError) as e:
+        c2.plan_load([1, 2], n16, B, hbm_budget_bytes=70 * page)
+    assert e.value.code == orbit.ORBIT_E_CAPACITY
+    c2.plan_load([1, 2], n16, C, hbm_budget_bytes=70 * page)
+
+
+def test_plan_check_matches_oracle_on_random_plans():
+    rng = np.random.default_rng(0)
+    for _ in range(50):
+        B, L = int(rng.integers(1, 9)), int(rng.integers(1, 12))
+        n = rng.integers(0, 5000, size=B)
+        x = rng.integers(0, 2, size=(B, L)).astype(np.uint8)
+        k, win = int(rng.integers(1, 4)), int(rng.integers(0, 40))
+        b = ref.blocks(n + win)
+        want = (ref.resident_blocks(b, x), ref.prefetch_buffer_blocks(b, x), ref.gpu_blocks_needed(b, x, k),
+                int(((1 - x.astype(np.int64)) * b[:, None]).sum()))
+        assert orbit_plan_check(n, x, prefetch_slots=k, decode_window=win) == want
+
+
+def test_capacity_boundary_and_atomic_failure():
+    c = ctx(L=3, hbm_pages=1000)
+    n = [100, 900]
+    x = np.array([[1, 0, 1], [0, 1, 1]], dtype=np.uint8)
+    need = orbit_plan_check(n, x)[2]
+    with pytest.raises(OrbitError) as e:
+        c.plan_load([7, 8], n, x, hbm_budget_bytes=(need - 1) * PAGE)
+    assert e.value.code == orbit.ORBIT_E_CAPACITY
+    with pytest.raises(OrbitError):
+        c.get_plan_info()                                   # nothing was installed
+    c.plan_load([7, 8], n, x, hbm_budget_bytes=need * PAGE)
+    before = [c.get_pages(r, l) for r in (7, 8) for l in range(3)]
+    for bad in (dict(ids=[7, 7]), dict(n=[101, 900]), dict(budget=(need - 1) * PAGE, x=np.ones((2, 3), np.uint8))):
+        with pytest.raises(OrbitError):
+            c.plan_load(bad.get("ids", [7, 8]), bad.get("n", n), bad.get("x", x),
+                        hbm_budget_bytes=bad.get("budget", need * PAGE))
+    after = [c.get_pages(r, l) for r in (7, 8) for l in range(3)]
+    for a, b in zip(before, after):
+        assert a["tier"] == b["tier"] and a["host_first_page"] == b["host_first_page"]
+        assert np.array_equal(a["pages"], b["pages"])
+
+
+def test_host_arena_capacity():
+    c = ctx(L=2, host_pages=10)
+    with pytest.raises(OrbitError) as e:
+        c.plan_load([1], [16 * 11], np.array([[0, 1]], dtype=np.uint8))
+    assert e.value.code == orbit.ORBIT_E_HOST_CAPACITY
+    c.plan_load([1], [16 * 10], np.array([[0, 1]], dtype=np.uint8))
+
+
+# ------------------------------------------------------------------ block tables
+
+def _layout_invariants(c, ids, L):
+    info = c.get_plan_info()
+    first, nstage = info["staging_first_page"], info["staging_blocks"]
+    seen_hbm, host_runs = set(), []
+    per_layer_stage = {l: [] for l in range(L)}
+    for r in ids:
+        for l in range(L):
+            p = c.get_pages(r, l)
+            pages = [int(v) for v in p["pages"]]
+            if p["tier"] == 1:
+                assert all(0 <= q < first for q in pages)
+                assert not (seen_hbm & set(pages))
+                seen_hbm |= set(pages)
+            else:
+                assert pages == list(range(pages[0], pages[0] + len(pages)))       # contiguous staging range
+                assert first <= pages[0] and pages[-1] < first + nstage
+                per_layer_stage[l].append((pages[0], pages[-1]))
+                host_runs.append((p["host_first_page"], p["host_first_page"] + len(pages)))
+    assert len(seen_hbm) == info["resident_blocks"]
+    for l, spans in per_layer_stage.items():                # requests of one layer never share staging pages
+        spans.sort()
+        assert all(a[1] < b[0] for a, b in zip(spans, spans[1:]))
+    host_runs.sort()
+    assert all(a[1] <= b[0] for a, b in zip(host_runs, host_runs[1:]))
+    return info
+
+
+def test_block_tables_are_consistent_for_random_plans():
+    rng = np.random.default_rng(1)
+    for trial in range(20):
+        B, L = int(rng.integers(1, 7)), int(rng.integers(1, 7))
+        c = ctx(L=L, hbm_pages=6000, host_pages=6000, slots=int(rng.integers(1, 3)), window=int(rng.integers(0, 50)))
+        ids = [int(v) for v in rng.permutation(100)[:B]]
+        n = rng.integers(1, 3000, size=B)
+        x = rng.integers(0, 2, size=(B, L)).astype(np.uint8)
+        c.plan_load(ids, n, x)
+        info = _layout_invariants(c, ids, L)
+        assert info["buffer_blocks"] == ref.prefetch_buffer_blocks(ref.blocks(n + c.cfg.decode_window), x)
+        assert info["staging_first_page"] + info["staging_blocks"] == info["budget_blocks"]
+
+
+def test_plan_switch_moves_exactly_the_delta():
+    rng = np.random.default_rng(2)
+    B, L = 5, 6
+    c = ctx(L=L, hbm_pages=5000, host_pages=5000)
+    ids = list(range(10, 10 + B))
+    n = rng.integers(1, 2000, size=B)
+    b = ref.blocks(n)
+    x0 = rng.integers(0, 2, size=(B, L)).astype(np.uint8)
+    c.plan_load(ids, n, x0)
+    assert c.get_plan_info()["moved_to_host_blocks"] == 0 and c.get_plan_info()["moved_to_hbm_blocks"] == 0
+    for _ in range(6):
+        x1 = rng.integers(0, 2, size=(B, L)).astype(np.uint8)
+        c.plan_load(ids, n, x1)
+        info = _layout_invariants(c, ids, L)
+        assert info["moved_to_host_blocks"] == int((((x0 == 1) & (x1 == 0)) * b[:, None]).sum())
+        assert info["moved_to_hbm_blocks"] == int((((x0 == 0) & (x1 == 1)) * b[:, None]).sum())
+        x0 = x1
+    c.plan_load(ids, n, x0)                                # identical plan: nothing moves
+    info = c.get_plan_info()
+    assert (info["moved_to_host_blocks"], info["moved_to_hbm_blocks"], info["relocated_blocks"]) == (0, 0, 0)
+    # drop two requests, add one
+    keep = ids[:3] + [77]
+    c.plan_load(keep, list(n[:3]) + [500], np.ones((4, L), dtype=np.uint8))
+    _layout_invariants(c, keep, L)
+    with pytest.raises(OrbitError) as e:
+        c.get_pages(ids[4], 0)
+    assert e.value.code == orbit.ORBIT_E_NOT_FOUND
+
+
+def test_growing_staging_region_relocates_resident_blocks():
+    L = 1
+    c = ctx(L=L, hbm_pages=100)
+    c.plan_load([1, 2], [16 * 40, 16 * 40], np.ones((2, L), dtype=np.uint8), hbm_budget_bytes=100 * PAGE)
+    # a third request, offloaded, needs a 20-block staging region at the top of the budget
+    with pytest.raises(OrbitError):
+        c.plan_load([1, 2, 3], [640, 640, 16 * 21], np.array([[1], [1], [0]], np.uint8), hbm_budget_bytes=100 * PAGE)
+    c.plan_load([1, 2, 3], [640, 640, 16 * 20], np.array([[1], [1], [0]], np.uint8), hbm_budget_bytes=100 * PAGE)
+    info = _layout_invariants(c, [1, 2, 3], L)
+    assert info["staging_first_page"] == 80 and info["relocated_blocks"] == 0   # the lowest pages were in use
+    # shrink the budget: resident blocks above the new staging start must move down
+    c2 = ctx(L=1, hbm_pages=100)
+    c2.plan_load([1, 2], [16 * 30, 16 * 30], np.ones((2, 1), dtype=np.uint8))
+    c2.plan_load([2], [16 * 30], np.ones((1, 1), dtype=np.uint8), hbm_budget_bytes=30 * PAGE)
+    info = _layout_invariants(c2, [2], 1)
+    assert info["relocated_blocks"] == 30 and max(c2.get_pages(2, 0)["pages"]) < 30
+
+
+# ------------------------------------------------------------------ appends and the decode window
+
+def test_block_growth_and_window_expiry():
+    c = ctx(L=2, window=20)
+    c.plan_load([5], [40], np.array([[1, 0]], dtype=np.uint8))       # reserves ceil(60/16) = 4 blocks
+    assert len(c.get_pages(5, 0)["pages"]) == 4
+    steps = 0
+    with pytest.raises(OrbitError) as e:
+        for _ in range(100):
+            c.step(None, None, None, None)
+            steps += 1
+    assert e.value.code == orbit.ORBIT_E_STATE and steps == 64 - 40   # 4 blocks hold 64 tokens
+    assert c.get_pages(5, 0)["length"] == 64 and c.get_pages(5, 1)["length"] == 64
+    c.plan_load([5], [64], np.array([[1, 0]], dtype=np.uint8))        # a new plan opens a new window
+    c.step(None, None, None, None)
+    assert c.get_pages(5, 1)["length"] == 65
+    # per-layer appends through orbit_kv_append
+    c.kv_append(5, 0, 1, 1)
+    assert c.get_pages(5, 0)["length"] == 66 and c.get_pages(5, 1)["length"] == 65
+    with pytest.raises(OrbitError):
+        c.step(None, None, None, None) if False else c.plan_load([5], [65], np.array([[1, 0]], dtype=np.uint8))
+
+
+# ------------------------------------------------------------------ work list
+
+@pytest.mark.parametrize("chunk", [64, 512])
+def test_work_items_match_brute_force(chunk):
+    rng = np.random.default_rng(3)
+    B, L, Hkv = 6, 2, 8
+    max_tokens = 8192
+    c = ctx(L=L, max_tokens=max_tokens, chunk=chunk)
+    n = np.array([1, chunk, chunk + 1, 3 * chunk - 1, 777, 5000])
+    c.plan_load(list(range(B)), n, np.ones((B, L), dtype=np.uint8))
+    items = c.get_work_items(1)
+    max_chunks = -(-max_tokens // chunk)
+    want = {(r, g, ch): (r * max_chunks + ch) * Hkv + g
+            for r in range(B) for g in range(Hkv) for ch in range(-(-int(n[r]) // chunk))}
+    got = {(int(a), int(b), int(cc)): int(s) for a, b, cc, s in items}
+    assert got == want and len(items) == len(want)
+    # in order of first appearance, the (request, chunk) groups with a ragged chunk come last
+    first_seen = list(dict.fromkeys((int(r), int(cc)) for r, g, cc, s in items))
+    is_full = [bool((cc + 1) * chunk <= n[r]) for r, cc in first_seen]
+    assert is_full == sorted(is_full, reverse=True)
+    # the kv heads of one (request, chunk) sit 8 items apart: same XCD under round-robin dispatch
+    # (every full span of 8 groups; the last, shorter span is packed densely)
+    pos = {}
+    full_spans = (len(first_seen) // 8) * 8 * Hkv
+    for i, (r, g, cc, s) in enumerate(items[:full_spans]):
+        pos.setdefault((int(r), int(cc)), []).append(i % 8)
+    assert pos and all(len(set(v)) == 1 and len(v) == Hkv for v in pos.values())
+
+
+def test_attention_on_an_empty_request_is_an_error():
+    c = ctx(L=1)
+    c.plan_load([1, 2], [0, 5], np.ones((2, 1), dtype=np.uint8))
+    with pytest.raises(OrbitError) as e:
+        c.decode_attention(0, None, None)
+    assert e.value.code == orbit.ORBIT_E_INVAL
+
+
+# ------------------------------------------------------------------ staging schedule and gating
+
+def test_copy_schedule_order_and_ring_layout():
+    rng = np.random.default_rng(4)
+    for slots in (1, 2, 3):
+        B, L = 5, 7
+        c = ctx(L=L, hbm_pages=8000, host_pages=8000, slots=slots)
+        n = rng.integers(1, 3000, size=B)
+        b = ref.blocks(n)
+        x = rng.integers(0, 2, size=(B, L)).astype(np.uint8)
+        c.plan_load(list(range(B)), n, x)
+        info = c.get_plan_info()
+        rows = c.get_copy_schedule()
+        # brute force: layers ascending; inside a layer requests by ascending block count (stable);
+        # each layer's range packed round-robin into the staging region, wrapping to 0 when it does not fit
+        want, cursor = [], 0
+        for l in range(L):
+            off = [r for r in range(B) if x[r, l] == 0]
+            if not off:
+                continue
+            off.sort(key=lambda r: b[r])
+            tot = int(sum(b[r] for r in off))
+            if cursor + tot > info["staging_blocks"]:
+                cursor = 0
+            at = cursor
+            for r in off:
+                want.append([l, r, info["staging_first_page"] + at, int(b[r]), cursor])
+                at += int(b[r])
+            cursor += tot
+        assert rows.tolist() == want
+
+
+def test_staging_range_is_reused_only_after_its_layer_was_attended():
+    # single buffer (the paper's B_buf): two offloaded layers share the staging range
+    c = ctx(L=3, slots=1)
+    c.plan_load([1], [100], np.array([[0, 1, 0]], dtype=np.uint8))
+    c.kv_prefetch(0)
+    c.kv_prefetch(0)                                        # already prefetched: no-op
+    c.kv_prefetch(1)                                        # nothing offloaded: no-op
+    with pytest.raises(OrbitError) as e:
+        c.kv_prefetch(2)                                    # would overwrite layer 0's data
+    assert e.value.code == orbit.ORBIT_E_STATE
+    c.decode_attention(0, None, None)
+    c.kv_prefetch(2)                                        # layer 0 was attended: its range is free
+    with pytest.raises(OrbitError):
+        c.step(None, None, None, None)                      # layer 2 prefetched but never attended
+    c.decode_attention(2, None, None)
+    # two slots: both layers can be in flight at once
+    c2 = ctx(L=3, slots=2)
+    c2.plan_load([1], [100], np.array([[0, 1, 0]], dtype=np.uint8))
+    c2.kv_prefetch(0)
+    c2.kv_prefetch(2)
+    c2.decode_attention(0, None, None)
+    c2.decode_attention(2, None, None)
+    for _ in range(3):
+        c2.step(None, None, None, None) if c2.cfg.decode_window else None
+
+
+def test_steps_run_for_every_placement_of_a_small_batch():
+    # exhaustive over 2 requests x 3 layers: the schedule never deadlocks, lengths advance
+    for bits in itertools.product([0, 1], repeat=6):
+        x = np.array(bits, dtype=np.uint8).reshape(2, 3)
+        for slots in (1, 2):
+            c = ctx(L=3, slots=slots, window=3)
+            c.plan_load([1, 2], [30, 70], x)
+            for _ in range(3):
+                c.step(None, None, None, None)
+            assert c.get_pages(2, 2)["length"] == 73

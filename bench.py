@@ -241,7 +241,7 @@ def main():
         "config": {"workload": f"{args.workload}: {WORKLOAD_TEXT[args.workload]}", "seed": args.seed,
                    "placement": args.placement, "n_req": B, "n_layers": L, "tokens_per_layer": float(mid_len.sum()),
                    "kv_bytes_per_step": step_bytes, "resident_fraction": resident_frac,
-                   "prefetch_slots": args.prefetch_slots, "chunk_tokens": args.chunk_tokens or 512},
+                   "prefetch_slots": args.prefetch_slots, "chunk_tokens": args.chunk_tokens or 1024},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "host_link": link,

@@ -19,7 +19,7 @@ using namespace orbit;
 
 namespace {
 std::string g_create_error;
-constexpr int kDefaultChunkTokens = 512;
+constexpr int kDefaultChunkTokens = 1024;
 }  // namespace
 
 struct orbit_ctx {

@@ -43,13 +43,20 @@ __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __builtin
 
 __device__ __forceinline__ float xor_max(float v, int mask) { return fmaxf(v, __shfl_xor(v, mask, 64)); }
 
+template <bool NT>
+__device__ __forceinline__ u32x4_t load16(const uint8_t *p) {
+  if (NT) return __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+  return *reinterpret_cast<const u32x4_t *>(p);
+}
+
+template <bool NT>
 __device__ __forceinline__ void load_page(u32x4_t (&k)[4], u32x4_t (&v)[4], const uint8_t *ktile, const uint8_t *vtile,
                                           uint32_t lane_off) {
   // wave-uniform tile addresses + a 32-bit per-lane offset: scalar-base global loads, 1 KiB per instruction
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk) k[kk] = *reinterpret_cast<const u32x4_t *>(ktile + (lane_off + kk * 1024u));
+  for (int kk = 0; kk < 4; ++kk) k[kk] = load16<NT>(ktile + (lane_off + kk * 1024u));
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk) v[kk] = *reinterpret_cast<const u32x4_t *>(vtile + (lane_off + kk * 1024u));
+  for (int kk = 0; kk < 4; ++kk) v[kk] = load16<NT>(vtile + (lane_off + kk * 1024u));
 }
 
 __device__ __forceinline__ void zero_page(u32x4_t (&k)[4], u32x4_t (&v)[4]) {
@@ -130,7 +137,7 @@ __device__ __forceinline__ void process_tile(Tile &T, const bf16x8_t (&q)[4], f3
 
 // PREFETCH = true keeps the next tile's loads in flight while the current one is processed
 // (two register tiles, 2 workgroups per CU); false relies on more resident wavefronts instead.
-template <bool PREFETCH, int MIN_BLOCKS>
+template <bool PREFETCH, int MIN_BLOCKS, bool NT>
 __global__ __launch_bounds__(256, MIN_BLOCKS) void attention_kernel(const AttnParams p) {
   extern __shared__ float smem[];  // [3][G][128] accumulators of waves 1..3, then [4][2][16] (m, l)
   const int lane = threadIdx.x & 63;
@@ -168,11 +175,11 @@ __global__ __launch_bounds__(256, MIN_BLOCKS) void attention_kernel(const AttnPa
     const int valid = ntok - 2 * kP * t;
     const int p0 = __builtin_amdgcn_readfirstlane(row[2 * t]);
     const uint8_t *t0 = head_base + (int64_t)p0 * p.page_bytes;
-    load_page(T.k0, T.v0, t0, t0 + v_off, lane_off);
+    load_page<NT>(T.k0, T.v0, t0, t0 + v_off, lane_off);
     if (valid > kP) {
       const int p1 = __builtin_amdgcn_readfirstlane(row[2 * t + 1]);
       const uint8_t *t1 = head_base + (int64_t)p1 * p.page_bytes;
-      load_page(T.k1, T.v1, t1, t1 + v_off, lane_off);
+      load_page<NT>(T.k1, T.v1, t1, t1 + v_off, lane_off);
     } else {
       zero_page(T.k1, T.v1);
     }
@@ -424,9 +431,14 @@ __global__ void set_i32_kernel(int32_t *dst, int32_t value) { *dst = value; }
 hipError_t launch_attention(const AttnParams &p, hipStream_t s) {
   if (p.n_items <= 0) return hipSuccess;
   const size_t lds = (size_t)(3 * p.G * kD + kWaves * 32) * sizeof(float);
-  if (p.variant == 1) hipLaunchKernelGGL((attention_kernel<true, 1>), dim3((unsigned)p.n_items), dim3(256), lds, s, p);
-  else if (p.variant == 2) hipLaunchKernelGGL((attention_kernel<false, 3>), dim3((unsigned)p.n_items), dim3(256), lds, s, p);
-  else hipLaunchKernelGGL((attention_kernel<false, 2>), dim3((unsigned)p.n_items), dim3(256), lds, s, p);
+  const dim3 grid((unsigned)p.n_items), block(256);
+  switch (p.variant) {  // 0 is the measured best on MI355X; the others are kept for tuning runs
+    case 1: hipLaunchKernelGGL((attention_kernel<true, 1, false>), grid, block, lds, s, p); break;
+    case 2: hipLaunchKernelGGL((attention_kernel<false, 2, false>), grid, block, lds, s, p); break;
+    case 3: hipLaunchKernelGGL((attention_kernel<false, 3, false>), grid, block, lds, s, p); break;
+    case 4: hipLaunchKernelGGL((attention_kernel<false, 2, true>), grid, block, lds, s, p); break;
+    default: hipLaunchKernelGGL((attention_kernel<true, 1, true>), grid, block, lds, s, p); break;
+  }
   return hipGetLastError();
 }
 

@@ -75,7 +75,8 @@ def test_tiny_steps_append_then_attend():
 @pytest.mark.parametrize("lens,chunk", [
     ([1, 2, 15, 16, 17], 0),
     ([31, 32, 33, 63, 64, 65], 0),
-    ([511, 512, 513, 1024, 1025], 0),
+    ([511, 512, 513, 1024, 1025], 512),
+    ([1023, 1024, 1025, 2049, 3100], 0),
     ([100, 129, 700, 3000], 64),        # many chunks, ragged tails, several tiles per wave
     ([5000], 128),
 ])

@@ -250,7 +250,7 @@ def test_block_growth_and_window_expiry():
 
 # ------------------------------------------------------------------ work list
 
-@pytest.mark.parametrize("chunk", [64, 512])
+@pytest.mark.parametrize("chunk", [64, 1024])
 def test_work_items_match_brute_force(chunk):
     rng = np.random.default_rng(3)
     B, L, Hkv = 6, 2, 8

@@ -1,0 +1,79 @@
+"""GPU parity at the full lengths of the larger benchmark workloads, on two-layer slices (one
+launch per layer has the real shape: all requests at their real context lengths), checked on
+sampled (request, kv head) groups that the oracle computes one by one."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from workloads import make_workload
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS, REL_L2, REL_L2_F32 = 1e-2, 5e-3, 3e-3
+
+
+def _two_layer_slice(name, seed=0, n_req=None, steps=0):
+    w = make_workload(name, seed, n_req=n_req)
+    pl = np.zeros((w.n_req, 2), dtype=np.uint8)
+    pl[0::2] = [1, 0]                      # even requests: layer 0 resident, layer 1 streamed
+    pl[1::2] = [0, 1]
+    return dataclasses.replace(w, n_layers=2, placement=pl, steps=steps)
+
+
+def _check_groups(h, w, out, out32, lens, samples, step=0):
+    G = w.n_q_heads // w.n_kv_heads
+    for layer, r, g in samples:
+        want = h.oracle_one_group(w, r, layer, g, int(lens[r]), step)
+        got = out[layer][r, g * G:(g + 1) * G]
+        ma, rl = h.errors(got, want)
+        assert ma <= MAX_ABS and rl <= REL_L2, (layer, r, g, ma, rl)
+        if out32 is not None:
+            _, rl32 = h.errors(out32[layer][r, g * G:(g + 1) * G], want)
+            assert rl32 <= REL_L2_F32, (layer, r, g, rl32)
+
+
+def test_long_ctx_32_appended_steps():
+    """Batch 4, contexts in [64K, 128K], one token appended per step for 32 steps."""
+    import harness as h
+    w = _two_layer_slice("long_ctx", steps=32)
+    g = h.GpuRun(w, prefetch_slots=2)
+    out = None
+    for s in range(32):
+        out, _ = g.step(s)
+    assert torch.isfinite(out.float()).all()
+    lens = w.ctx_len.astype(np.int64) + 32
+    _check_groups(h, w, out, None, lens, [(0, 0, 3), (1, 0, 5), (0, 3, 0), (1, 2, 7)], step=31)
+    g.close()
+
+
+def test_llama70b_shape_group_of_eight():
+    """64 query heads over 8 KV heads, contexts in [16K, 128K] (batch truncated to 4)."""
+    import harness as h
+    w = _two_layer_slice("llama70b", n_req=4)
+    g = h.GpuRun(w)
+    outs, outs32 = [], []
+    for layer in range(2):
+        o, o32 = g.attention(layer)
+        outs.append(o)
+        outs32.append(o32)
+    _check_groups(h, w, outs, outs32, w.ctx_len, [(0, 0, 0), (1, 1, 6), (0, 3, 2), (1, 2, 4)])
+    g.close()
+
+
+def test_heavy_mixed_lengths():
+    """Batch 64, log-uniform contexts in [1K, 64K]: short and long requests in one launch."""
+    import harness as h
+    w = _two_layer_slice("heavy_mixed")
+    g = h.GpuRun(w, prefetch_slots=1)
+    outs, outs32 = [], []
+    for layer in range(2):
+        o, o32 = g.attention(layer)
+        outs.append(o)
+        outs32.append(o32)
+    order = np.argsort(w.ctx_len)
+    picks = [int(order[0]), int(order[len(order) // 2]), int(order[-1])]
+    _check_groups(h, w, outs, outs32, w.ctx_len, [(0, picks[0], 1), (1, picks[0], 6), (0, picks[1], 2),
+                                                  (1, picks[2], 4), (0, picks[2], 7)])
+    g.close()

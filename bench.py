@@ -82,6 +82,8 @@ def main():
     ap.add_argument("--chunk-tokens", type=int, default=0)
     ap.add_argument("--placement", default="workload", choices=["workload", "resident", "host"])
     ap.add_argument("--n-req", type=int, default=None, help="truncate the batch")
+    ap.add_argument("--max-host-gib", type=float, default=60.0,
+                    help="largest pinned host arena to ask for; the batch is truncated to fit")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-resident-variant", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -102,21 +104,30 @@ def main():
     dev = torch.device("cuda:0")
     K, W = args.steps, args.warmup
     total_steps = W + 2 * K + 4          # warm-up, timed, timed-with-events, all-resident variant
-    w = make_workload(args.workload, args.seed, n_req=args.n_req)
-    w = dataclasses.replace(w, steps=total_steps)
-    if args.placement == "resident":
-        w = w.all_resident()
-    elif args.placement == "host":
-        w = w.all_host()
+    from paper_2601_10729_amd import orbit_plan_check
+    n_req = args.n_req
+    while True:
+        w = make_workload(args.workload, args.seed, n_req=n_req, steps=total_steps)
+        if args.placement == "resident":
+            w = w.all_resident()
+        elif args.placement == "host":
+            w = w.all_host()
+        slots = args.prefetch_slots if w.hbm_budget_bytes is None else 1   # the byte budget was clipped for one buffer
+        _, _, need, host_blocks = orbit_plan_check(w.ctx_len, w.placement, w.page_tokens, slots, total_steps)
+        if (host_blocks + 8) * w.page_bytes <= args.max_host_gib * (1 << 30) or w.n_req == 1:
+            break
+        n_req = w.n_req - 1            # this host cannot pin that much: drop the last request and say so
 
     link_peak = measure_link_peak(torch)
     t_setup = time.perf_counter()
     # the arena is sized so that the all-resident variant of the same workload also fits
-    from paper_2601_10729_amd import orbit_plan_check
-    _, _, need, host_blocks = orbit_plan_check(w.ctx_len, w.placement, w.page_tokens, args.prefetch_slots, total_steps)
     all_res = int(w.blocks(2 * total_steps).sum()) * w.n_layers
-    g = harness.GpuRun(w, prefetch_slots=args.prefetch_slots, chunk_tokens=args.chunk_tokens,
-                       budget_pages=max(need, all_res) + 8, host_pages=host_blocks + 8,
+    fits_resident = w.hbm_budget_bytes is None and all_res * w.page_bytes < 250e9
+    pages = (max(need, all_res) if fits_resident else need) + 8
+    if w.hbm_budget_bytes is not None:
+        pages = max(pages, w.hbm_budget_bytes // w.page_bytes)
+    g = harness.GpuRun(w, prefetch_slots=slots, chunk_tokens=args.chunk_tokens,
+                       budget_pages=pages, host_pages=host_blocks + 8,
                        max_tokens=int(w.ctx_len.max()) + 2 * total_steps + 32)
     B, L = w.n_req, w.n_layers
     # per-step inputs, generated once and resident in HBM: [S][L][B][...]
@@ -203,7 +214,7 @@ def main():
 
     # all-resident variant of the same workload: the kernel's HBM rate without the link in the way
     resident = None
-    if not args.no_resident_variant and args.placement == "workload" and not w.placement.all():
+    if not args.no_resident_variant and args.placement == "workload" and not w.placement.all() and fits_resident:
         drain()
         cur = w.ctx_len.astype(np.int64) + step_no[0]
         g.ctx.plan_load(w.req_ids, cur.astype(np.int32), np.ones_like(w.placement))
@@ -241,7 +252,7 @@ def main():
         "config": {"workload": f"{args.workload}: {WORKLOAD_TEXT[args.workload]}", "seed": args.seed,
                    "placement": args.placement, "n_req": B, "n_layers": L, "tokens_per_layer": float(mid_len.sum()),
                    "kv_bytes_per_step": step_bytes, "resident_fraction": resident_frac,
-                   "prefetch_slots": args.prefetch_slots, "chunk_tokens": args.chunk_tokens or 1024},
+                   "prefetch_slots": slots, "note": w.note, "hbm_budget_bytes": w.hbm_budget_bytes, "chunk_tokens": args.chunk_tokens or 1024},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "host_link": link,

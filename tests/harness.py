@@ -45,7 +45,7 @@ class GpuRun:
                                 chunk_tokens=chunk_tokens, decode_window=self.window,
                                 hbm_arena=self.hbm, host_arena=self.host,
                                 compute_stream=self.cs, copy_stream=self.xs)
-        self.ctx.plan_load(w.req_ids, w.ctx_len, self.placement)
+        self.ctx.plan_load(w.req_ids, w.ctx_len, self.placement, w.hbm_budget_bytes)
         self.len = w.ctx_len.astype(np.int64).copy()
         if fill:
             self.fill(layers)

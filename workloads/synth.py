@@ -205,10 +205,12 @@ def _per_request_subsets(rng, n_req, n_layers, n_resident):
     return pl
 
 
-def make_workload(name: str, seed: int = 0, n_req: Optional[int] = None) -> Workload:
+def make_workload(name: str, seed: int = 0, n_req: Optional[int] = None,
+                  steps: Optional[int] = None) -> Workload:
     """One of: tiny, llama8b_b16, long_ctx, heavy_mixed, llama70b.
 
-    ``n_req`` truncates the batch (used when a machine cannot pin enough host memory).
+    ``n_req`` truncates the batch (used when a machine cannot pin enough host memory);
+    ``steps`` overrides the number of decode steps the plan must leave room for.
     """
     rng = np.random.Generator(np.random.PCG64([seed, sum(map(ord, name))]))
     shape8b = dict(n_layers=32, n_q_heads=32, n_kv_heads=8, head_dim=128, page_tokens=16)
@@ -236,7 +238,6 @@ def make_workload(name: str, seed: int = 0, n_req: Optional[int] = None) -> Work
         pl = _per_request_subsets(rng, b, 32, np.floor(frac * 32))
         w = Workload(name, seed, req_ids=np.arange(b, dtype=np.int64) + 3000, ctx_len=ctx,
                      placement=pl, hbm_budget_bytes=40 * 10**9, **shape8b)
-        w = _clip_to_budget(w)
     elif name == "llama70b":
         b = 32
         ctx = rng.integers(16384, 131072, size=b, endpoint=True).astype(np.int32)
@@ -250,6 +251,10 @@ def make_workload(name: str, seed: int = 0, n_req: Optional[int] = None) -> Work
         w = dataclasses.replace(w, req_ids=w.req_ids[:n_req], ctx_len=w.ctx_len[:n_req],
                                 placement=w.placement[:n_req],
                                 note=(w.note + f" truncated to {n_req} requests").strip())
+    if steps is not None:
+        w = dataclasses.replace(w, steps=steps)
+    if w.hbm_budget_bytes is not None:
+        w = _clip_to_budget(w)
     return w
 
 
@@ -274,4 +279,4 @@ def _clip_to_budget(w: Workload, prefetch_slots: int = 1) -> Workload:
             raise ValueError("budget too small even with everything on the host")
         layer = int(np.nonzero(pl[r])[0].max())
         pl[r, layer] = 0
-    return w.with_placement(pl, "clipped to the byte budget")
+    return w.with_placement(pl, (w.note + " clipped to the byte budget").strip())

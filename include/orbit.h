@@ -108,6 +108,10 @@ typedef struct {
   int64_t relocated_blocks;       /* resident blocks moved out of the new staging region        */
   int32_t n_requests;
   int32_t chunk_tokens;
+  int64_t evicted_blocks;         /* HBM blocks of paused requests the last plan load pushed to host */
+  int64_t paused_resident_blocks; /* HBM blocks still held by paused requests (reclaimable)     */
+  int32_t paused_requests;
+  int32_t reserved_;
 } orbit_plan_info;
 
 /* ---- lifetime (ancillary) ------------------------------------------------------------------ */
@@ -130,9 +134,9 @@ ORBIT_API int orbit_plan_check(int32_t n_req, int32_t n_layers, int32_t page_tok
                      int64_t *out4);
 
 /* Installs a placement for the batch {req_ids}.  All pointers are host memory.
- *   req_ids[n_req]  distinct ids; ids not listed are dropped and their blocks freed; ids not
- *                   known yet are created holding ctx_len tokens of undefined content (write
- *                   them with orbit_kv_fill).
+ *   req_ids[n_req]  distinct ids; active ids not listed are dropped and their blocks freed
+ *                   (paused ones stay paused); ids not known yet are created holding ctx_len
+ *                   tokens of undefined content (write them with orbit_kv_fill).
  *   ctx_len[n_req]  tokens held now; for a known request it must equal its current length.
  *   placement_bitmap as in orbit_plan_check.
  *   hbm_budget_bytes  B_GPU = floor(min(budget, arena) / page bytes).
@@ -144,6 +148,16 @@ ORBIT_API int orbit_plan_load(orbit_ctx *ctx, int32_t n_req, const int64_t *req_
                     const uint8_t *placement_bitmap, int64_t hbm_budget_bytes);
 
 ORBIT_API int orbit_get_plan_info(orbit_ctx *ctx, orbit_plan_info *out);
+
+/* Pause-Resume (Section 3.4) with the removable cache of Section 4.  orbit_request_pause takes an
+ * active request out of the batch (the other requests keep their placement; tables are rebuilt;
+ * this call synchronises like orbit_plan_load) but leaves its KV where it is.  Its HBM blocks no
+ * longer count against Eq. (1): a later orbit_plan_load that needs the room evicts them to the
+ * host arena one layer at a time, only as many as needed.  A paused request is resumed by
+ * listing it in orbit_plan_load again (only layers that were evicted and are wanted in HBM move
+ * back), and forgotten with orbit_request_drop. */
+ORBIT_API int orbit_request_pause(orbit_ctx *ctx, int64_t req_id);
+ORBIT_API int orbit_request_drop(orbit_ctx *ctx, int64_t req_id);
 
 /* ---- a3: KV writes (Section 2.3 block growth; Section 3.2 direct-to-host writes) ------------ */
 

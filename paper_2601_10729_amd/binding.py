@@ -55,14 +55,15 @@ class orbit_plan_info(C.Structure):
                 ("buffer_blocks", C.c_int64), ("staging_first_page", C.c_int64), ("staging_blocks", C.c_int64),
                 ("host_blocks", C.c_int64), ("moved_to_host_blocks", C.c_int64),
                 ("moved_to_hbm_blocks", C.c_int64), ("relocated_blocks", C.c_int64),
-                ("n_requests", C.c_int32), ("chunk_tokens", C.c_int32)]
+                ("n_requests", C.c_int32), ("chunk_tokens", C.c_int32), ("evicted_blocks", C.c_int64),
+                ("paused_resident_blocks", C.c_int64), ("paused_requests", C.c_int32), ("reserved_", C.c_int32)]
 
     def as_dict(self):
         return {f: getattr(self, f) for f, _ in self._fields_}
 
 
 EXPORTS = ["orbit_create", "orbit_destroy", "orbit_last_error", "orbit_plan_check", "orbit_plan_load",
-           "orbit_get_plan_info", "orbit_kv_fill", "orbit_kv_read", "orbit_kv_append", "orbit_kv_prefetch",
+           "orbit_get_plan_info", "orbit_request_pause", "orbit_request_drop", "orbit_kv_fill", "orbit_kv_read", "orbit_kv_append", "orbit_kv_prefetch",
            "orbit_decode_attention", "orbit_step", "orbit_get_pages", "orbit_get_work_items",
            "orbit_get_copy_schedule"]
 
@@ -87,6 +88,8 @@ def lib() -> C.CDLL:
     L.orbit_plan_check.argtypes = [i32, i32, i32, i32p, u8p, i32, i32, i64p]
     L.orbit_plan_load.argtypes = [vp, i32, i64p, i32p, u8p, i64]
     L.orbit_get_plan_info.argtypes = [vp, C.POINTER(orbit_plan_info)]
+    L.orbit_request_pause.argtypes = [vp, i64]
+    L.orbit_request_drop.argtypes = [vp, i64]
     L.orbit_kv_fill.argtypes = [vp, i64, i32, i64, i64, vp, vp]
     L.orbit_kv_read.argtypes = [vp, i64, i32, i64, i64, vp, vp]
     L.orbit_kv_append.argtypes = [vp, i64, i32, vp, vp]
@@ -200,6 +203,12 @@ class OrbitContext:
         info = orbit_plan_info()
         self._check(self._L.orbit_get_plan_info(self._h, C.byref(info)))
         return info.as_dict()
+
+    def request_pause(self, req_id: int):
+        self._check(self._L.orbit_request_pause(self._h, int(req_id)))
+
+    def request_drop(self, req_id: int):
+        self._check(self._L.orbit_request_drop(self._h, int(req_id)))
 
     def kv_fill(self, req_id: int, layer: int, first_token: int, k, v):
         self._check(self._L.orbit_kv_fill(self._h, int(req_id), layer, first_token, k.shape[0], _ptr(k), _ptr(v)))

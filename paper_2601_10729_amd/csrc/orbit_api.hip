@@ -275,6 +275,17 @@ int run_phases(orbit_ctx *c, const std::vector<std::vector<PageOp>> &phases) {
   return ORBIT_OK;
 }
 
+int upload_tables(orbit_ctx *c) {
+  const int n_req = (int)c->hs.reqs.size();
+  if (!c->host_only && n_req > 0) {
+    const Shape &sh = c->hs.sh;
+    HIPCHECK(c, hipMemcpy(c->d_table, c->hs.h_table.data(), (size_t)n_req * sh.L * sh.cap_pages * sizeof(int32_t),
+                          hipMemcpyHostToDevice));
+    HIPCHECK(c, hipMemcpy(c->d_len, c->hs.h_len.data(), (size_t)n_req * sh.L * sizeof(int32_t), hipMemcpyHostToDevice));
+  }
+  return ORBIT_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -451,13 +462,29 @@ int orbit_plan_load(orbit_ctx *c, int32_t n_req, const int64_t *req_ids, const i
   c->items_valid = false;
   std::fill(c->host_dirty.begin(), c->host_dirty.end(), 0);
   if ((rc = run_phases(c, phases))) return rc;
-  if (!c->host_only && n_req > 0) {
-    const Shape &sh = c->hs.sh;
-    HIPCHECK(c, hipMemcpy(c->d_table, c->hs.h_table.data(), (size_t)n_req * sh.L * sh.cap_pages * sizeof(int32_t),
-                          hipMemcpyHostToDevice));
-    HIPCHECK(c, hipMemcpy(c->d_len, c->hs.h_len.data(), (size_t)n_req * sh.L * sizeof(int32_t), hipMemcpyHostToDevice));
+  return upload_tables(c);
+}
+
+int orbit_request_pause(orbit_ctx *c, int64_t req_id) {
+  if (!c) return ORBIT_E_INVAL;
+  if (!c->hs.has_plan) return set_err(c, ORBIT_E_STATE, "no plan installed");
+  if (!c->host_only) {
+    HIPCHECK(c, hipStreamSynchronize(c->cs));
+    HIPCHECK(c, hipStreamSynchronize(c->xs));
   }
-  return ORBIT_OK;
+  std::vector<std::vector<PageOp>> phases;
+  int rc = c->hs.pause(req_id, phases);
+  if (rc) return set_err(c, rc, c->hs.err);
+  c->items_valid = false;
+  std::fill(c->host_dirty.begin(), c->host_dirty.end(), 0);
+  if ((rc = run_phases(c, phases))) return rc;
+  return upload_tables(c);
+}
+
+int orbit_request_drop(orbit_ctx *c, int64_t req_id) {
+  if (!c) return ORBIT_E_INVAL;
+  int rc = c->hs.drop_paused(req_id);
+  return rc ? set_err(c, rc, c->hs.err) : ORBIT_OK;
 }
 
 int orbit_get_plan_info(orbit_ctx *c, orbit_plan_info *out) {
@@ -683,15 +710,17 @@ int64_t orbit_get_pages(orbit_ctx *c, int64_t req_id, int32_t layer, int32_t *ti
   int rc = check_layer(c, layer);
   if (rc) return rc;
   const int r = c->hs.find(req_id);
-  if (r < 0) return set_err(c, ORBIT_E_NOT_FOUND, "unknown request id");
-  const LayerKV &lk = c->hs.reqs[r].layers[layer];
+  const int pr = r < 0 ? c->hs.find_paused(req_id) : -1;
+  if (r < 0 && pr < 0) return set_err(c, ORBIT_E_NOT_FOUND, "unknown request id");
+  const Req &q = r >= 0 ? c->hs.reqs[r] : c->hs.paused[pr];
+  const LayerKV &lk = q.layers[layer];
   if (tier) *tier = lk.tier;
   if (host_first_page) *host_first_page = lk.tier == 0 ? lk.host_page0 : -1;
   if (length) *length = lk.len;
-  const int64_t n = c->hs.reqs[r].reserved;
-  const int32_t *row = c->hs.table_row(r, layer);
+  const int64_t n = lk.tier == 1 ? (int64_t)lk.pages.size() : (r >= 0 ? q.reserved : lk.host_cap);
   if (pages_out)
-    for (int64_t i = 0; i < n && i < cap; ++i) pages_out[i] = row[i];
+    for (int64_t i = 0; i < n && i < cap; ++i)
+      pages_out[i] = lk.tier == 1 ? lk.pages[i] : (r >= 0 ? lk.stage_page0 + (int32_t)i : -1);
   return n;
 }
 

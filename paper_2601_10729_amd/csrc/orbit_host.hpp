@@ -155,7 +155,9 @@ class HostState {
  public:
   Shape sh;
   int64_t arena_pages = 0, host_pages = 0;
-  std::vector<Req> reqs;  // plan order
+  std::vector<Req> reqs;    // plan order
+  std::vector<Req> paused;  // out of the batch; their HBM blocks are reclaimable (removable cache)
+  int64_t last_budget_bytes = 0;
   HbmAlloc hbm;
   RunAlloc host;
   bool has_plan = false;
@@ -188,13 +190,23 @@ class HostState {
       if (reqs[i].id == id) return (int)i;
     return -1;
   }
+  int find_paused(int64_t id) const {
+    for (size_t i = 0; i < paused.size(); ++i)
+      if (paused[i].id == id) return (int)i;
+    return -1;
+  }
   int32_t *table_row(int r, int l) { return &h_table[((size_t)r * sh.L + l) * sh.cap_pages]; }
 
   // ------------------------------------------------------------------------------ plan load
   // On success fills `phases` with the page copies to run, in order (one blit per phase), and
   // commits the new state.  On failure nothing is changed.
+  // `pause_id` (or -1): an active request that leaves the batch but keeps its blocks (Pause-Resume,
+  // Section 3.4; removable cache, Section 4).  Paused requests not listed in `ids` stay paused;
+  // listing one resumes it.  Their HBM blocks are evicted to the host only when this plan needs
+  // the space, one layer at a time.
   int plan_load(int32_t n_req, const int64_t *ids, const int32_t *ctx_len, const uint8_t *bitmap,
-                int64_t budget_bytes, std::vector<std::vector<PageOp>> &phases) {
+                int64_t budget_bytes, std::vector<std::vector<PageOp>> &phases, int64_t pause_id = -1,
+                bool do_pause = false) {
     phases.clear();
     if (n_req < 0 || n_req > sh.max_req) return fail(ORBIT_E_INVAL, "n_req out of range");
     if (n_req > 0 && (!ids || !ctx_len || !bitmap)) return fail(ORBIT_E_INVAL, "null argument");
@@ -210,10 +222,13 @@ class HostState {
       rb[r] = ceil_div((int64_t)ctx_len[r] + sh.window, P);
       for (int l = 0; l < L; ++l) x[(size_t)r * L + l] = bitmap_get(bitmap, L, r, l);
       int o = find(ids[r]);
-      if (o >= 0)
+      int po = o < 0 ? find_paused(ids[r]) : -1;
+      const Req *known = o >= 0 ? &reqs[o] : (po >= 0 ? &paused[po] : nullptr);
+      if (known)
         for (int l = 0; l < L; ++l)
-          if (reqs[o].layers[l].len != ctx_len[r])
+          if (known->layers[l].len != ctx_len[r])
             return fail(ORBIT_E_STATE, "ctx_len differs from the stored length of a known request");
+      if (do_pause && ids[r] == pause_id) return fail(ORBIT_E_INVAL, "request both listed and paused");
     }
     // Eq. (1)
     Eq1 e = eq1_eval(n_req, L, rb, x);
@@ -229,19 +244,36 @@ class HostState {
     HbmAlloc A = hbm;
     RunAlloc H = host;
     std::vector<Req> old = reqs;
+    std::vector<Req> oldp = paused;
+    std::vector<Req> np;  // paused after this call
     std::vector<Req> nw(n_req);
-    std::vector<int> old_of(n_req, -1);
-    std::vector<uint8_t> kept(old.size(), 0);
-    int64_t to_host = 0, to_hbm = 0, reloc = 0;
+    std::vector<int> old_of(n_req, -1), oldp_of(n_req, -1);
+    std::vector<uint8_t> kept(old.size(), 0), resumed(oldp.size(), 0);
+    int64_t to_host = 0, to_hbm = 0, reloc = 0, evicted = 0;
 
     for (int r = 0; r < n_req; ++r) {
       int o = find(ids[r]);
       old_of[r] = o;
       if (o >= 0) kept[o] = 1;
+      else if ((oldp_of[r] = find_paused(ids[r])) >= 0) resumed[oldp_of[r]] = 1;
     }
-    // (a) dropped requests: nothing to preserve
+    for (size_t o = 0; o < oldp.size(); ++o)
+      if (!resumed[o]) np.push_back(std::move(oldp[o]));
+    // (a) requests that leave the batch: paused ones keep their blocks (trimmed to what is used),
+    //     dropped ones free everything
     for (size_t o = 0; o < old.size(); ++o) {
       if (kept[o]) continue;
+      if (do_pause && old[o].id == pause_id) {
+        Req q = std::move(old[o]);
+        for (auto &lk : q.layers) {
+          const size_t used = (size_t)ceil_div(lk.len, P);
+          while (lk.pages.size() > used) { A.release(lk.pages.back()); lk.pages.pop_back(); }
+          lk.stage_page0 = -1;
+        }
+        q.reserved = (int32_t)ceil_div(q.layers[0].len, P);
+        np.push_back(std::move(q));
+        continue;
+      }
       for (auto &lk : old[o].layers) {
         for (int32_t p : lk.pages) A.release(p);
         if (lk.tier == 0) H.release(lk.host_page0, lk.host_cap);
@@ -249,6 +281,7 @@ class HostState {
     }
     for (int r = 0; r < n_req; ++r) {
       if (old_of[r] >= 0) nw[r] = std::move(old[old_of[r]]);
+      else if (oldp_of[r] >= 0) nw[r] = std::move(oldp[oldp_of[r]]);
       else {
         nw[r].id = ids[r];
         nw[r].layers.assign(L, LayerKV());
@@ -264,6 +297,55 @@ class HostState {
       free_hbm.clear();
       free_host.clear();
     };
+    // (a2) removable cache: paused blocks are evicted only where this plan needs the room — every
+    //      paused layer with a page inside the new staging region, then, while the active resident
+    //      blocks do not fit below it, the highest resident layer of the paused request that holds
+    //      the most HBM blocks.
+    phases.emplace_back();
+    {
+      auto resident_pages = [&](const Req &q) {
+        int64_t n = 0;
+        for (auto &lk : q.layers) if (lk.tier == 1) n += (int64_t)lk.pages.size();
+        return n;
+      };
+      auto evict = [&](LayerKV &lk) -> int {
+        const int64_t used = (int64_t)lk.pages.size();
+        int64_t run = H.alloc(used);
+        if (run < 0) return ORBIT_E_HOST_CAPACITY;
+        for (int64_t i = 0; i < used; ++i) phases.back().push_back({OP_HBM_TO_HOST, lk.pages[i], run + i});
+        for (int32_t p : lk.pages) free_hbm.push_back(p);
+        evicted += used;
+        lk.pages.clear();
+        lk.tier = 0;
+        lk.host_page0 = run;
+        lk.host_cap = (int32_t)used;
+        return ORBIT_OK;
+      };
+      for (auto &q : np)
+        for (auto &lk : q.layers) {
+          if (lk.tier != 1) continue;
+          bool inside = false;
+          for (int32_t pg : lk.pages) inside |= pg >= ring_first;
+          if (inside && evict(lk)) return fail(ORBIT_E_HOST_CAPACITY, "host arena full (evicting a paused request)");
+        }
+      for (;;) {
+        int64_t held = 0;
+        int victim = -1;
+        int64_t most = 0;
+        for (size_t i = 0; i < np.size(); ++i) {
+          int64_t n = resident_pages(np[i]);
+          held += n;
+          if (n > most) { most = n; victim = (int)i; }
+        }
+        if (e.resident + held <= ring_first || victim < 0) break;
+        for (int l = L - 1; l >= 0; --l)
+          if (np[victim].layers[l].tier == 1 && !np[victim].layers[l].pages.empty()) {
+            if (evict(np[victim].layers[l])) return fail(ORBIT_E_HOST_CAPACITY, "host arena full (evicting a paused request)");
+            break;
+          }
+      }
+    }
+    end_phase();
     // (b) demotions HBM -> host
     phases.emplace_back();
     for (int r = 0; r < n_req; ++r)
@@ -386,6 +468,8 @@ class HostState {
     hbm = std::move(A);
     host = std::move(H);
     reqs = std::move(nw);
+    paused = std::move(np);
+    last_budget_bytes = budget_bytes;
     blocks = std::move(nb);
     block_of_layer = std::move(bol);
     live.clear();
@@ -400,9 +484,59 @@ class HostState {
     info.moved_to_host_blocks = to_host;
     info.moved_to_hbm_blocks = to_hbm;
     info.relocated_blocks = reloc;
+    info.evicted_blocks = evicted;
+    info.paused_requests = (int32_t)paused.size();
+    info.paused_resident_blocks = 0;
+    for (auto &q : paused)
+      for (auto &lk : q.layers)
+        if (lk.tier == 1) info.paused_resident_blocks += (int64_t)lk.pages.size();
     info.n_requests = n_req;
     info.chunk_tokens = sh.chunk_tokens;
     rebuild_tables();
+    return ORBIT_OK;
+  }
+
+  // Re-installs the current placement for the batch without `id`, which becomes paused.
+  int pause(int64_t id, std::vector<std::vector<PageOp>> &phases) {
+    const int o = find(id);
+    if (o < 0) return fail(find_paused(id) >= 0 ? ORBIT_E_STATE : ORBIT_E_NOT_FOUND,
+                           find_paused(id) >= 0 ? "request is already paused" : "unknown request id");
+    for (int l = 1; l < sh.L; ++l)
+      if (reqs[o].layers[l].len != reqs[o].layers[0].len)
+        return fail(ORBIT_E_STATE, "request is in the middle of a step (layer lengths differ)");
+    std::vector<int64_t> ids;
+    std::vector<int32_t> n;
+    std::vector<uint8_t> bm;
+    const int bpr = (sh.L + 7) / 8;
+    for (size_t r = 0; r < reqs.size(); ++r) {
+      if ((int)r == o) continue;
+      ids.push_back(reqs[r].id);
+      n.push_back(reqs[r].layers[0].len);
+      for (int l = 1; l < sh.L; ++l)
+        if (reqs[r].layers[l].len != n.back())
+          return fail(ORBIT_E_STATE, "a request is in the middle of a step (layer lengths differ)");
+      size_t at = bm.size();
+      bm.resize(at + bpr, 0);
+      for (int l = 0; l < sh.L; ++l)
+        if (reqs[r].layers[l].tier == 1) bm[at + l / 8] |= (uint8_t)(1u << (l % 8));
+    }
+    return plan_load((int32_t)ids.size(), ids.data(), n.data(), bm.data(), last_budget_bytes, phases, id, true);
+  }
+
+  int drop_paused(int64_t id) {
+    const int po = find_paused(id);
+    if (po < 0) return fail(find(id) >= 0 ? ORBIT_E_STATE : ORBIT_E_NOT_FOUND,
+                            find(id) >= 0 ? "request is active; pause it or leave it out of the next plan" : "unknown request id");
+    for (auto &lk : paused[po].layers) {
+      for (int32_t p : lk.pages) hbm.release(p);
+      if (lk.tier == 0) host.release(lk.host_page0, lk.host_cap);
+    }
+    paused.erase(paused.begin() + po);
+    info.paused_requests = (int32_t)paused.size();
+    info.paused_resident_blocks = 0;
+    for (auto &q : paused)
+      for (auto &lk : q.layers)
+        if (lk.tier == 1) info.paused_resident_blocks += (int64_t)lk.pages.size();
     return ORBIT_OK;
   }
 

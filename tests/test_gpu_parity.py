@@ -234,3 +234,39 @@ def test_full_size_launch_sampled_against_oracle():
             want = h.oracle_one_group(w2, r, layer, kvh, int(w2.ctx_len[r]))
             _check(out[r, kvh * G:(kvh + 1) * G], out32[r, kvh * G:(kvh + 1) * G], want)
     g.close()
+
+
+def test_pause_evict_resume_keeps_kv_bit_exact():
+    """Pause a request, force the eviction of some of its layers by admitting a new request,
+    resume it: its attention output and its stored KV are unchanged bit for bit."""
+    h = _harness()
+    from workloads import gen_kv
+    L = 4
+    w = _custom([600, 900, 1500], L=L, placement=np.ones((3, L), dtype=np.uint8))
+    need = int(w.blocks().sum()) * L
+    g = h.GpuRun(w, budget_pages=need + 200, host_pages=need * 2)
+    before = [g.attention(l)[0].cpu() for l in range(L)]
+    victim = int(w.req_ids[2])
+    g.ctx.request_pause(victim)
+    assert g.ctx.get_plan_info()["paused_resident_blocks"] == int(w.blocks()[2]) * L
+    # a newcomer of 1200 tokens (75 blocks x 4 layers) does not fit beside the paused blocks
+    ids2 = [int(w.req_ids[0]), int(w.req_ids[1]), 55]
+    g.ctx.plan_load(ids2, [600, 900, 1200], np.ones((3, L), dtype=np.uint8))
+    info = g.ctx.get_plan_info()
+    assert 0 < info["evicted_blocks"] < int(w.blocks()[2]) * L
+    for l in range(L):
+        k, v = gen_kv(w.seed, l, 55, 0, 1200, w.n_kv_heads, w.head_dim, g.dev)
+        torch.cuda.synchronize()
+        g.ctx.kv_fill(55, l, 0, k, v)
+    torch.cuda.synchronize()
+    # the newcomer finishes; the paused request comes back with every layer wanted in HBM
+    g.ctx.plan_load([int(x) for x in w.req_ids], w.ctx_len, np.ones((3, L), dtype=np.uint8))
+    assert g.ctx.get_plan_info()["moved_to_hbm_blocks"] == info["evicted_blocks"]
+    after = [g.attention(l)[0].cpu() for l in range(L)]
+    for a, b in zip(before, after):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    for l in range(L):
+        k, v = g.read_kv(2, l, 0, 1500)
+        kw, vw = gen_kv(w.seed, l, victim, 0, 1500, w.n_kv_heads, w.head_dim, "cpu")
+        assert torch.equal(k.cpu(), kw) and torch.equal(v.cpu(), vw)
+    g.close()

@@ -353,3 +353,72 @@ def test_steps_run_for_every_placement_of_a_small_batch():
             for _ in range(3):
                 c.step(None, None, None, None)
             assert c.get_pages(2, 2)["length"] == 73
+
+
+# ------------------------------------------------------------------ pause / resume (removable cache)
+
+def test_pause_keeps_blocks_and_evicts_only_what_is_needed():
+    L = 4
+    c = ctx(L=L, hbm_pages=200, host_pages=2000)
+    ones = lambda b: np.ones((b, L), dtype=np.uint8)
+    c.plan_load([1, 2, 3], [160, 240, 320], ones(3))                 # 10 + 15 + 20 blocks per layer
+    before = [c.get_pages(3, l)["pages"].copy() for l in range(L)]
+    c.request_pause(3)
+    info = c.get_plan_info()
+    assert (info["n_requests"], info["paused_requests"], info["paused_resident_blocks"]) == (2, 1, 80)
+    assert (info["evicted_blocks"], info["moved_to_host_blocks"], info["moved_to_hbm_blocks"]) == (0, 0, 0)
+    for l in range(L):
+        p = c.get_pages(3, l)
+        assert p["tier"] == 1 and np.array_equal(p["pages"], before[l])
+    with pytest.raises(OrbitError) as e:
+        c.request_pause(3)
+    assert e.value.code == orbit.ORBIT_E_STATE
+    assert len(c.get_work_items(0)) == (1 + 1) * 8                   # only the two active requests
+    # a new request needs 40 blocks: 100 + 40 + 80 paused > 200, so exactly one paused layer (20 blocks) goes
+    c.plan_load([1, 2, 4], [160, 240, 160], ones(3))
+    info = c.get_plan_info()
+    assert (info["evicted_blocks"], info["paused_resident_blocks"], info["paused_requests"]) == (20, 60, 1)
+    assert c.get_pages(3, 3)["tier"] == 0                             # highest layer first
+    for l in range(3):
+        p = c.get_pages(3, l)
+        assert p["tier"] == 1 and np.array_equal(p["pages"], before[l])
+    _layout_invariants(c, [1, 2, 4], L)
+    # resume with the evicted layer left on the host: nothing moves
+    x = ones(3)
+    x[2, 3] = 0
+    c.plan_load([1, 2, 3], [160, 240, 320], x)
+    info = c.get_plan_info()
+    assert (info["moved_to_hbm_blocks"], info["moved_to_host_blocks"], info["evicted_blocks"]) == (0, 0, 0)
+    assert info["paused_requests"] == 0
+    with pytest.raises(OrbitError):
+        c.get_pages(4, 0)                                             # request 4 was active and not listed: dropped
+    _layout_invariants(c, [1, 2, 3], L)
+    # pause again, then resume wanting every layer in HBM: only the evicted layer comes back
+    c.request_pause(3)
+    c.plan_load([1, 2, 3], [160, 240, 320], ones(3))
+    assert c.get_plan_info()["moved_to_hbm_blocks"] == 20
+    # drop
+    c.request_pause(2)
+    with pytest.raises(OrbitError):
+        c.request_drop(1)                                             # active
+    c.request_drop(2)
+    with pytest.raises(OrbitError) as e:
+        c.request_drop(2)
+    assert e.value.code == orbit.ORBIT_E_NOT_FOUND
+    c.plan_load([1, 3, 9], [160, 320, 16 * 15], ones(3))              # the freed blocks are usable again
+    _layout_invariants(c, [1, 3, 9], L)
+
+
+def test_paused_blocks_leave_a_growing_staging_region():
+    L = 2
+    c = ctx(L=L, hbm_pages=100, host_pages=1000)
+    c.plan_load([1, 2], [16 * 20, 16 * 25], np.ones((2, L), dtype=np.uint8))    # pages 0..89 in use
+    c.request_pause(2)
+    # request 3 is offloaded: staging region of 30 blocks = pages 70..99, where paused blocks sit
+    c.plan_load([1, 3], [16 * 20, 16 * 30], np.array([[1, 1], [0, 0]], dtype=np.uint8))
+    info = c.get_plan_info()
+    assert info["staging_first_page"] == 70
+    for l in range(L):
+        p = c.get_pages(2, l)
+        assert p["tier"] == 0 or max(p["pages"]) < 70
+    assert info["evicted_blocks"] in (25, 50) and info["evicted_blocks"] + info["paused_resident_blocks"] == 50

@@ -323,6 +323,7 @@ int orbit_create(const orbit_config *cfg, orbit_ctx **out) {
   if (cfg->page_tokens != 16) return bad("page_tokens must be 16");
   if (cfg->n_kv_heads < 1 || cfg->n_q_heads < 1 || cfg->n_q_heads % cfg->n_kv_heads) return bad("bad head counts");
   if (cfg->n_q_heads / cfg->n_kv_heads > 16) return bad("more than 16 query heads per kv head");
+  if (cfg->n_kv_heads > 128) return bad("more than 128 kv heads");
   if (cfg->max_requests < 1 || cfg->max_requests > ORBIT_MAX_REQUESTS) return bad("max_requests out of range");
   if (cfg->max_tokens_per_request < 1 || cfg->max_tokens_per_request > (1 << 24)) return bad("max_tokens_per_request out of range");
   if (cfg->prefetch_slots < 1 || cfg->prefetch_slots > 16) return bad("prefetch_slots out of range");

@@ -206,6 +206,37 @@ ORBIT_API int orbit_decode_attention(orbit_ctx *ctx, int32_t layer, const void *
 ORBIT_API int orbit_step(orbit_ctx *ctx, const void *q, const void *k_new, const void *v_new, void *out,
                orbit_step_stats *stats);
 
+/* ---- planner helpers (host only, no context, no GPU) ---------------------------------------- */
+
+/* Distance-driven candidates of Section 3.3.2: writes the distinct values of floor(L/k),
+ * k = 2..L, in descending order (16 10 8 6 5 4 3 2 1 for L = 32) and returns their number D(L)
+ * (<= 2*floor(sqrt(L)) - 1), or a negative error.  counts_out may be NULL. */
+ORBIT_API int orbit_distance_options(int32_t n_layers, int32_t *counts_out, int32_t cap);
+
+/* One request's placement row for an offload count: every N-th layer (1-based l with l % N == 0)
+ * is offloaded, N the largest distance with floor(L/N) == count; 0 keeps all layers on the GPU,
+ * L offloads all.  row_out: ceil(L/8) bytes, bit l LSB-first, 1 = GPU. */
+ORBIT_API int orbit_distance_pattern(int32_t n_layers, int32_t offload_count, uint8_t *row_out);
+
+/* Modelled decode latency of a placement (Section 3.3.1, the prefetch rules behind Algorithm 1,
+ * run as an event-driven simulation with even bandwidth sharing).  blocks[r] = b_r,
+ * blocks_per_time = link bandwidth B in blocks per time unit, comp[l] = compute time of layer l.
+ * stall_out (optional, L doubles) receives the stall time in front of each layer; *t_batch the
+ * total (sum comp + sum stall).  All pointers host memory. */
+ORBIT_API int orbit_model_latency(int32_t n_req, int32_t n_layers, const int64_t *blocks,
+                                  const uint8_t *placement_bitmap, double blocks_per_time, const double *comp,
+                                  double *stall_out, double *t_batch);
+
+/* Searches the pruned space (per request: keep all, the D(L) distance-driven counts, offload all)
+ * for the placement of minimum modelled latency that satisfies Eq. (1) with gpu_blocks and
+ * prefetch_slots.  Exhaustive if the space has at most max_evals points (ties: fewest offloads
+ * for the earliest request), coordinate descent from the best uniform plan otherwise.
+ * bitmap_out: [n_req][ceil(L/8)].  Returns ORBIT_E_CAPACITY if nothing is feasible (the
+ * planner's "infeasible", after which the paper pauses a request). */
+ORBIT_API int orbit_plan_search(int32_t n_req, int32_t n_layers, const int64_t *blocks, int64_t gpu_blocks,
+                                int32_t prefetch_slots, double blocks_per_time, const double *comp,
+                                int64_t max_evals, uint8_t *bitmap_out, double *t_batch, int64_t *evals_out);
+
 /* ---- host-side introspection (integers only; used by tests) --------------------------------- */
 
 /* Page ids that attention reads for (req_id, layer): arena ids for a resident block list,

@@ -10,5 +10,9 @@ from .binding import (  # noqa: F401
     OrbitContext,
     OrbitError,
     lib,
+    orbit_distance_options,
+    orbit_distance_pattern,
+    orbit_model_latency,
     orbit_plan_check,
+    orbit_plan_search,
 )

@@ -65,7 +65,8 @@ class orbit_plan_info(C.Structure):
 EXPORTS = ["orbit_create", "orbit_destroy", "orbit_last_error", "orbit_plan_check", "orbit_plan_load",
            "orbit_get_plan_info", "orbit_request_pause", "orbit_request_drop", "orbit_kv_fill", "orbit_kv_read", "orbit_kv_append", "orbit_kv_prefetch",
            "orbit_decode_attention", "orbit_step", "orbit_get_pages", "orbit_get_work_items",
-           "orbit_get_copy_schedule"]
+           "orbit_get_copy_schedule", "orbit_distance_options", "orbit_distance_pattern", "orbit_model_latency",
+           "orbit_plan_search"]
 
 _lib = None
 
@@ -102,6 +103,11 @@ def lib() -> C.CDLL:
     L.orbit_get_work_items.restype = i64
     L.orbit_get_copy_schedule.argtypes = [vp, i32p, i64]
     L.orbit_get_copy_schedule.restype = i64
+    f64p = C.POINTER(C.c_double)
+    L.orbit_distance_options.argtypes = [i32, i32p, i32]
+    L.orbit_distance_pattern.argtypes = [i32, i32, u8p]
+    L.orbit_model_latency.argtypes = [i32, i32, i64p, u8p, C.c_double, f64p, f64p, f64p]
+    L.orbit_plan_search.argtypes = [i32, i32, i64p, i64, i32, C.c_double, f64p, i64, u8p, f64p, i64p]
     for name in EXPORTS:
         fn = getattr(L, name)
         if fn.restype is C.c_int:
@@ -136,6 +142,60 @@ def orbit_plan_check(ctx_len: Sequence[int], placement: np.ndarray, page_tokens:
     if rc != 0:
         raise OrbitError(rc, "orbit_plan_check")
     return tuple(int(v) for v in out)
+
+
+def _bitmap(placement) -> np.ndarray:
+    return _np(np.packbits(np.asarray(placement, dtype=np.uint8), axis=1, bitorder="little"), np.uint8)
+
+
+def _unbitmap(bm: np.ndarray, n_layers: int) -> np.ndarray:
+    return np.unpackbits(bm, axis=1, bitorder="little")[:, :n_layers].astype(np.uint8)
+
+
+def orbit_distance_options(n_layers: int):
+    """The D(L) distance-driven offload counts, descending."""
+    out = np.zeros(ORBIT_MAX_LAYERS, dtype=np.int32)
+    n = lib().orbit_distance_options(n_layers, out.ctypes.data_as(C.POINTER(C.c_int32)), len(out))
+    if n < 0:
+        raise OrbitError(n, "orbit_distance_options")
+    return [int(v) for v in out[:n]]
+
+
+def orbit_distance_pattern(n_layers: int, offload_count: int) -> np.ndarray:
+    row = np.zeros((1, (n_layers + 7) // 8), dtype=np.uint8)
+    rc = lib().orbit_distance_pattern(n_layers, offload_count, row.ctypes.data_as(C.POINTER(C.c_uint8)))
+    if rc != 0:
+        raise OrbitError(rc, "orbit_distance_pattern")
+    return _unbitmap(row, n_layers)[0]
+
+
+def orbit_model_latency(blocks, placement, blocks_per_time: float, comp):
+    """(T_batch, stall time per layer) of a placement under the library's prefetch model."""
+    pl = np.asarray(placement, dtype=np.uint8)
+    n_req, n_layers = pl.shape
+    b, cp, bm = _np(blocks, np.int64), _np(comp, np.float64), _bitmap(pl)
+    stall, t = np.zeros(n_layers, dtype=np.float64), C.c_double()
+    rc = lib().orbit_model_latency(n_req, n_layers, b.ctypes.data_as(C.POINTER(C.c_int64)),
+                                   bm.ctypes.data_as(C.POINTER(C.c_uint8)), float(blocks_per_time),
+                                   cp.ctypes.data_as(C.POINTER(C.c_double)),
+                                   stall.ctypes.data_as(C.POINTER(C.c_double)), C.byref(t))
+    if rc != 0:
+        raise OrbitError(rc, "orbit_model_latency")
+    return t.value, stall
+
+
+def orbit_plan_search(blocks, n_layers: int, gpu_blocks: int, blocks_per_time: float, comp,
+                      prefetch_slots: int = 1, max_evals: int = 100000):
+    """(T_batch, placement [B][L], evaluations) of the best plan in the pruned space."""
+    b, cp = _np(blocks, np.int64), _np(comp, np.float64)
+    bm = np.zeros((len(b), (n_layers + 7) // 8), dtype=np.uint8)
+    t, ev = C.c_double(), C.c_int64()
+    rc = lib().orbit_plan_search(len(b), n_layers, b.ctypes.data_as(C.POINTER(C.c_int64)), int(gpu_blocks),
+                                 prefetch_slots, float(blocks_per_time), cp.ctypes.data_as(C.POINTER(C.c_double)),
+                                 int(max_evals), bm.ctypes.data_as(C.POINTER(C.c_uint8)), C.byref(t), C.byref(ev))
+    if rc != 0:
+        raise OrbitError(rc, "orbit_plan_search: no feasible placement" if rc == ORBIT_E_CAPACITY else "orbit_plan_search")
+    return t.value, _unbitmap(bm, n_layers), ev.value
 
 
 class OrbitContext:

@@ -14,6 +14,7 @@
 #include "../../include/orbit.h"
 #include "orbit_host.hpp"
 #include "orbit_kernels.h"
+#include "orbit_planner.hpp"
 
 using namespace orbit;
 
@@ -308,6 +309,64 @@ int orbit_plan_check(int32_t n_req, int32_t n_layers, int32_t page_tokens, const
   out4[1] = e.buffer;
   out4[2] = e.resident + (int64_t)prefetch_slots * e.buffer;
   out4[3] = e.host;
+  return ORBIT_OK;
+}
+
+int orbit_distance_options(int32_t n_layers, int32_t *counts_out, int32_t cap) {
+  if (n_layers < 1 || n_layers > ORBIT_MAX_LAYERS) return ORBIT_E_INVAL;
+  std::vector<int> v = distance_counts(n_layers);
+  if (counts_out)
+    for (int i = 0; i < (int)v.size() && i < cap; ++i) counts_out[i] = v[i];
+  return (int)v.size();
+}
+
+int orbit_distance_pattern(int32_t n_layers, int32_t offload_count, uint8_t *row_out) {
+  if (n_layers < 1 || n_layers > ORBIT_MAX_LAYERS || offload_count < 0 || offload_count > n_layers || !row_out)
+    return ORBIT_E_INVAL;
+  std::vector<uint8_t> x(n_layers);
+  if (!distance_pattern(n_layers, offload_count, x.data())) return ORBIT_E_INVAL;  // not a floor(L/k)
+  for (int i = 0; i < (n_layers + 7) / 8; ++i) row_out[i] = 0;
+  for (int l = 0; l < n_layers; ++l)
+    if (x[l]) row_out[l / 8] |= (uint8_t)(1u << (l % 8));
+  return ORBIT_OK;
+}
+
+static bool planner_args_ok(int32_t n_req, int32_t n_layers, const int64_t *blocks, double bw, const double *comp) {
+  if (n_req < 0 || n_req > ORBIT_MAX_REQUESTS || n_layers < 1 || n_layers > ORBIT_MAX_LAYERS || !comp) return false;
+  if (!(bw > 0.0) || (n_req > 0 && !blocks)) return false;
+  for (int r = 0; r < n_req; ++r)
+    if (blocks[r] < 0) return false;
+  for (int l = 0; l < n_layers; ++l)
+    if (!(comp[l] >= 0.0)) return false;
+  return true;
+}
+
+int orbit_model_latency(int32_t n_req, int32_t n_layers, const int64_t *blocks, const uint8_t *placement_bitmap,
+                        double blocks_per_time, const double *comp, double *stall_out, double *t_batch) {
+  if (!planner_args_ok(n_req, n_layers, blocks, blocks_per_time, comp) || !t_batch) return ORBIT_E_INVAL;
+  if (n_req > 0 && !placement_bitmap) return ORBIT_E_INVAL;
+  std::vector<uint8_t> x((size_t)n_req * n_layers);
+  for (int r = 0; r < n_req; ++r)
+    for (int l = 0; l < n_layers; ++l) x[(size_t)r * n_layers + l] = bitmap_get(placement_bitmap, n_layers, r, l);
+  *t_batch = simulate_prefetch(n_req, n_layers, x.data(), blocks, blocks_per_time, comp, stall_out);
+  return ORBIT_OK;
+}
+
+int orbit_plan_search(int32_t n_req, int32_t n_layers, const int64_t *blocks, int64_t gpu_blocks, int32_t prefetch_slots,
+                      double blocks_per_time, const double *comp, int64_t max_evals, uint8_t *bitmap_out,
+                      double *t_batch, int64_t *evals_out) {
+  if (!planner_args_ok(n_req, n_layers, blocks, blocks_per_time, comp) || prefetch_slots < 1 || gpu_blocks < 0 ||
+      max_evals < 1 || !t_batch || (n_req > 0 && !bitmap_out))
+    return ORBIT_E_INVAL;
+  SearchResult res = plan_search(n_req, n_layers, blocks, gpu_blocks, prefetch_slots, blocks_per_time, comp, max_evals);
+  if (evals_out) *evals_out = res.evals;
+  if (!(res.t < std::numeric_limits<double>::infinity())) return ORBIT_E_CAPACITY;
+  *t_batch = res.t;
+  const int bpr = (n_layers + 7) / 8;
+  for (int i = 0; i < n_req * bpr; ++i) bitmap_out[i] = 0;
+  for (int r = 0; r < n_req; ++r)
+    for (int l = 0; l < n_layers; ++l)
+      if (res.x[(size_t)r * n_layers + l]) bitmap_out[r * bpr + l / 8] |= (uint8_t)(1u << (l % 8));
   return ORBIT_OK;
 }
 

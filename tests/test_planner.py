@@ -1,0 +1,176 @@
+"""Planner helpers: pins for the oracle's cost model and pruning enumerator (numbers printed in
+the paper), then parity of the library's host implementation against that oracle.  CPU only."""
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+
+import paper_2601_10729_amd as orbit
+from oracle import latency_model as lm
+from oracle import reference as ref
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def _toy():
+    with open(os.path.join(HERE, "golden", "toy_example.json")) as f:
+        return json.load(f)
+
+
+def _x(n_layers, offloaded_1based):
+    m = np.ones((len(offloaded_1based), n_layers), dtype=np.uint8)
+    for r, layers in enumerate(offloaded_1based):
+        for l in layers:
+            m[r, l - 1] = 0
+    return m
+
+
+# ------------------------------------------------------------------ pins: pruning (Section 3.3.2)
+
+def test_distance_counts_match_the_papers_numbers():
+    assert len(lm.distance_offload_counts(32)) == 9                       # D(32) = 9
+    assert 9 ** 4 == 6561
+    for L in range(2, 129):
+        assert len(lm.distance_offload_counts(L)) <= 2 * math.isqrt(L) - 1       # the bound of Section 3.3.2
+    # two of six layers offloaded: [1 1 0 1 1 0]  (Section 2.2)
+    assert lm.distance_pattern(6, 2).tolist() == [1, 1, 0, 1, 1, 0]
+    # every 4th / 5th of 32 layers: 8 / 6 layers offloaded
+    assert lm.distance_of_count(32, 8) == 4 and int((lm.distance_pattern(32, 8) == 0).sum()) == 8
+    assert lm.distance_of_count(32, 6) == 5 and int((lm.distance_pattern(32, 6) == 0).sum()) == 6
+    for c in lm.distance_offload_counts(32):
+        assert int((lm.distance_pattern(32, c) == 0).sum()) == c
+    assert lm.distance_pattern(32, 0).all() and not lm.distance_pattern(32, 32).any()
+
+
+# ------------------------------------------------------------------ pins: latency model (Sections 2.3, 3.3.1)
+
+def test_simulation_reproduces_the_stall_totals_of_the_papers_example():
+    toy = _toy()
+    L, bw = toy["n_layers"], float(toy["link_blocks_per_layer_time"])
+    comp = [1.0] * L
+    A = _x(L, toy["placement_A"]["offloaded_layers_1based"])
+    B = _x(L, [[], [3, 6, 9]])
+    for step in ("step1", "step16"):
+        b = toy[step]["blocks_per_layer"]
+        t, stalls = lm.simulate_prefetch(A, b, bw, comp)
+        assert abs(sum(stalls) * bw - toy["placement_A"]["stalls"][step]) < 1e-9    # 9 and 12, in block units
+        assert abs(t - (L + sum(stalls))) < 1e-12
+        assert [i + 1 for i, s in enumerate(stalls) if s > 0] == [3, 6, 9]
+    t, stalls = lm.simulate_prefetch(B, toy["step1"]["blocks_per_layer"], bw, comp)
+    assert sum(stalls) == toy["placement_B"]["stalls"]["step1"] == 0
+
+
+def test_algorithm_as_printed_differs_from_the_example_at_step_16():
+    # kept as a record of why the planner uses the simulation: 9 is reproduced, 12 is not,
+    # and placement B at step 1 is not stall-free under the printed pseudo-code
+    toy = _toy()
+    L, bw, comp = toy["n_layers"], 3.0, [1.0] * toy["n_layers"]
+    A = _x(L, toy["placement_A"]["offloaded_layers_1based"])
+    assert abs(sum(lm.algorithm1_as_printed(A, [3, 6], bw, comp)[1]) - 9.0) < 1e-9
+    assert abs(sum(lm.algorithm1_as_printed(A, [4, 6], bw, comp)[1]) - 11.0) < 1e-9
+    assert sum(lm.algorithm1_as_printed(_x(L, [[], [3, 6, 9]]), [3, 6], bw, comp)[1]) > 0
+
+
+def test_simulation_closed_forms():
+    comp = [2.0, 1.0, 3.0, 1.5]
+    # nothing offloaded: pure compute
+    t, st = lm.simulate_prefetch(np.ones((3, 4), np.uint8), [5, 7, 9], 2.0, comp)
+    assert t == sum(comp) and not any(st)
+    # one request, only layer 1 offloaded: nothing to overlap with
+    t, st = lm.simulate_prefetch(_x(4, [[1]]), [6], 2.0, comp)
+    assert st == [3.0, 0, 0, 0] and t == sum(comp) + 3.0
+    # one request, every layer offloaded: the buffer is busy while a layer runs, no overlap at all
+    t, st = lm.simulate_prefetch(np.zeros((1, 4), np.uint8), [6], 2.0, comp)
+    assert st == [3.0] * 4 and t == sum(comp) + 12.0
+    # one request, layer 3 offloaded: the fetch overlaps layers 1 and 2 (3 time units)
+    t, st = lm.simulate_prefetch(_x(4, [[3]]), [10], 2.0, comp)
+    assert st == [0, 0, 2.0, 0]
+    # two equal requests sharing the link evenly finish together: same as one request of twice the size
+    t2, st2 = lm.simulate_prefetch(_x(4, [[3], [3]]), [5, 5], 2.0, comp)
+    assert st2 == st
+    # more bandwidth never hurts; the link bound holds
+    rng = np.random.default_rng(0)
+    for _ in range(30):
+        n_req, L = int(rng.integers(1, 5)), int(rng.integers(1, 9))
+        x = rng.integers(0, 2, size=(n_req, L)).astype(np.uint8)
+        b = rng.integers(1, 20, size=n_req)
+        cp = rng.uniform(0.5, 2.0, size=L)
+        t1, _ = lm.simulate_prefetch(x, b, 3.0, cp)
+        t2, _ = lm.simulate_prefetch(x, b, 6.0, cp)
+        assert t2 <= t1 + 1e-9 and t1 >= cp.sum() - 1e-9
+        assert t1 >= float(((1 - x.astype(np.int64)) * b[:, None]).sum()) / 3.0 - 1e-9
+
+
+# ------------------------------------------------------------------ library against the oracle
+
+def test_library_enumerator_matches_oracle():
+    for L in (1, 2, 6, 9, 32, 80, 128):
+        assert orbit.orbit_distance_options(L) == lm.distance_offload_counts(L)
+        for c in [0] + lm.distance_offload_counts(L) + [L]:
+            assert orbit.orbit_distance_pattern(L, c).tolist() == lm.distance_pattern(L, c).tolist()
+    with pytest.raises(orbit.OrbitError):
+        orbit.orbit_distance_pattern(32, 7)                   # 7 is not a floor(32/k)
+
+
+def test_library_latency_model_matches_oracle():
+    rng = np.random.default_rng(1)
+    for _ in range(200):
+        n_req, L = int(rng.integers(1, 7)), int(rng.integers(1, 13))
+        x = rng.integers(0, 2, size=(n_req, L)).astype(np.uint8)
+        b = rng.integers(0, 50, size=n_req)
+        comp = rng.uniform(0.1, 3.0, size=L)
+        bw = float(rng.uniform(0.5, 20.0))
+        t, st = orbit.orbit_model_latency(b, x, bw, comp)
+        tw, sw = lm.simulate_prefetch(x, b, bw, comp)
+        assert abs(t - tw) <= 1e-9 * max(1.0, tw)
+        np.testing.assert_allclose(st, sw, rtol=1e-9, atol=1e-9)
+    toy = _toy()
+    A = _x(9, toy["placement_A"]["offloaded_layers_1based"])
+    t, st = orbit.orbit_model_latency([4, 6], A, 3.0, [1.0] * 9)
+    assert abs(st.sum() * 3.0 - 12.0) < 1e-9
+
+
+def test_library_search_matches_brute_force_and_picks_the_papers_plan():
+    toy = _toy()
+    L, cap, bw, comp = toy["n_layers"], toy["gpu_blocks"], 3.0, [1.0] * toy["n_layers"]
+    # step 1: keep the short request resident, offload 3 evenly spaced layers of the long one (placement B)
+    t, x, evals = orbit.orbit_plan_search([3, 6], L, cap, bw, comp)
+    assert t == 9.0 and x.tolist() == _x(L, [[], [3, 6, 9]]).tolist()
+    # step 16: B no longer fits; whatever is chosen is feasible and no slower than uniform placement A
+    t16, x16, _ = orbit.orbit_plan_search([4, 6], L, cap, bw, comp)
+    assert ref.feasible([4, 6], x16, cap)
+    assert t16 <= lm.simulate_prefetch(_x(L, [[3, 6, 9], [3, 6, 9]]), [4, 6], bw, comp)[0] + 1e-9
+    rng = np.random.default_rng(2)
+    for _ in range(12):
+        n_req, L = int(rng.integers(1, 4)), int(rng.integers(2, 9))
+        b = rng.integers(1, 30, size=n_req)
+        comp = rng.uniform(0.5, 2.0, size=L)
+        bw = float(rng.uniform(1.0, 10.0))
+        slots = int(rng.integers(1, 3))
+        cap = int(b.sum() * L * rng.uniform(0.3, 1.1))
+        tw, xw = lm.exhaustive_search(b, L, cap, slots, bw, comp)
+        if xw is None:
+            with pytest.raises(orbit.OrbitError) as e:
+                orbit.orbit_plan_search(b, L, cap, bw, comp, prefetch_slots=slots)
+            assert e.value.code == orbit.ORBIT_E_CAPACITY
+            continue
+        t, x, _ = orbit.orbit_plan_search(b, L, cap, bw, comp, prefetch_slots=slots)
+        assert abs(t - tw) <= 1e-9 * tw and x.tolist() == xw.tolist()
+
+
+def test_descent_mode_is_feasible_and_not_worse_than_uniform():
+    rng = np.random.default_rng(3)
+    L, n_req = 32, 16
+    b = rng.integers(512, 2048, size=n_req)
+    comp = np.full(L, 0.25)
+    bw = 900.0
+    cap = int(b.sum() * L * 0.8)
+    t, x, evals = orbit.orbit_plan_search(b, L, cap, bw, comp, prefetch_slots=2, max_evals=10000)
+    assert ref.feasible(b, x, cap, 2) and evals < 10000
+    best_uniform = min(lm.simulate_prefetch(np.tile(lm.distance_pattern(L, c), (n_req, 1)), b, bw, comp)[0]
+                       for c in lm.candidate_counts(L)
+                       if ref.feasible(b, np.tile(lm.distance_pattern(L, c), (n_req, 1)), cap, 2))
+    assert t <= best_uniform + 1e-9
+    assert abs(t - lm.simulate_prefetch(x, b, bw, comp)[0]) <= 1e-9 * t

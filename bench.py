@@ -212,6 +212,30 @@ def main():
                 "attn_ms_per_step": float(np.sum(attn_ms) / K),
                 "overlap_efficiency": max(float(np.mean(copy_ms)), float(np.sum(attn_ms) / K)) / ms_per_step_events}
 
+    # the planner's cost model fed with what was just measured (per-layer compute time, link rate):
+    # its prediction for this placement against the observed step, and the plan its pruned search
+    # would pick under the same block budget
+    planner = None
+    if link_bytes:
+        from paper_2601_10729_amd import orbit_model_latency, orbit_plan_search
+        per_layer = np.asarray(attn_ms, dtype=np.float64).reshape(K, L).mean(axis=0) + \
+            np.asarray(comb_ms, dtype=np.float64).reshape(K, L).mean(axis=0)
+        blocks_per_ms = (link_bytes / (sum(copy_ms) * 1e-3) / 1e3) / w.page_bytes
+        b_now = -(-(w.ctx_len.astype(np.int64) + W + 2 * K) // w.page_tokens)
+        pred, _ = orbit_model_latency(b_now, w.placement, blocks_per_ms, per_layer)
+        t_s = time.perf_counter()
+        try:
+            t_plan, x_plan, evals = orbit_plan_search(b_now, L, need, blocks_per_ms,
+                                                      per_layer, prefetch_slots=slots, max_evals=20000)
+            planner = {"predicted_ms_for_this_placement": pred, "observed_ms": ms_per_step_events,
+                       "relative_gap": abs(pred - ms_per_step_events) / pred,
+                       "searched_plan_predicted_ms": t_plan, "searched_plan_resident_fraction":
+                       float((x_plan * b_now[:, None]).sum() / (b_now.sum() * L)),
+                       "search_budget_blocks": need, "search_evaluations": evals, "search_ms": (time.perf_counter() - t_s) * 1e3}
+        except Exception as e:                                   # infeasible under the pruned space
+            planner = {"predicted_ms_for_this_placement": pred, "observed_ms": ms_per_step_events,
+                       "relative_gap": abs(pred - ms_per_step_events) / pred, "search": str(e)}
+
     # all-resident variant of the same workload: the kernel's HBM rate without the link in the way
     resident = None
     if not args.no_resident_variant and args.placement == "workload" and not w.placement.all() and fits_resident:
@@ -256,6 +280,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "host_link": link,
+        "planner_model": planner,
         "all_resident_variant": resident,
         "ms_per_step_with_events": ms_per_step_events,
         "setup_seconds": setup_s,

@@ -237,6 +237,31 @@ ORBIT_API int orbit_plan_search(int32_t n_req, int32_t n_layers, const int64_t *
                                 int32_t prefetch_slots, double blocks_per_time, const double *comp,
                                 int64_t max_evals, uint8_t *bitmap_out, double *t_batch, int64_t *evals_out);
 
+/* ---- Token-Deposit and profile refresh (host only; Section 3.2 and Section 3.4) --------------- */
+
+typedef struct orbit_deposit orbit_deposit;
+
+/* One request's deposit: a FIFO of 4-byte token ids released at the SLO rate.  Times are doubles
+ * in any unit; slo_interval > 0 in the same unit. */
+ORBIT_API int orbit_deposit_create(double slo_interval, orbit_deposit **out);
+ORBIT_API int orbit_deposit_destroy(orbit_deposit *d);
+/* A token was generated at time `now` (non-decreasing across calls). */
+ORBIT_API int orbit_deposit_push(orbit_deposit *d, int32_t token, double now);
+/* The request finished at `now`: whatever is still deposited becomes due at once. */
+ORBIT_API int orbit_deposit_finish(orbit_deposit *d, double now);
+/* Delivers, in order, every token due by `now`: one per SLO interval while tokens are deposited,
+ * immediately on generation when the deposit was empty.  Writes up to cap tokens and their
+ * delivery times (the instant each became due, not `now`); returns how many, or a negative error. */
+ORBIT_API int64_t orbit_deposit_release(orbit_deposit *d, double now, int32_t *tokens_out, double *times_out,
+                                        int64_t cap);
+/* out4: {tokens waiting, tokens delivered, user-visible interval violations, largest size seen}. */
+ORBIT_API int orbit_deposit_stats(orbit_deposit *d, int64_t *out4);
+
+/* Profile-mismatch trigger: returns 1 if |predicted - observed| > fraction * predicted, else 0. */
+ORBIT_API int orbit_profile_mismatch(double predicted, double observed, double fraction);
+/* profile[i] <- (1 - weight) * profile[i] + weight * observed[i], 0 <= weight <= 1. */
+ORBIT_API int orbit_profile_ewma(double *profile, const double *observed, int64_t n, double weight);
+
 /* ---- host-side introspection (integers only; used by tests) --------------------------------- */
 
 /* Page ids that attention reads for (req_id, layer): arena ids for a resident block list,

@@ -66,7 +66,9 @@ EXPORTS = ["orbit_create", "orbit_destroy", "orbit_last_error", "orbit_plan_chec
            "orbit_get_plan_info", "orbit_request_pause", "orbit_request_drop", "orbit_kv_fill", "orbit_kv_read", "orbit_kv_append", "orbit_kv_prefetch",
            "orbit_decode_attention", "orbit_step", "orbit_get_pages", "orbit_get_work_items",
            "orbit_get_copy_schedule", "orbit_distance_options", "orbit_distance_pattern", "orbit_model_latency",
-           "orbit_plan_search"]
+           "orbit_plan_search", "orbit_deposit_create", "orbit_deposit_destroy", "orbit_deposit_push",
+           "orbit_deposit_finish", "orbit_deposit_release", "orbit_deposit_stats", "orbit_profile_mismatch",
+           "orbit_profile_ewma"]
 
 _lib = None
 
@@ -108,6 +110,15 @@ def lib() -> C.CDLL:
     L.orbit_distance_pattern.argtypes = [i32, i32, u8p]
     L.orbit_model_latency.argtypes = [i32, i32, i64p, u8p, C.c_double, f64p, f64p, f64p]
     L.orbit_plan_search.argtypes = [i32, i32, i64p, i64, i32, C.c_double, f64p, i64, u8p, f64p, i64p]
+    L.orbit_deposit_create.argtypes = [C.c_double, C.POINTER(vp)]
+    L.orbit_deposit_destroy.argtypes = [vp]
+    L.orbit_deposit_push.argtypes = [vp, i32, C.c_double]
+    L.orbit_deposit_finish.argtypes = [vp, C.c_double]
+    L.orbit_deposit_release.argtypes = [vp, C.c_double, i32p, f64p, i64]
+    L.orbit_deposit_release.restype = i64
+    L.orbit_deposit_stats.argtypes = [vp, i64p]
+    L.orbit_profile_mismatch.argtypes = [C.c_double, C.c_double, C.c_double]
+    L.orbit_profile_ewma.argtypes = [f64p, f64p, i64, C.c_double]
     for name in EXPORTS:
         fn = getattr(L, name)
         if fn.restype is C.c_int:
@@ -196,6 +207,60 @@ def orbit_plan_search(blocks, n_layers: int, gpu_blocks: int, blocks_per_time: f
     if rc != 0:
         raise OrbitError(rc, "orbit_plan_search: no feasible placement" if rc == ORBIT_E_CAPACITY else "orbit_plan_search")
     return t.value, _unbitmap(bm, n_layers), ev.value
+
+
+class TokenDeposit:
+    """One request's Token-Deposit (orbit_deposit_* calls)."""
+
+    def __init__(self, slo_interval: float):
+        self._L = lib()
+        h = C.c_void_p()
+        rc = self._L.orbit_deposit_create(float(slo_interval), C.byref(h))
+        if rc != 0:
+            raise OrbitError(rc, "orbit_deposit_create")
+        self._h = h
+
+    def push(self, token: int, now: float):
+        rc = self._L.orbit_deposit_push(self._h, int(token), float(now))
+        if rc != 0:
+            raise OrbitError(rc, "orbit_deposit_push")
+
+    def finish(self, now: float):
+        self._L.orbit_deposit_finish(self._h, float(now))
+
+    def release(self, now: float, cap: int = 4096):
+        toks, times = np.zeros(cap, dtype=np.int32), np.zeros(cap, dtype=np.float64)
+        n = self._L.orbit_deposit_release(self._h, float(now), toks.ctypes.data_as(C.POINTER(C.c_int32)),
+                                          times.ctypes.data_as(C.POINTER(C.c_double)), cap)
+        if n < 0:
+            raise OrbitError(int(n), "orbit_deposit_release")
+        return toks[:n].tolist(), times[:n].tolist()
+
+    def stats(self) -> dict:
+        out = np.zeros(4, dtype=np.int64)
+        self._L.orbit_deposit_stats(self._h, out.ctypes.data_as(C.POINTER(C.c_int64)))
+        return dict(waiting=int(out[0]), delivered=int(out[1]), visible_violations=int(out[2]), max_size=int(out[3]))
+
+    def __del__(self):
+        try:
+            if self._h:
+                self._L.orbit_deposit_destroy(self._h)
+                self._h = None
+        except Exception:
+            pass
+
+
+def orbit_profile_mismatch(predicted: float, observed: float, fraction: float) -> bool:
+    return bool(lib().orbit_profile_mismatch(float(predicted), float(observed), float(fraction)))
+
+
+def orbit_profile_ewma(profile, observed, weight: float) -> np.ndarray:
+    p, o = _np(profile, np.float64).copy(), _np(observed, np.float64)
+    rc = lib().orbit_profile_ewma(p.ctypes.data_as(C.POINTER(C.c_double)), o.ctypes.data_as(C.POINTER(C.c_double)),
+                                  len(p), float(weight))
+    if rc != 0:
+        raise OrbitError(rc, "orbit_profile_ewma")
+    return p
 
 
 class OrbitContext:

@@ -15,6 +15,7 @@
 #include "orbit_host.hpp"
 #include "orbit_kernels.h"
 #include "orbit_planner.hpp"
+#include "orbit_deposit.hpp"
 
 using namespace orbit;
 
@@ -22,6 +23,10 @@ namespace {
 std::string g_create_error;
 constexpr int kDefaultChunkTokens = 1024;
 }  // namespace
+
+struct orbit_deposit {
+  Deposit d;
+};
 
 struct orbit_ctx {
   orbit_config cfg{};
@@ -309,6 +314,53 @@ int orbit_plan_check(int32_t n_req, int32_t n_layers, int32_t page_tokens, const
   out4[1] = e.buffer;
   out4[2] = e.resident + (int64_t)prefetch_slots * e.buffer;
   out4[3] = e.host;
+  return ORBIT_OK;
+}
+
+int orbit_deposit_create(double slo_interval, orbit_deposit **out) {
+  if (!out || !(slo_interval > 0.0)) return ORBIT_E_INVAL;
+  *out = new orbit_deposit();
+  (*out)->d.slo = slo_interval;
+  return ORBIT_OK;
+}
+int orbit_deposit_destroy(orbit_deposit *d) {
+  if (!d) return ORBIT_E_INVAL;
+  delete d;
+  return ORBIT_OK;
+}
+int orbit_deposit_push(orbit_deposit *d, int32_t token, double now) {
+  if (!d) return ORBIT_E_INVAL;
+  if (d->d.finished) return ORBIT_E_STATE;
+  if (!d->d.gen.empty() && now < d->d.gen.back()) return ORBIT_E_INVAL;
+  d->d.push(token, now);
+  return ORBIT_OK;
+}
+int orbit_deposit_finish(orbit_deposit *d, double now) {
+  if (!d) return ORBIT_E_INVAL;
+  d->d.finished = true;
+  d->d.finish_time = now;
+  return ORBIT_OK;
+}
+int64_t orbit_deposit_release(orbit_deposit *d, double now, int32_t *tokens_out, double *times_out, int64_t cap) {
+  if (!d || cap < 0 || (cap > 0 && (!tokens_out || !times_out))) return ORBIT_E_INVAL;
+  int64_t n = 0;
+  while (n < cap && d->d.pop_due(now, tokens_out + n, times_out + n)) ++n;
+  return n;
+}
+int orbit_deposit_stats(orbit_deposit *d, int64_t *out4) {
+  if (!d || !out4) return ORBIT_E_INVAL;
+  out4[0] = (int64_t)d->d.tok.size();
+  out4[1] = d->d.delivered;
+  out4[2] = d->d.visible_violations;
+  out4[3] = d->d.max_size;
+  return ORBIT_OK;
+}
+int orbit_profile_mismatch(double predicted, double observed, double fraction) {
+  return profile_mismatch(predicted, observed, fraction) ? 1 : 0;
+}
+int orbit_profile_ewma(double *profile, const double *observed, int64_t n, double weight) {
+  if (n < 0 || (n > 0 && (!profile || !observed)) || !(weight >= 0.0 && weight <= 1.0)) return ORBIT_E_INVAL;
+  profile_ewma(profile, observed, n, weight);
   return ORBIT_OK;
 }
 

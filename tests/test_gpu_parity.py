@@ -270,3 +270,23 @@ def test_pause_evict_resume_keeps_kv_bit_exact():
         kw, vw = gen_kv(w.seed, l, victim, 0, 1500, w.n_kv_heads, w.head_dim, "cpu")
         assert torch.equal(k.cpu(), kw) and torch.equal(v.cpu(), vw)
     g.close()
+
+
+def test_many_small_requests_cross_the_append_batch_boundary():
+    """130 requests (more than one append launch holds), lengths 1..130, alternating placement."""
+    h = _harness()
+    n = 130
+    lens = [1 + i for i in range(n)]
+    pl = np.array([[i % 2, (i + 1) % 2] for i in range(n)], dtype=np.uint8)
+    w = _custom(lens, L=2, placement=pl, steps=2)
+    g = h.GpuRun(w, prefetch_slots=2)
+    o = h.OracleRun(w, extra_tokens=2)
+    for s in range(2):
+        out, _ = g.step(s)
+        o.append_all()
+    for layer in range(2):
+        _check(out[layer], None, o.attention(layer, 1))
+    k, v = g.read_kv(129, 1, 0, 132)
+    ko, vo = o.store.read(int(w.req_ids[129]), 1, 0, 132)
+    assert np.array_equal(k.cpu().view(torch.int16).numpy().view(np.uint16), ko)
+    g.close()

@@ -422,3 +422,28 @@ def test_paused_blocks_leave_a_growing_staging_region():
         p = c.get_pages(2, l)
         assert p["tier"] == 0 or max(p["pages"]) < 70
     assert info["evicted_blocks"] in (25, 50) and info["evicted_blocks"] + info["paused_resident_blocks"] == 50
+
+
+def test_empty_batch_and_bad_calls():
+    c = ctx(L=2)
+    with pytest.raises(OrbitError) as e:
+        c.step(None, None, None, None)                                # no plan yet
+    assert e.value.code == orbit.ORBIT_E_STATE
+    c.plan_load([], [], np.zeros((0, 2), dtype=np.uint8))             # an empty batch is a valid plan
+    assert c.get_plan_info()["n_requests"] == 0
+    for call in (lambda: c.step(None, None, None, None), lambda: c.decode_attention(0, None, None)):
+        with pytest.raises(OrbitError) as e:
+            call()
+        assert e.value.code == orbit.ORBIT_E_STATE
+    with pytest.raises(OrbitError) as e:
+        c.kv_prefetch(5)
+    assert e.value.code == orbit.ORBIT_E_INVAL
+    with pytest.raises(OrbitError) as e:
+        c.kv_append(1, 0, 1, 1)
+    assert e.value.code == orbit.ORBIT_E_NOT_FOUND
+    with pytest.raises(OrbitError) as e:
+        c.plan_load(list(range(9)), [1] * 9, np.ones((9, 2), dtype=np.uint8))   # max_requests is 8
+    assert e.value.code == orbit.ORBIT_E_INVAL
+    with pytest.raises(OrbitError) as e:
+        c.plan_load([1], [8193], np.ones((1, 2), dtype=np.uint8))               # beyond max_tokens_per_request
+    assert e.value.code == orbit.ORBIT_E_INVAL

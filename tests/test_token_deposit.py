@@ -1,0 +1,89 @@
+"""Token-Deposit: hand-worked cases of the release rule pin the oracle; the library's FIFO is then
+compared with it on random traces and polling patterns.  Profile refresh helpers.  CPU only."""
+import numpy as np
+import pytest
+
+import paper_2601_10729_amd as orbit
+from oracle import token_deposit as td
+
+
+def test_rule_hand_worked_cases():
+    # generation faster than the SLO: the deposit fills and delivery is one token per interval
+    assert td.delivery_times([0.0, 0.1, 0.2, 0.3], 1.0) == [0.0, 1.0, 2.0, 3.0]
+    # generation slower than the SLO: the deposit stays empty, every token goes out on generation
+    assert td.delivery_times([0.0, 2.0, 5.0], 1.0) == [0.0, 2.0, 5.0]
+    assert td.summary([0.0, 2.0, 5.0], 1.0) == (2, 2)
+    # early margin masks a later slow stretch: four quick tokens, then gaps of 2 intervals
+    gen = [0.0, 0.1, 0.2, 0.3, 2.3, 4.3, 6.3]
+    assert td.delivery_times(gen, 1.0) == [0.0, 1.0, 2.0, 3.0, 4.0, 5.0, 6.3]
+    assert td.summary(gen, 1.0) == (1, 3)                # three backend violations, one seen
+    # finish: what is still deposited leaves in one burst at the finish time
+    assert td.delivery_times([0.0, 0.1, 0.2, 0.3], 1.0, finish=1.5) == [0.0, 1.0, 1.5, 1.5]
+
+
+def test_deposit_never_adds_violations_and_keeps_order():
+    rng = np.random.default_rng(0)
+    for _ in range(100):
+        n = int(rng.integers(1, 60))
+        gen = np.cumsum(rng.exponential(rng.uniform(0.2, 2.0), size=n))
+        d = td.delivery_times(gen, 1.0)
+        assert all(b >= a for a, b in zip(d, d[1:])) and all(x >= g for x, g in zip(d, gen))
+        seen, backend = td.summary(gen, 1.0)
+        assert seen <= backend
+
+
+def test_library_fifo_matches_the_rule():
+    rng = np.random.default_rng(1)
+    for trial in range(60):
+        n = int(rng.integers(1, 80))
+        slo = float(rng.uniform(0.5, 2.0))
+        gen = np.cumsum(rng.exponential(rng.uniform(0.2, 2.5), size=n))
+        finish = float(gen[-1]) if trial % 2 else None
+        dep = orbit.TokenDeposit(slo)
+        polls = np.sort(rng.uniform(0, gen[-1] + n * slo + 1, size=int(rng.integers(1, 40))))
+        got_tok, got_t, gi = [], [], 0
+        events = sorted([(t, 0) for t in gen] + [(t, 1) for t in polls])
+        for t, kind in events:
+            if kind == 0:
+                dep.push(1000 + gi, t)
+                gi += 1
+                if gi == n and finish is not None:
+                    dep.finish(finish)
+            else:
+                a, b = dep.release(t)
+                got_tok += a
+                got_t += b
+        a, b = dep.release(1e18)
+        got_tok += a
+        got_t += b
+        want = td.delivery_times(list(gen), slo, finish)
+        assert got_tok == [1000 + i for i in range(n)]
+        np.testing.assert_allclose(got_t, want, rtol=0, atol=1e-9)
+        st = dep.stats()
+        assert st["waiting"] == 0 and st["delivered"] == n
+        assert st["visible_violations"] == td.violations(want, slo)
+
+
+def test_release_respects_time_and_capacity():
+    dep = orbit.TokenDeposit(1.0)
+    for i, t in enumerate([0.0, 0.1, 0.2]):
+        dep.push(i, t)
+    assert dep.release(0.5) == ([0], [0.0])
+    assert dep.release(0.9) == ([], [])
+    assert dep.release(2.5, cap=1) == ([1], [1.0])
+    assert dep.stats()["waiting"] == 1 and dep.stats()["max_size"] == 3
+    with pytest.raises(orbit.OrbitError):
+        dep.push(9, 0.05)                                    # time runs backwards
+    dep.finish(2.6)
+    with pytest.raises(orbit.OrbitError):
+        dep.push(9, 3.0)                                     # finished
+    assert dep.release(2.6) == ([2], [2.0])
+
+
+def test_profile_refresh_helpers():
+    assert orbit.orbit_profile_mismatch(100.0, 131.0, 0.3) and not orbit.orbit_profile_mismatch(100.0, 129.0, 0.3)
+    assert orbit.orbit_profile_mismatch(100.0, 60.0, 0.3)
+    p = orbit.orbit_profile_ewma([1.0, 2.0, 4.0], [3.0, 2.0, 0.0], 0.25)
+    np.testing.assert_allclose(p, [1.5, 2.0, 3.0])
+    with pytest.raises(orbit.OrbitError):
+        orbit.orbit_profile_ewma([1.0], [1.0], 1.5)

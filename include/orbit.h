@@ -142,16 +142,19 @@ ORBIT_API int orbit_plan_check(int32_t n_req, int32_t n_layers, int32_t page_tok
  *   hbm_budget_bytes  B_GPU = floor(min(budget, arena) / page bytes).
  * Checks Eq. (1) (ORBIT_E_CAPACITY) and the host arena (ORBIT_E_HOST_CAPACITY); on any error
  * NOTHING changes.  On success it moves only the blocks whose tier changed, plus resident
- * blocks that sit where the new contiguous staging region goes, rebuilds the tables, and
- * returns after both streams have drained (this call synchronises). */
+ * blocks that sit where the new contiguous staging region goes, and rebuilds the tables.
+ * The host does not wait for the GPU (no stream or device synchronisation, as Section 4 asks):
+ * the migrations are enqueued on copy_stream behind everything already enqueued on
+ * compute_stream, and compute_stream waits for them before any later call's work.
+ * ORBIT_E_STATE if a prefetched layer has not been attended yet. */
 ORBIT_API int orbit_plan_load(orbit_ctx *ctx, int32_t n_req, const int64_t *req_ids, const int32_t *ctx_len,
                     const uint8_t *placement_bitmap, int64_t hbm_budget_bytes);
 
 ORBIT_API int orbit_get_plan_info(orbit_ctx *ctx, orbit_plan_info *out);
 
 /* Pause-Resume (Section 3.4) with the removable cache of Section 4.  orbit_request_pause takes an
- * active request out of the batch (the other requests keep their placement; tables are rebuilt;
- * this call synchronises like orbit_plan_load) but leaves its KV where it is.  Its HBM blocks no
+ * active request out of the batch (the other requests keep their placement; tables are rebuilt,
+ * stream-ordered like orbit_plan_load) but leaves its KV where it is.  Its HBM blocks no
  * longer count against Eq. (1): a later orbit_plan_load that needs the room evicts them to the
  * host arena one layer at a time, only as many as needed.  A paused request is resumed by
  * listing it in orbit_plan_load again (only layers that were evicted and are wanted in HBM move

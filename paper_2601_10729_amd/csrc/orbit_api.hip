@@ -37,8 +37,12 @@ struct orbit_ctx {
   uint8_t *host_dev = nullptr;  // device-visible address of the pinned host arena
   int32_t *d_table = nullptr, *d_len = nullptr, *d_items = nullptr;
   float *d_pacc = nullptr, *d_pml = nullptr;
-  BlitOp *d_ops = nullptr;
+  BlitOp *d_ops = nullptr;            // device list of page copies of the last plan switch
+  BlitOp *h_ops_pinned = nullptr;     // its pinned staging copy
   size_t d_ops_cap = 0;
+  int32_t *h_tab_pinned = nullptr, *h_len_pinned = nullptr;  // pinned snapshots the table uploads read
+  hipEvent_t ev_ops = nullptr, ev_tab = nullptr;             // last use of the staging copies
+  hipEvent_t ev_plan_c = nullptr, ev_plan_x = nullptr;       // stream ordering of a plan switch
   int32_t *h_items_pinned[2] = {nullptr, nullptr};
   hipEvent_t ev_items[2] = {nullptr, nullptr};
   int items_buf = 0;
@@ -242,52 +246,66 @@ int check_layer(orbit_ctx *c, int layer) {
   return ORBIT_OK;
 }
 
-int run_phases(orbit_ctx *c, const std::vector<std::vector<PageOp>> &phases) {
+// GPU side of a plan switch, without any host-side stream synchronisation: the copy stream first
+// waits for everything already enqueued on the compute stream, then runs the page migrations
+// (one blit per phase, in order); the compute stream waits for them and then receives the new
+// page table and lengths.  The pinned staging copies are reused only after their last transfer.
+int apply_plan_gpu(orbit_ctx *c, const std::vector<std::vector<PageOp>> &phases) {
+  if (c->host_only) return ORBIT_OK;
   const HostState &hs = c->hs;
+  const Shape &sh = hs.sh;
+  HIPCHECK(c, hipEventRecord(c->ev_plan_c, c->cs));
+  HIPCHECK(c, hipStreamWaitEvent(c->xs, c->ev_plan_c, 0));
   size_t total = 0;
   for (auto &ph : phases) total += ph.size();
-  if (total == 0 || c->host_only) return ORBIT_OK;
-  if (total > c->d_ops_cap) {
-    if (c->d_ops) HIPCHECK(c, hipFree(c->d_ops));
-    c->d_ops = nullptr;
-    c->d_ops_cap = 0;
-    HIPCHECK(c, hipMalloc((void **)&c->d_ops, total * sizeof(BlitOp)));
-    c->d_ops_cap = total;
-  }
-  std::vector<BlitOp> ops;
-  ops.reserve(total);
-  const int64_t pb = hs.sh.page_bytes;
-  auto hbm = [&](int64_t p) { return (uint64_t)(uintptr_t)(c->arena + p * pb); };
-  auto hst = [&](int64_t p) { return (uint64_t)(uintptr_t)(c->host_dev + p * pb); };
-  for (auto &ph : phases)
-    for (const PageOp &op : ph) {
-      BlitOp b{};
-      switch (op.kind) {
-        case OP_HBM_TO_HOST: b.src = hbm(op.src); b.dst = hst(op.dst); break;
-        case OP_HOST_TO_HBM: b.src = hst(op.src); b.dst = hbm(op.dst); break;
-        case OP_HBM_TO_HBM: b.src = hbm(op.src); b.dst = hbm(op.dst); break;
-        default: b.src = hst(op.src); b.dst = hst(op.dst); break;
-      }
-      ops.push_back(b);
+  if (total > 0) {
+    HIPCHECK(c, hipEventSynchronize(c->ev_ops));
+    if (total > c->d_ops_cap) {
+      const size_t cap = std::max(total, 2 * c->d_ops_cap);
+      if (c->d_ops) HIPCHECK(c, hipFree(c->d_ops));
+      if (c->h_ops_pinned) HIPCHECK(c, hipHostFree(c->h_ops_pinned));
+      c->d_ops = nullptr;
+      c->h_ops_pinned = nullptr;
+      c->d_ops_cap = 0;
+      HIPCHECK(c, hipMalloc((void **)&c->d_ops, cap * sizeof(BlitOp)));
+      HIPCHECK(c, hipHostMalloc((void **)&c->h_ops_pinned, cap * sizeof(BlitOp), hipHostMallocDefault));
+      c->d_ops_cap = cap;
     }
-  HIPCHECK(c, hipMemcpy(c->d_ops, ops.data(), total * sizeof(BlitOp), hipMemcpyHostToDevice));
-  size_t at = 0;
-  for (auto &ph : phases) {
-    if (ph.empty()) continue;
-    HIPCHECK(c, launch_blit(c->d_ops + at, (int64_t)ph.size(), pb, c->xs));  // phases run in stream order
-    at += ph.size();
+    const int64_t pb = sh.page_bytes;
+    auto hbm = [&](int64_t p) { return (uint64_t)(uintptr_t)(c->arena + p * pb); };
+    auto hst = [&](int64_t p) { return (uint64_t)(uintptr_t)(c->host_dev + p * pb); };
+    size_t n = 0;
+    for (auto &ph : phases)
+      for (const PageOp &op : ph) {
+        BlitOp b{};
+        switch (op.kind) {
+          case OP_HBM_TO_HOST: b.src = hbm(op.src); b.dst = hst(op.dst); break;
+          case OP_HOST_TO_HBM: b.src = hst(op.src); b.dst = hbm(op.dst); break;
+          case OP_HBM_TO_HBM: b.src = hbm(op.src); b.dst = hbm(op.dst); break;
+          default: b.src = hst(op.src); b.dst = hst(op.dst); break;
+        }
+        c->h_ops_pinned[n++] = b;
+      }
+    HIPCHECK(c, hipMemcpyAsync(c->d_ops, c->h_ops_pinned, total * sizeof(BlitOp), hipMemcpyHostToDevice, c->xs));
+    size_t at = 0;
+    for (auto &ph : phases) {
+      if (ph.empty()) continue;
+      HIPCHECK(c, launch_blit(c->d_ops + at, (int64_t)ph.size(), pb, c->xs));  // phases run in stream order
+      at += ph.size();
+    }
+    HIPCHECK(c, hipEventRecord(c->ev_ops, c->xs));
   }
-  HIPCHECK(c, hipStreamSynchronize(c->xs));
-  return ORBIT_OK;
-}
-
-int upload_tables(orbit_ctx *c) {
-  const int n_req = (int)c->hs.reqs.size();
-  if (!c->host_only && n_req > 0) {
-    const Shape &sh = c->hs.sh;
-    HIPCHECK(c, hipMemcpy(c->d_table, c->hs.h_table.data(), (size_t)n_req * sh.L * sh.cap_pages * sizeof(int32_t),
-                          hipMemcpyHostToDevice));
-    HIPCHECK(c, hipMemcpy(c->d_len, c->hs.h_len.data(), (size_t)n_req * sh.L * sizeof(int32_t), hipMemcpyHostToDevice));
+  HIPCHECK(c, hipEventRecord(c->ev_plan_x, c->xs));
+  HIPCHECK(c, hipStreamWaitEvent(c->cs, c->ev_plan_x, 0));
+  const size_t n_req = hs.reqs.size();
+  if (n_req > 0) {
+    const size_t nt = n_req * sh.L * sh.cap_pages, nl = n_req * sh.L;
+    HIPCHECK(c, hipEventSynchronize(c->ev_tab));
+    std::memcpy(c->h_tab_pinned, hs.h_table.data(), nt * sizeof(int32_t));
+    std::memcpy(c->h_len_pinned, hs.h_len.data(), nl * sizeof(int32_t));
+    HIPCHECK(c, hipMemcpyAsync(c->d_table, c->h_tab_pinned, nt * sizeof(int32_t), hipMemcpyHostToDevice, c->cs));
+    HIPCHECK(c, hipMemcpyAsync(c->d_len, c->h_len_pinned, nl * sizeof(int32_t), hipMemcpyHostToDevice, c->cs));
+    HIPCHECK(c, hipEventRecord(c->ev_tab, c->cs));
   }
   return ORBIT_OK;
 }
@@ -508,6 +526,12 @@ int orbit_create(const orbit_config *cfg, orbit_ctx **out) {
       CREATE_CHECK(hipHostMalloc((void **)&p->h_items_pinned[b], (size_t)c->slots * 4 * sizeof(int32_t), hipHostMallocDefault));
       CREATE_CHECK(hipEventCreateWithFlags(&p->ev_items[b], hipEventDisableTiming));
     }
+    CREATE_CHECK(hipHostMalloc((void **)&p->h_tab_pinned, c->hs.h_table.size() * sizeof(int32_t), hipHostMallocDefault));
+    CREATE_CHECK(hipHostMalloc((void **)&p->h_len_pinned, c->hs.h_len.size() * sizeof(int32_t), hipHostMallocDefault));
+    CREATE_CHECK(hipEventCreateWithFlags(&p->ev_ops, hipEventDisableTiming));
+    CREATE_CHECK(hipEventCreateWithFlags(&p->ev_tab, hipEventDisableTiming));
+    CREATE_CHECK(hipEventCreateWithFlags(&p->ev_plan_c, hipEventDisableTiming));
+    CREATE_CHECK(hipEventCreateWithFlags(&p->ev_plan_x, hipEventDisableTiming));
     CREATE_CHECK(hipEventCreateWithFlags(&p->ev_tmp, hipEventDisableTiming));
     CREATE_CHECK(hipEventCreate(&p->t_step0));
     CREATE_CHECK(hipEventCreate(&p->t_step1));
@@ -540,6 +564,11 @@ int orbit_destroy(orbit_ctx *c) {
     (void)hipFree(c->d_pacc);
     (void)hipFree(c->d_pml);
     (void)hipFree(c->d_ops);
+    if (c->h_ops_pinned) (void)hipHostFree(c->h_ops_pinned);
+    if (c->h_tab_pinned) (void)hipHostFree(c->h_tab_pinned);
+    if (c->h_len_pinned) (void)hipHostFree(c->h_len_pinned);
+    for (hipEvent_t e : {c->ev_ops, c->ev_tab, c->ev_plan_c, c->ev_plan_x})
+      if (e) (void)hipEventDestroy(e);
     for (int b = 0; b < 2; ++b) {
       if (c->h_items_pinned[b]) (void)hipHostFree(c->h_items_pinned[b]);
       if (c->ev_items[b]) (void)hipEventDestroy(c->ev_items[b]);
@@ -564,33 +593,27 @@ int orbit_destroy(orbit_ctx *c) {
 int orbit_plan_load(orbit_ctx *c, int32_t n_req, const int64_t *req_ids, const int32_t *ctx_len,
                     const uint8_t *placement_bitmap, int64_t hbm_budget_bytes) {
   if (!c) return ORBIT_E_INVAL;
-  if (!c->host_only) {
-    HIPCHECK(c, hipStreamSynchronize(c->cs));
-    HIPCHECK(c, hipStreamSynchronize(c->xs));
-  }
+  for (auto &lb : c->hs.live)
+    if (!lb.consumed) return set_err(c, ORBIT_E_STATE, "a prefetched layer was never attended; finish it before a new plan");
   std::vector<std::vector<PageOp>> phases;
   int rc = c->hs.plan_load(n_req, req_ids, ctx_len, placement_bitmap, hbm_budget_bytes, phases);
   if (rc) return set_err(c, rc, c->hs.err);
   c->items_valid = false;
   std::fill(c->host_dirty.begin(), c->host_dirty.end(), 0);
-  if ((rc = run_phases(c, phases))) return rc;
-  return upload_tables(c);
+  return apply_plan_gpu(c, phases);
 }
 
 int orbit_request_pause(orbit_ctx *c, int64_t req_id) {
   if (!c) return ORBIT_E_INVAL;
   if (!c->hs.has_plan) return set_err(c, ORBIT_E_STATE, "no plan installed");
-  if (!c->host_only) {
-    HIPCHECK(c, hipStreamSynchronize(c->cs));
-    HIPCHECK(c, hipStreamSynchronize(c->xs));
-  }
+  for (auto &lb : c->hs.live)
+    if (!lb.consumed) return set_err(c, ORBIT_E_STATE, "a prefetched layer was never attended; finish it before pausing");
   std::vector<std::vector<PageOp>> phases;
   int rc = c->hs.pause(req_id, phases);
   if (rc) return set_err(c, rc, c->hs.err);
   c->items_valid = false;
   std::fill(c->host_dirty.begin(), c->host_dirty.end(), 0);
-  if ((rc = run_phases(c, phases))) return rc;
-  return upload_tables(c);
+  return apply_plan_gpu(c, phases);
 }
 
 int orbit_request_drop(orbit_ctx *c, int64_t req_id) {

@@ -105,6 +105,16 @@ struct RunAlloc {
     }
     free_[s] = n;
   }
+  // Grows the run [s, s+n) in place to `m` pages if the pages right behind it are free.
+  bool extend(int64_t s, int64_t n, int64_t m) {
+    auto it = free_.find(s + n);
+    if (m <= n) return true;
+    if (it == free_.end() || it->second < m - n) return false;
+    const int64_t len = it->second;
+    free_.erase(it);
+    if (len > m - n) free_[s + m] = len - (m - n);
+    return true;
+  }
   int64_t total_free() const {
     int64_t t = 0;
     for (auto &kv : free_) t += kv.second;
@@ -370,6 +380,10 @@ class HostState {
       for (int l = 0; l < L; ++l) {
         LayerKV &lk = nw[r].layers[l];
         if (lk.tier != 0 || x[(size_t)r * L + l] || lk.host_cap >= rb[r]) continue;
+        if (H.extend(lk.host_page0, lk.host_cap, rb[r])) {  // room right behind the run: no copy
+          lk.host_cap = (int32_t)rb[r];
+          continue;
+        }
         int64_t run = H.alloc(rb[r]);
         if (run < 0) return fail(ORBIT_E_HOST_CAPACITY, "host arena full or fragmented (growth)");
         int64_t used = ceil_div(lk.len, P);

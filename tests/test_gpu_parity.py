@@ -290,3 +290,45 @@ def test_many_small_requests_cross_the_append_batch_boundary():
     ko, vo = o.store.read(int(w.req_ids[129]), 1, 0, 132)
     assert np.array_equal(k.cpu().view(torch.int16).numpy().view(np.uint16), ko)
     g.close()
+
+
+def test_plan_switches_between_steps_without_host_sync():
+    """Steps and plan switches are enqueued back to back with no host-side wait in between; the
+    outputs equal, bit for bit, those of a run that keeps everything resident."""
+    h = _harness()
+    from workloads import gen_q_steps, gen_kv
+    w = _custom([300, 1200, 90, 2100], L=4, steps=8)
+    rng = np.random.default_rng(11)
+    plans = [rng.integers(0, 2, size=(4, 4)).astype(np.uint8) for _ in range(4)]
+    S = 8
+
+    def run(switching: bool):
+        g = h.GpuRun(w, placement=plans[0] if switching else np.ones((4, 4), np.uint8), prefetch_slots=2,
+                     budget_pages=int(w.blocks(S).sum()) * 4 * 3, host_pages=int(w.blocks(2 * S).sum()) * 4 * 2,
+                     decode_window=S, max_tokens=int(w.ctx_len.max()) + 2 * S + 16)
+        dev = g.dev
+        q = torch.stack([torch.stack([gen_q_steps(w.seed, l, int(rid), 0, S, w.n_q_heads, w.head_dim, dev)
+                                      for rid in w.req_ids], dim=1) for l in range(4)], dim=1).contiguous()
+        kv = [[gen_kv(w.seed, l, int(rid), int(w.ctx_len[r]), S, w.n_kv_heads, w.head_dim, dev)
+               for r, rid in enumerate(w.req_ids)] for l in range(4)]
+        k_new = torch.stack([torch.stack([kv[l][r][0] for r in range(4)], dim=1) for l in range(4)], dim=1).contiguous()
+        v_new = torch.stack([torch.stack([kv[l][r][1] for r in range(4)], dim=1) for l in range(4)], dim=1).contiguous()
+        outs = torch.zeros((S, 4, 4, w.n_q_heads, w.head_dim), dtype=torch.bfloat16, device=dev)
+        torch.cuda.synchronize()
+        for s in range(S):
+            if switching and s in (2, 3, 5, 6):
+                g.ctx.plan_load(w.req_ids, w.ctx_len + s, plans[(s * 7) % 4])      # no wait before or after
+            g.ctx.step(q[s], k_new[s], v_new[s], outs[s])
+        g.cs.synchronize()
+        g.xs.synchronize()
+        res = outs.cpu()
+        g.close()
+        return res
+
+    a, b = run(True), run(False)
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    o = h.OracleRun(w, extra_tokens=S)
+    for _ in range(S):
+        o.append_all()
+    for layer in range(4):
+        _check(a[S - 1, layer], None, o.attention(layer, S - 1))

@@ -52,22 +52,25 @@ def measure_link_peak(torch, nbytes=1 << 30, reps=4):
     return best
 
 
-def cpu_baseline(w, n_req_sample=16, layer=0):
-    """The oracle as it stands, timed on a bounded sample: `n_req_sample` requests x one layer x
-    all query heads, through its own paged store.  Returns GB/s of KV consumed."""
+def cpu_baseline(w, n_req_sample=16, n_layers_sample=3):
+    """The oracle as it stands, timed on a bounded sample: `n_req_sample` requests x
+    `n_layers_sample` layers x all query heads, through its own paged store.  Returns GB/s of KV
+    consumed (threads x seconds is about 10-20 core-seconds on the GPU machine's host)."""
     import dataclasses
     import harness
     from oracle import reference as ref
     n_req_sample = min(n_req_sample, w.n_req)
-    ws = dataclasses.replace(w, n_layers=layer + 1, req_ids=w.req_ids[:n_req_sample], ctx_len=w.ctx_len[:n_req_sample],
-                             placement=w.placement[:n_req_sample, :layer + 1])
-    o = harness.OracleRun(ws, layers=[layer])
+    nl = min(n_layers_sample, w.n_layers)
+    ws = dataclasses.replace(w, n_layers=nl, req_ids=w.req_ids[:n_req_sample], ctx_len=w.ctx_len[:n_req_sample],
+                             placement=w.placement[:n_req_sample, :nl])
+    o = harness.OracleRun(ws)
     t0 = time.perf_counter()
-    o.attention(layer, 0)
+    for layer in range(nl):
+        o.attention(layer, 0)
     dt = time.perf_counter() - t0
-    nbytes = int(ws.ctx_len.astype("int64").sum()) * ws.kv_bytes_per_token_layer
+    nbytes = int(ws.ctx_len.astype("int64").sum()) * ws.kv_bytes_per_token_layer * nl
     return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": ref.num_threads(), "kind": "oracle",
-            "sample": f"{n_req_sample} requests x 1 layer x {w.n_q_heads} query heads of the same workload "
+            "sample": f"{n_req_sample} requests x {nl} layers x {w.n_q_heads} query heads of the same workload "
                       f"({nbytes / 1e6:.0f} MB of KV, {dt:.2f} s)", "seconds": dt}
 
 

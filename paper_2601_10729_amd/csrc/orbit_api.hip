@@ -651,7 +651,6 @@ static int fill_or_read(orbit_ctx *c, bool write, int64_t req_id, int32_t layer,
   else fp.host_run = c->host_dev + lk.host_page0 * sh.page_bytes;
   fp.k = (uint16_t *)k;
   fp.v = (uint16_t *)v;
-  fp.len_slot = nullptr;
   fp.page_bytes = sh.page_bytes;
   fp.first_token = first;
   fp.n_tokens = n;

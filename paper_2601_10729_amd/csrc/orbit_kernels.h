@@ -54,9 +54,8 @@ struct FillParams {
   uint8_t *host_run;        // device-visible address of the host run's first page (row == NULL)
   uint16_t *k;              // token-major [n_tokens][Hkv][128] bf16 (source of fill, dest of read)
   uint16_t *v;
-  int32_t *len_slot;        // device address of lens[r][l] (fill only; may be NULL)
   int64_t page_bytes, first_token, n_tokens;
-  int32_t Hkv, new_len;
+  int32_t Hkv;
 };
 
 struct BlitOp {
@@ -69,6 +68,5 @@ hipError_t launch_append(const AppendParams &p, hipStream_t s);
 hipError_t launch_fill(const FillParams &p, hipStream_t s);
 hipError_t launch_gather(const FillParams &p, hipStream_t s);
 hipError_t launch_blit(const BlitOp *ops_dev, int64_t n_ops, int64_t page_bytes, hipStream_t s);
-hipError_t launch_set_i32(int32_t *dst, int32_t value, hipStream_t s);
 
 }  // namespace orbit

@@ -383,7 +383,6 @@ __global__ __launch_bounds__(256) void fill_kernel(const FillParams p) {
         }
     }
   }
-  if (p.len_slot && blockIdx.x == 0 && g == 0 && tid == 0) *p.len_slot = p.new_len;
 }
 
 // grid (pages touched, Hkv); page tiles -> token-major.
@@ -423,8 +422,6 @@ __global__ __launch_bounds__(256) void blit_kernel(const BlitOp *ops, int64_t un
        i += (int64_t)gridDim.y * blockDim.x)
     d[i] = s[i];
 }
-
-__global__ void set_i32_kernel(int32_t *dst, int32_t value) { *dst = value; }
 
 // ------------------------------------------------------------------------------------ launches
 
@@ -476,11 +473,6 @@ hipError_t launch_blit(const BlitOp *ops_dev, int64_t n_ops, int64_t page_bytes,
   const int64_t units = page_bytes / 16;
   const unsigned split = (unsigned)std::max<int64_t>(1, std::min<int64_t>(8, units / 1024));
   hipLaunchKernelGGL(blit_kernel, dim3((unsigned)n_ops, split), dim3(256), 0, s, ops_dev, units);
-  return hipGetLastError();
-}
-
-hipError_t launch_set_i32(int32_t *dst, int32_t value, hipStream_t s) {
-  hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(1), 0, s, dst, value);
   return hipGetLastError();
 }
 

@@ -1,0 +1,154 @@
+// Randomised exercise of the HIP-free host logic (block tables, allocators, delta migration,
+// pause / resume, work list, planner, deposit) meant to be built with
+//   g++ -std=c++17 -O1 -g -fsanitize=address,undefined
+// Every step re-checks the layout invariants; any violation aborts with a message.
+#include <cstdio>
+#include <cstdlib>
+#include <random>
+#include <set>
+
+#include "../paper_2601_10729_amd/csrc/orbit_deposit.hpp"
+#include "../paper_2601_10729_amd/csrc/orbit_host.hpp"
+#include "../paper_2601_10729_amd/csrc/orbit_planner.hpp"
+
+using namespace orbit;
+
+#define CHECK(cond)                                                        \
+  do {                                                                     \
+    if (!(cond)) {                                                         \
+      std::fprintf(stderr, "invariant failed: %s (line %d)\n", #cond, __LINE__); \
+      std::abort();                                                        \
+    }                                                                      \
+  } while (0)
+
+static void check_layout(const HostState &hs) {
+  std::set<int32_t> seen;
+  std::vector<std::pair<int64_t, int64_t>> runs;
+  auto visit = [&](const Req &q, bool active) {
+    for (int l = 0; l < hs.sh.L; ++l) {
+      const LayerKV &lk = q.layers[l];
+      CHECK(lk.tier == 0 || lk.tier == 1);
+      if (lk.tier == 1) {
+        for (int32_t p : lk.pages) {
+          CHECK(p >= 0 && p < hs.arena_pages && hs.hbm.used[p]);
+          CHECK(seen.insert(p).second);
+          CHECK(p < hs.info.staging_first_page);
+        }
+        if (active) CHECK((int)lk.pages.size() == q.reserved);
+      } else {
+        CHECK(lk.host_page0 >= 0 && lk.host_page0 + lk.host_cap <= hs.host_pages);
+        CHECK(lk.host_cap >= ceil_div(lk.len, hs.sh.P));
+        runs.push_back({lk.host_page0, lk.host_page0 + lk.host_cap});
+        if (active) {
+          CHECK(lk.stage_page0 >= hs.info.staging_first_page);
+          CHECK(lk.stage_page0 + q.reserved <= hs.info.staging_first_page + hs.info.staging_blocks);
+        }
+      }
+    }
+  };
+  for (auto &q : hs.reqs) visit(q, true);
+  for (auto &q : hs.paused) visit(q, false);
+  int64_t used = 0;
+  for (uint8_t u : hs.hbm.used) used += u;
+  CHECK(used == (int64_t)seen.size());
+  std::sort(runs.begin(), runs.end());
+  for (size_t i = 1; i < runs.size(); ++i) CHECK(runs[i - 1].second <= runs[i].first);
+  int64_t run_pages = 0;
+  for (auto &r : runs) run_pages += r.second - r.first;
+  CHECK(run_pages + hs.host.total_free() == hs.host_pages);
+  CHECK(hs.info.resident_blocks + hs.info.staging_blocks <= hs.info.budget_blocks);
+}
+
+int main(int argc, char **argv) {
+  const unsigned seed = argc > 1 ? (unsigned)std::atoi(argv[1]) : 1u;
+  const int rounds = argc > 2 ? std::atoi(argv[2]) : 300;
+  std::mt19937 rng(seed);
+  auto rnd = [&](int lo, int hi) { return lo + (int)(rng() % (unsigned)(hi - lo + 1)); };
+  Shape sh;
+  sh.L = rnd(1, 6);
+  sh.Hq = 32;
+  sh.Hkv = 8;
+  sh.G = 4;
+  sh.D = 128;
+  sh.P = 16;
+  sh.max_req = 8;
+  sh.max_tokens = 4096;
+  sh.page_bytes = 65536;
+  sh.cap_pages = 256;
+  sh.chunk_tokens = 64 * rnd(1, 8);
+  sh.max_chunks = (int)ceil_div(sh.max_tokens, sh.chunk_tokens);
+  sh.window = rnd(0, 40);
+  sh.slots = rnd(1, 3);
+  HostState hs;
+  hs.init(sh, 3000, 3000);
+  std::vector<int64_t> known_ids;
+  std::vector<int32_t> known_len;
+  int ok = 0, rejected = 0;
+  for (int it = 0; it < rounds; ++it) {
+    const int action = rnd(0, 9);
+    std::vector<std::vector<PageOp>> phases;
+    if (action <= 5 || !hs.has_plan) {  // new plan: keep some, add some, resume some
+      std::vector<int64_t> ids;
+      std::vector<int32_t> lens;
+      for (auto &q : hs.reqs)
+        if (rnd(0, 3)) { ids.push_back(q.id); lens.push_back(q.layers[0].len); }
+      for (auto &q : hs.paused)
+        if (rnd(0, 2) == 0 && (int)ids.size() < sh.max_req) { ids.push_back(q.id); lens.push_back(q.layers[0].len); }
+      while ((int)ids.size() < sh.max_req && rnd(0, 2) == 0) {
+        ids.push_back(1000 + it * 10 + (int64_t)ids.size());
+        lens.push_back(rnd(0, 1500));
+      }
+      const int n = (int)ids.size(), bpr = (sh.L + 7) / 8;
+      std::vector<uint8_t> bm((size_t)n * bpr);
+      for (auto &b : bm) b = (uint8_t)rng();
+      const int64_t budget = (int64_t)rnd(200, 3200) * sh.page_bytes;
+      int rc = hs.plan_load(n, ids.data(), lens.data(), bm.data(), budget, phases);
+      rc == 0 ? ++ok : ++rejected;
+      for (auto &ph : phases)
+        for (auto &op : ph) CHECK(op.src >= 0 && op.dst >= 0);
+    } else if (action <= 7 && !hs.reqs.empty()) {  // pause one
+      int rc = hs.pause(hs.reqs[rnd(0, (int)hs.reqs.size() - 1)].id, phases);
+      rc == 0 ? ++ok : ++rejected;
+    } else if (action == 8 && !hs.paused.empty()) {
+      CHECK(hs.drop_paused(hs.paused[rnd(0, (int)hs.paused.size() - 1)].id) == 0);
+    } else if (!hs.reqs.empty()) {  // append one token everywhere when the window allows it
+      bool room = true;
+      for (auto &q : hs.reqs) room &= q.layers[0].len / sh.P < q.reserved;
+      if (room)
+        for (auto &q : hs.reqs)
+          for (auto &lk : q.layers) lk.len += 1;
+    }
+    if (hs.has_plan) {
+      check_layout(hs);
+      std::vector<int32_t> items;
+      bool all_nonempty = !hs.reqs.empty();
+      for (auto &q : hs.reqs) all_nonempty &= q.layers[0].len > 0;
+      if (all_nonempty) {
+        CHECK(hs.build_work_items(0, items) == 0);
+        std::set<int32_t> slots;
+        for (size_t i = 0; i < items.size(); i += 4) {
+          CHECK(items[i] >= 0 && items[i] < (int)hs.reqs.size() && items[i + 1] < sh.Hkv);
+          CHECK((int64_t)items[i + 2] * sh.chunk_tokens < hs.reqs[items[i]].layers[0].len);
+          CHECK(slots.insert(items[i + 3]).second);
+        }
+      }
+    }
+  }
+  // planner and deposit under the sanitizers
+  std::vector<int64_t> b = {30, 70, 110};
+  std::vector<double> comp(8, 1.0);
+  SearchResult sr = plan_search(3, 8, b.data(), 1200, 2, 5.0, comp.data(), 5000);
+  CHECK(sr.t >= 8.0 && sr.x.size() == 24);
+  Deposit d;
+  d.slo = 1.0;
+  double t = 0;
+  int32_t tok;
+  double when;
+  for (int i = 0; i < 200; ++i) {
+    t += (rng() % 300) / 100.0;
+    d.push(i, t);
+    while (d.pop_due(t, &tok, &when)) CHECK(when <= t);
+  }
+  std::printf("host fuzz ok: seed %u, %d plan changes accepted, %d rejected\n", seed, ok, rejected);
+  return 0;
+}

@@ -77,3 +77,28 @@ def test_heavy_mixed_lengths():
     _check_groups(h, w, outs, outs32, w.ctx_len, [(0, picks[0], 1), (1, picks[0], 6), (0, picks[1], 2),
                                                   (1, picks[2], 4), (0, picks[2], 7)])
     g.close()
+
+
+def test_bench_configuration_full_step_sampled():
+    """The exact configuration bench.py times: all 32 layers of the 8B-shaped batch-16 workload
+    with its 75 %-resident placement and two staging ranges; one full orbit_step, then sampled
+    (layer, request, kv head) groups of resident and streamed layers against the oracle."""
+    import harness as h
+    from paper_2601_10729_amd import orbit_plan_check
+    w = dataclasses.replace(make_workload("llama8b_b16", 0), steps=1)
+    _, _, need, host_blocks = orbit_plan_check(w.ctx_len, w.placement, w.page_tokens, 2, 1)
+    g = h.GpuRun(w, prefetch_slots=2, budget_pages=need + 8, host_pages=host_blocks + 8)
+    out, stats = g.step(0, want_stats=True)
+    assert torch.isfinite(out.float()).all()
+    assert stats.link_kv_bytes == int(((1 - w.placement.astype(np.int64)) * w.blocks()[:, None]).sum()) * w.page_bytes
+    rng = np.random.default_rng(3)
+    lens = w.ctx_len.astype(np.int64) + 1
+    samples = []
+    for want_tier in (0, 1, 0, 1):
+        while True:
+            layer, r = int(rng.integers(w.n_layers)), int(rng.integers(w.n_req))
+            if w.placement[r, layer] == want_tier:
+                samples.append((layer, r, int(rng.integers(w.n_kv_heads))))
+                break
+    _check_groups(h, w, out, None, lens, samples, step=0)
+    g.close()

@@ -67,6 +67,33 @@ __device__ __forceinline__ void zero_page(u32x4_t (&k)[4], u32x4_t (&v)[4]) {
   }
 }
 
+// LDS-staged prefetch: the next tile's 16 KiB go from HBM straight into this wave's private LDS
+// buffer (global_load_lds_dwordx4: lane i of each instruction lands at byte 16 i of the KiB the
+// instruction names), costing no VGPRs while in flight.  Buffer order: K0 | V0 | K1 | V1, 4 KiB each.
+typedef const __attribute__((address_space(1))) void *gptr_t;
+typedef __attribute__((address_space(3))) void *lptr_t;
+
+template <bool NT>
+__device__ __forceinline__ void page_to_lds(uint8_t *lds_page, const uint8_t *ktile, const uint8_t *vtile,
+                                            uint32_t lane_off) {
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk)
+    __builtin_amdgcn_global_load_lds((gptr_t)(ktile + (lane_off + kk * 1024u)), (lptr_t)(lds_page + kk * 1024), 16, 0,
+                                     NT ? 2 : 0);
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk)
+    __builtin_amdgcn_global_load_lds((gptr_t)(vtile + (lane_off + kk * 1024u)), (lptr_t)(lds_page + 4096 + kk * 1024),
+                                     16, 0, NT ? 2 : 0);
+}
+
+__device__ __forceinline__ void page_from_lds(u32x4_t (&k)[4], u32x4_t (&v)[4], const uint8_t *lds_page,
+                                              uint32_t lane_off) {
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) k[kk] = *reinterpret_cast<const u32x4_t *>(lds_page + kk * 1024 + lane_off);
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) v[kk] = *reinterpret_cast<const u32x4_t *>(lds_page + 4096 + kk * 1024 + lane_off);
+}
+
 // One 32-token tile: scores, online-softmax update, P.V.  `valid` = tokens of the tile that
 // exist (1..32); MASK = false promises valid == 32.
 template <bool MASK>
@@ -135,9 +162,11 @@ __device__ __forceinline__ void process_tile(Tile &T, const bf16x8_t (&q)[4], f3
   }
 }
 
-// PREFETCH = true keeps the next tile's loads in flight while the current one is processed
-// (two register tiles, 2 workgroups per CU); false relies on more resident wavefronts instead.
-template <bool PREFETCH, int MIN_BLOCKS, bool NT>
+// DEPTH = 4: one register tile plus one LDS-staged tile in flight per wave (2 workgroups per CU).
+// DEPTH = register tiles per wave otherwise: 1 issues a tile's loads and waits for them (relies on other
+// resident wavefronts), 2 keeps the next tile in flight while the current one is processed, 3 keeps
+// the next two in flight (about 32 KiB per wave, 128 KiB per CU, outstanding at all times).
+template <int DEPTH, int MIN_BLOCKS, bool NT>
 __global__ __launch_bounds__(256, MIN_BLOCKS) void attention_kernel(const AttnParams p) {
   extern __shared__ float smem[];  // [3][G][128] accumulators of waves 1..3, then [4][2][16] (m, l)
   const int lane = threadIdx.x & 63;
@@ -190,7 +219,53 @@ __global__ __launch_bounds__(256, MIN_BLOCKS) void attention_kernel(const AttnPa
     else process_tile<true>(T, q, acc, m, l, p.scale_log2, valid, j);
   };
 
-  if (PREFETCH) {
+  if (DEPTH == 4) {
+    // merge area first, then one 16 KiB staging buffer per wave
+    uint8_t *stage = reinterpret_cast<uint8_t *>(smem) + (((3 * p.G * kD + kWaves * 32) * 4 + 1023) & ~1023) + wave * 16384;
+    auto issue = [&](int t) {
+      const int valid = ntok - 2 * kP * t;
+      const int p0 = __builtin_amdgcn_readfirstlane(row[2 * t]);
+      const uint8_t *t0 = head_base + (int64_t)p0 * p.page_bytes;
+      page_to_lds<NT>(stage, t0, t0 + v_off, lane_off);
+      if (valid > kP) {
+        const int p1 = __builtin_amdgcn_readfirstlane(row[2 * t + 1]);
+        const uint8_t *t1 = head_base + (int64_t)p1 * p.page_bytes;
+        page_to_lds<NT>(stage + 8192, t1, t1 + v_off, lane_off);
+      }
+    };
+    Tile A;
+    int t = wave;
+    if (t < ntiles) issue(t);
+    while (t < ntiles) {
+      __builtin_amdgcn_s_waitcnt(0);  // the staged tile has landed in LDS
+      page_from_lds(A.k0, A.v0, stage, lane_off);
+      if (ntok - 2 * kP * t > kP) page_from_lds(A.k1, A.v1, stage + 8192, lane_off);
+      else zero_page(A.k1, A.v1);
+      __builtin_amdgcn_s_waitcnt(0);  // registers filled: the buffer may be overwritten
+      const int tn = t + kWaves;
+      if (tn < ntiles) issue(tn);
+      run_tile(A, t);
+      t = tn;
+    }
+  } else if (DEPTH == 3) {
+    Tile A, B, C;
+    int t = wave;
+    if (t < ntiles) load_tile(A, t);
+    if (t + kWaves < ntiles) load_tile(B, t + kWaves);
+    while (t < ntiles) {
+      if (t + 2 * kWaves < ntiles) load_tile(C, t + 2 * kWaves);
+      run_tile(A, t);
+      t += kWaves;
+      if (t >= ntiles) break;
+      if (t + 2 * kWaves < ntiles) load_tile(A, t + 2 * kWaves);
+      run_tile(B, t);
+      t += kWaves;
+      if (t >= ntiles) break;
+      if (t + 2 * kWaves < ntiles) load_tile(B, t + 2 * kWaves);
+      run_tile(C, t);
+      t += kWaves;
+    }
+  } else if (DEPTH == 2) {
     Tile A, B;
     int t = wave;
     if (t < ntiles) load_tile(A, t);
@@ -427,14 +502,26 @@ __global__ __launch_bounds__(256) void blit_kernel(const BlitOp *ops, int64_t un
 
 hipError_t launch_attention(const AttnParams &p, hipStream_t s) {
   if (p.n_items <= 0) return hipSuccess;
-  const size_t lds = (size_t)(3 * p.G * kD + kWaves * 32) * sizeof(float);
+  const size_t merge = (size_t)(3 * p.G * kD + kWaves * 32) * sizeof(float);
   const dim3 grid((unsigned)p.n_items), block(256);
   switch (p.variant) {  // 0 is the measured best on MI355X; the others are kept for tuning runs
-    case 1: hipLaunchKernelGGL((attention_kernel<true, 1, false>), grid, block, lds, s, p); break;
-    case 2: hipLaunchKernelGGL((attention_kernel<false, 2, false>), grid, block, lds, s, p); break;
-    case 3: hipLaunchKernelGGL((attention_kernel<false, 3, false>), grid, block, lds, s, p); break;
-    case 4: hipLaunchKernelGGL((attention_kernel<false, 2, true>), grid, block, lds, s, p); break;
-    default: hipLaunchKernelGGL((attention_kernel<true, 1, true>), grid, block, lds, s, p); break;
+    case 1: hipLaunchKernelGGL((attention_kernel<2, 1, false>), grid, block, merge, s, p); break;
+    case 2: hipLaunchKernelGGL((attention_kernel<1, 2, false>), grid, block, merge, s, p); break;
+    case 3: hipLaunchKernelGGL((attention_kernel<3, 1, true>), grid, block, merge, s, p); break;
+    case 4: hipLaunchKernelGGL((attention_kernel<1, 2, true>), grid, block, merge, s, p); break;
+    case 5: {
+      const size_t lds = ((merge + 1023) & ~(size_t)1023) + kWaves * 16384;
+      static bool raised = false;  // dynamic LDS above 64 KiB has to be allowed once per function
+      if (!raised) {
+        hipError_t e = hipFuncSetAttribute((const void *)attention_kernel<4, 2, true>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        raised = true;
+      }
+      hipLaunchKernelGGL((attention_kernel<4, 2, true>), grid, block, lds, s, p);
+      break;
+    }
+    default: hipLaunchKernelGGL((attention_kernel<2, 1, true>), grid, block, merge, s, p); break;
   }
   return hipGetLastError();
 }

@@ -348,3 +348,42 @@ def test_alternative_kernel_builds_match_oracle(variant, monkeypatch):
         out, out32 = g.attention(layer)
         _check(out, out32, o.attention(layer))
     g.close()
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_shapes_lengths_and_placements(seed):
+    """Seeded random head shapes, chunk sizes, staging-range counts, lengths and placements."""
+    h = _harness()
+    rng = np.random.default_rng(100 + seed)
+    Hkv = int(rng.choice([1, 2, 4, 8]))
+    G = int(rng.choice([1, 2, 4, 8, 16]))
+    L = int(rng.integers(1, 4))
+    B = int(rng.integers(1, 7))
+    lens = [int(x) for x in rng.integers(1, 2600, size=B)]
+    pl = rng.integers(0, 2, size=(B, L)).astype(np.uint8)
+    w = _custom(lens, L=L, Hq=Hkv * G, Hkv=Hkv, seed=seed, placement=pl, steps=2)
+    g = h.GpuRun(w, prefetch_slots=int(rng.integers(1, 4)), chunk_tokens=int(rng.choice([0, 32, 96, 512, 2048])))
+    o = h.OracleRun(w, extra_tokens=2)
+    for layer in range(L):
+        out, out32 = g.attention(layer)
+        _check(out, out32, o.attention(layer))
+    for s in range(2):
+        out, _ = g.step(s)
+        o.append_all()
+    for layer in range(L):
+        _check(out[layer], None, o.attention(layer, 1))
+    g.close()
+
+
+def test_maximum_request_count():
+    """256 requests (ORBIT_MAX_REQUESTS): four append launches per layer, one attention launch."""
+    h = _harness()
+    n = 256
+    lens = [1 + (7 * i) % 50 for i in range(n)]
+    w = _custom(lens, L=1, placement=np.array([[i % 3 != 0] for i in range(n)], dtype=np.uint8), steps=1)
+    g = h.GpuRun(w)
+    o = h.OracleRun(w, extra_tokens=1)
+    out, _ = g.step(0)
+    o.append_all()
+    _check(out[0], None, o.attention(0, 0))
+    g.close()

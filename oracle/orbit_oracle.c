@@ -169,6 +169,15 @@ int oracle_attention_weights(const uint16_t *arena, int64_t arena_pages, const i
   return attend_one(arena, arena_pages, pages, n, h, Hq, Hkv, D, P, q_row, scale, out_row, weights);
 }
 
+/* Limits the OpenMP team used by oracle_decode_attention (n >= 1); no effect without OpenMP. */
+void oracle_set_threads(int n) {
+#ifdef _OPENMP
+  if (n >= 1) omp_set_num_threads(n);
+#else
+  (void)n;
+#endif
+}
+
 int oracle_num_threads(void) {
   int n = 1;
 #ifdef _OPENMP

@@ -37,6 +37,8 @@ def lib():
         L.oracle_attention_weights.argtypes = [u16p, i64, i32p, i64, ci, ci, ci, ci, ci, u16p,
                                                ctypes.c_double, f64p, f64p]
         L.oracle_num_threads.restype = ci
+        L.oracle_set_threads.argtypes = [ci]
+        L.oracle_set_threads.restype = None
         _lib = L
     return _lib
 
@@ -204,6 +206,11 @@ def attention_weights(store: PagedStore, layer: int, req_id: int, head: int, q_r
 
 def num_threads() -> int:
     return int(lib().oracle_num_threads())
+
+
+def set_threads(n: int) -> None:
+    """Size of the OpenMP team the attention call uses from now on (timing runs only)."""
+    lib().oracle_set_threads(int(n))
 
 
 def default_scale(head_dim: int) -> float:

@@ -387,3 +387,23 @@ def test_maximum_request_count():
     o.append_all()
     _check(out[0], None, o.attention(0, 0))
     g.close()
+
+
+def test_steps_starting_from_an_empty_request():
+    """A request admitted with no stored token gets its first tokens through orbit_step."""
+    h = _harness()
+    w = _custom([0, 5, 0], L=2, placement=[[1, 0], [0, 1], [0, 0]], steps=3)
+    g = h.GpuRun(w, prefetch_slots=1)
+    o = h.OracleRun(w, extra_tokens=3)
+    from paper_2601_10729_amd import OrbitError, ORBIT_E_INVAL
+    q = g.q_layer(0)
+    out = torch.empty((3, 8, 128), dtype=torch.bfloat16, device=g.dev)
+    with pytest.raises(OrbitError) as e:
+        g.ctx.decode_attention(0, q, out, None)          # nothing stored yet: an error, not NaN
+    assert e.value.code == ORBIT_E_INVAL
+    for s in range(3):
+        out, _ = g.step(s)
+        o.append_all()
+        for layer in range(2):
+            _check(out[layer], None, o.attention(layer, s))
+    g.close()

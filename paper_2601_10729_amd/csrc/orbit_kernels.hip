@@ -94,11 +94,13 @@ __device__ __forceinline__ void page_from_lds(u32x4_t (&k)[4], u32x4_t (&v)[4], 
   for (int kk = 0; kk < 4; ++kk) v[kk] = *reinterpret_cast<const u32x4_t *>(lds_page + 4096 + kk * 1024 + lane_off);
 }
 
-// One 32-token tile: scores, online-softmax update, P.V.  `valid` = tokens of the tile that
-// exist (1..32); MASK = false promises valid == 32.
+// One 32-token tile in two phases.  `valid` = tokens of the tile that exist (1..32); MASK = false
+// promises valid == 32.
+// Phase 1: scores S^T = K.Q^T, online-softmax update of (m, l); returns the bf16 weights in
+// B-operand order and the factor alpha by which the running accumulator must shrink.
 template <bool MASK>
-__device__ __forceinline__ void process_tile(Tile &T, const bf16x8_t (&q)[4], f32x4_t (&acc)[8], float &m, float &l,
-                                             float scale_log2, int valid, int j) {
+__device__ __forceinline__ bf16x8_t tile_scores(const Tile &T, const bf16x8_t (&q)[4], float &m, float &l,
+                                                float scale_log2, int valid, int j, float &alpha) {
   f32x4_t s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk)
@@ -125,7 +127,7 @@ __device__ __forceinline__ void process_tile(Tile &T, const bf16x8_t (&q)[4], f3
   mx = xor_max(mx, 16);
   mx = xor_max(mx, 32);
   const float mn = fmaxf(m, mx);  // finite: token 0 of the tile always exists
-  const float alpha = fast_exp2(m - mn);
+  alpha = fast_exp2(m - mn);
   uint32_t pb[8];
   float psum = 0.f;
 #pragma unroll
@@ -136,7 +138,12 @@ __device__ __forceinline__ void process_tile(Tile &T, const bf16x8_t (&q)[4], f3
   l = l * alpha + psum;
   m = mn;
   u32x4_t pw = {pb[0] | (pb[1] << 16), pb[2] | (pb[3] << 16), pb[4] | (pb[5] << 16), pb[6] | (pb[7] << 16)};
-  const bf16x8_t pB = __builtin_bit_cast(bf16x8_t, pw);
+  return __builtin_bit_cast(bf16x8_t, pw);
+}
+
+// Phase 2: O^T = alpha O^T + V^T.P^T.
+template <bool MASK>
+__device__ __forceinline__ void tile_pv(Tile &T, const bf16x8_t pB, float alpha, f32x4_t (&acc)[8], int valid, int j) {
   if (MASK) {
     // a slot past the stored length may hold anything (even Inf/NaN bits): clear it so that
     // weight 0 times garbage cannot poison the accumulator
@@ -162,6 +169,17 @@ __device__ __forceinline__ void process_tile(Tile &T, const bf16x8_t (&q)[4], f3
   }
 }
 
+template <bool MASK>
+__device__ __forceinline__ void process_tile(Tile &T, const bf16x8_t (&q)[4], f32x4_t (&acc)[8], float &m, float &l,
+                                             float scale_log2, int valid, int j) {
+  float alpha;
+  const bf16x8_t pB = tile_scores<MASK>(T, q, m, l, scale_log2, valid, j, alpha);
+  tile_pv<MASK>(T, pB, alpha, acc, valid, j);
+}
+
+// DEPTH = 5: one register tile reused in halves: the next tile's K is loaded into the K registers
+// as soon as the scores exist, its V into the V registers as soon as P.V is done (no second tile,
+// so two or three workgroups fit a CU and cover each other's start-up and merge phases).
 // DEPTH = 4: one register tile plus one LDS-staged tile in flight per wave (2 workgroups per CU).
 // DEPTH = register tiles per wave otherwise: 1 issues a tile's loads and waits for them (relies on other
 // resident wavefronts), 2 keeps the next tile in flight while the current one is processed, 3 keeps
@@ -219,7 +237,45 @@ __global__ __launch_bounds__(256, MIN_BLOCKS) void attention_kernel(const AttnPa
     else process_tile<true>(T, q, acc, m, l, p.scale_log2, valid, j);
   };
 
-  if (DEPTH == 4) {
+  if (DEPTH == 5) {
+    Tile T;
+    auto load_half = [&](int t, bool want_v) {
+      const int valid = ntok - 2 * kP * t;
+      const int p0 = __builtin_amdgcn_readfirstlane(row[2 * t]);
+      const uint8_t *t0 = head_base + (int64_t)p0 * p.page_bytes + (want_v ? v_off : 0);
+      u32x4_t(&d0)[4] = want_v ? T.v0 : T.k0;
+      u32x4_t(&d1)[4] = want_v ? T.v1 : T.k1;
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) d0[kk] = load16<NT>(t0 + (lane_off + kk * 1024u));
+      if (valid > kP) {
+        const int p1 = __builtin_amdgcn_readfirstlane(row[2 * t + 1]);
+        const uint8_t *t1 = head_base + (int64_t)p1 * p.page_bytes + (want_v ? v_off : 0);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) d1[kk] = load16<NT>(t1 + (lane_off + kk * 1024u));
+      } else {
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) d1[kk] = u32x4_t{0, 0, 0, 0};
+      }
+    };
+    int t = wave;
+    if (t < ntiles) {
+      load_half(t, false);
+      load_half(t, true);
+    }
+    while (t < ntiles) {
+      const int valid = ntok - 2 * kP * t, tn = t + kWaves;
+      const bool more = tn < ntiles;
+      float alpha;
+      bf16x8_t pB;
+      if (valid >= 2 * kP) pB = tile_scores<false>(T, q, m, l, p.scale_log2, 2 * kP, j, alpha);
+      else pB = tile_scores<true>(T, q, m, l, p.scale_log2, valid, j, alpha);
+      if (more) load_half(tn, false);  // the K registers are free once the scores exist
+      if (valid >= 2 * kP) tile_pv<false>(T, pB, alpha, acc, 2 * kP, j);
+      else tile_pv<true>(T, pB, alpha, acc, valid, j);
+      if (more) load_half(tn, true);   // and the V registers once P.V has been issued
+      t = tn;
+    }
+  } else if (DEPTH == 4) {
     // merge area first, then one 16 KiB staging buffer per wave
     uint8_t *stage = reinterpret_cast<uint8_t *>(smem) + (((3 * p.G * kD + kWaves * 32) * 4 + 1023) & ~1023) + wave * 16384;
     auto issue = [&](int t) {
@@ -521,6 +577,7 @@ hipError_t launch_attention(const AttnParams &p, hipStream_t s) {
       hipLaunchKernelGGL((attention_kernel<4, 2, true>), grid, block, lds, s, p);
       break;
     }
+    case 6: hipLaunchKernelGGL((attention_kernel<5, 2, true>), grid, block, merge, s, p); break;
     default: hipLaunchKernelGGL((attention_kernel<2, 1, true>), grid, block, merge, s, p); break;
   }
   return hipGetLastError();

@@ -334,10 +334,10 @@ def test_plan_switches_between_steps_without_host_sync():
         _check(a[S - 1, layer], None, o.attention(layer, S - 1))
 
 
-@pytest.mark.parametrize("variant", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("variant", [1, 2, 3, 4, 5, 6])
 def test_alternative_kernel_builds_match_oracle(variant, monkeypatch):
     """The tuning builds of the attention kernel (plain loads, one / three register tiles,
-    LDS-staged prefetch) stay parity-green on lengths with ragged tiles and several chunks."""
+    LDS-staged prefetch, half-tile register rotation) stay parity-green on lengths with ragged tiles and several chunks."""
     h = _harness()
     monkeypatch.setenv("ORBIT_ATTN_VARIANT", str(variant))
     w = _custom([1, 33, 700, 1025, 3100, 5000], L=2, Hq=32, Hkv=8,

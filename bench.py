@@ -170,8 +170,11 @@ def main():
         run_step()
     drain()
     t0 = time.perf_counter()
+    host_enqueue = 0.0
     for _ in range(K):
+        th = time.perf_counter()
         run_step()
+        host_enqueue += time.perf_counter() - th     # host time spent enqueueing the step (no GPU wait inside)
     drain()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / K
 
@@ -292,6 +295,7 @@ def main():
         "host_link": link,
         "planner_model": planner,
         "all_resident_variant": resident,
+        "host_enqueue_ms_per_step": host_enqueue * 1e3 / K,
         "ms_per_step_with_events": ms_per_step_events,
         "step_ms_median": float(np.median(step_ev_ms)), "step_ms_min": float(np.min(step_ev_ms)),
         "setup_seconds": setup_s,

@@ -94,6 +94,9 @@ def main():
     ap.add_argument("--n-req", type=int, default=None, help="truncate the batch")
     ap.add_argument("--max-host-gib", type=float, default=60.0,
                     help="largest pinned host arena to ask for; the batch is truncated to fit")
+    ap.add_argument("--zero-copy", action="store_true",
+                    help="ORBIT_FLAG_ZERO_COPY: the attention kernel reads offloaded blocks in place over the link "
+                         "(no staging region, no host->staging copies); a measured alternative, not the default")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-resident-variant", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -123,7 +126,8 @@ def main():
         elif args.placement == "host":
             w = w.all_host()
         slots = args.prefetch_slots if w.hbm_budget_bytes is None else 1   # the byte budget was clipped for one buffer
-        _, _, need, host_blocks = orbit_plan_check(w.ctx_len, w.placement, w.page_tokens, slots, total_steps)
+        _, _, need, host_blocks = orbit_plan_check(w.ctx_len, w.placement, w.page_tokens,
+                                                   0 if args.zero_copy else slots, total_steps)
         if (host_blocks + 8) * w.page_bytes <= args.max_host_gib * (1 << 30) or w.n_req == 1:
             break
         n_req = w.n_req - 1            # this host cannot pin that much: drop the last request and say so
@@ -137,7 +141,7 @@ def main():
     if w.hbm_budget_bytes is not None:
         pages = max(pages, w.hbm_budget_bytes // w.page_bytes)
     g = harness.GpuRun(w, prefetch_slots=slots, chunk_tokens=args.chunk_tokens,
-                       budget_pages=pages, host_pages=host_blocks + 8,
+                       budget_pages=pages, host_pages=host_blocks + 8, zero_copy=args.zero_copy,
                        max_tokens=int(w.ctx_len.max()) + 2 * total_steps + 32)
     B, L = w.n_req, w.n_layers
     # per-step inputs, generated once and resident in HBM: [S][L][B][...]
@@ -210,14 +214,20 @@ def main():
     if os.path.exists(tpath):
         with open(tpath) as f:
             tj = json.load(f)
-        if tj.get("workload") == args.workload and args.placement == "workload":
+        if tj.get("workload") == args.workload and args.placement == "workload" and not args.zero_copy:
             traffic = tj.get("hbm_bytes_per_launch")
     roofline = {"bound": "hbm", "kernel": "attention_kernel (split-K GQA decode attention, one launch per layer)",
                 "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                 "traffic": traffic, "bytes_per_launch": launch_bytes, "avg_launch_ms": avg_attn_ms,
                 "launches_timed": len(attn_ms), "avg_combine_ms": float(np.mean(comb_ms))}
     link = None
-    if link_bytes:
+    if link_bytes and args.zero_copy:
+        # the kernel itself pulls the offloaded blocks over the link: the attention launches are the transfer
+        rate = link_bytes / (sum(attn_ms) * 1e-3) / 1e9
+        link = {"bytes_per_step": link_bytes / K, "mode": "zero-copy (read in place by attention_kernel)",
+                "achieved": rate, "measured_peak": link_peak, "unit": "GB/s", "frac_of_measured_peak": rate / link_peak,
+                "attn_ms_per_step": float(np.sum(attn_ms) / K)}
+    elif link_bytes:
         rate = link_bytes / (sum(copy_ms) * 1e-3) / 1e9 if sum(copy_ms) > 0 else 0.0
         link = {"bytes_per_step": link_bytes / K, "copy_busy_ms_per_step": float(np.mean(copy_ms)),
                 "achieved": rate, "measured_peak": link_peak, "unit": "GB/s",
@@ -229,7 +239,7 @@ def main():
     # its prediction for this placement against the observed step, and the plan its pruned search
     # would pick under the same block budget
     planner = None
-    if link_bytes:
+    if link_bytes and not args.zero_copy:
         from paper_2601_10729_amd import orbit_model_latency, orbit_plan_search
         per_layer = np.asarray(attn_ms, dtype=np.float64).reshape(K, L).mean(axis=0) + \
             np.asarray(comb_ms, dtype=np.float64).reshape(K, L).mean(axis=0)
@@ -289,7 +299,7 @@ def main():
         "config": {"workload": f"{args.workload}: {WORKLOAD_TEXT[args.workload]}", "seed": args.seed,
                    "placement": args.placement, "n_req": B, "n_layers": L, "tokens_per_layer": float(mid_len.sum()),
                    "kv_bytes_per_step": step_bytes, "resident_fraction": resident_frac,
-                   "prefetch_slots": slots, "note": w.note, "hbm_budget_bytes": w.hbm_budget_bytes, "chunk_tokens": args.chunk_tokens or 1024},
+                   "prefetch_slots": 0 if args.zero_copy else slots, "zero_copy": bool(args.zero_copy), "note": w.note, "hbm_budget_bytes": w.hbm_budget_bytes, "chunk_tokens": args.chunk_tokens or 1024},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "host_link": link,

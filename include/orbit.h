@@ -50,6 +50,13 @@ extern "C" {
 /* flags */
 #define ORBIT_FLAG_HOST_ONLY 1    /* run only the host logic (tables, schedules); no GPU call is
                                      made and the arenas may be NULL.  For CPU-side tests.      */
+#define ORBIT_FLAG_ZERO_COPY 2    /* no staging region and no host->staging copies: the attention
+                                     kernel reads offloaded blocks straight from the mapped pinned
+                                     host arena over the link.  Eq. (1) then charges no B_buf,
+                                     orbit_kv_prefetch is a no-op and prefetch_slots is ignored.
+                                     Same arithmetic in the same order as the staged mode, so the
+                                     outputs are bit-identical to it.  A measured alternative to
+                                     the paper's prefetch buffer (Section 3.3.1), not its method. */
 
 typedef struct orbit_ctx orbit_ctx;
 
@@ -84,7 +91,8 @@ typedef struct {
   float   copy_ms_total;                 /* sum of copy_ms                                      */
   float   stall_ms_total;                /* compute_stream time spent waiting for prefetches    */
   int64_t hbm_kv_bytes;                  /* KV bytes attended from resident blocks              */
-  int64_t link_kv_bytes;                 /* KV bytes moved host -> staging this step            */
+  int64_t link_kv_bytes;                 /* KV bytes moved host -> staging this step (zero-copy
+                                            mode: read over the link by the attention kernel)   */
   int64_t hbm_blocks_reserved;           /* resident blocks + staging region (left of Eq. (1))  */
   int64_t hbm_blocks_budget;             /* B_GPU                                               */
   float   attn_ms[ORBIT_MAX_LAYERS];     /* split-K attention kernel, per layer                 */
@@ -128,7 +136,8 @@ ORBIT_API const char *orbit_last_error(orbit_ctx *ctx);
 
 /* Pure function, no context: evaluates Eq. (1) for a placement.
  * placement_bitmap: host, row-major [n_req][ceil(L/8)], bit l (LSB first) = x[r,l].
- * out4 (host): {resident blocks, B_buf, resident + prefetch_slots*B_buf, host blocks}. */
+ * out4 (host): {resident blocks, B_buf, resident + prefetch_slots*B_buf, host blocks};
+ * prefetch_slots >= 0 (0 = the zero-copy mode, which has no staging region). */
 ORBIT_API int orbit_plan_check(int32_t n_req, int32_t n_layers, int32_t page_tokens, const int32_t *ctx_len,
                      const uint8_t *placement_bitmap, int32_t prefetch_slots, int32_t decode_window,
                      int64_t *out4);

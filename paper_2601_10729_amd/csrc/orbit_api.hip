@@ -199,6 +199,7 @@ int attention_impl(orbit_ctx *c, int layer, const void *q, void *out, float *out
     if (c->timing) HIPCHECK(c, hipEventRecord(c->t_attn0[layer], c->cs));
     AttnParams ap{};
     ap.arena = c->arena;
+    ap.host = c->host_dev;
     ap.table = c->d_table;
     ap.lens = c->d_len;
     ap.items = c->d_items;
@@ -318,7 +319,7 @@ const char *orbit_last_error(orbit_ctx *ctx) { return ctx ? ctx->err.c_str() : g
 
 int orbit_plan_check(int32_t n_req, int32_t n_layers, int32_t page_tokens, const int32_t *ctx_len,
                      const uint8_t *placement_bitmap, int32_t prefetch_slots, int32_t decode_window, int64_t *out4) {
-  if (n_req < 0 || n_layers < 1 || page_tokens < 1 || prefetch_slots < 1 || decode_window < 0 || !out4) return ORBIT_E_INVAL;
+  if (n_req < 0 || n_layers < 1 || page_tokens < 1 || prefetch_slots < 0 || decode_window < 0 || !out4) return ORBIT_E_INVAL;
   if (n_req > 0 && (!ctx_len || !placement_bitmap)) return ORBIT_E_INVAL;
   std::vector<int64_t> b(n_req);
   std::vector<uint8_t> x((size_t)n_req * n_layers);
@@ -460,6 +461,8 @@ int orbit_create(const orbit_config *cfg, orbit_ctx **out) {
   const int ch = cfg->chunk_tokens == 0 ? kDefaultChunkTokens : cfg->chunk_tokens;
   if (ch < 32 || ch % 32 || ch > 65536) return bad("chunk_tokens must be a multiple of 32");
   const bool host_only = (cfg->flags & ORBIT_FLAG_HOST_ONLY) != 0;
+  const bool zero_copy = (cfg->flags & ORBIT_FLAG_ZERO_COPY) != 0;
+  if (cfg->flags & ~(ORBIT_FLAG_HOST_ONLY | ORBIT_FLAG_ZERO_COPY)) return bad("unknown flag");
   if (cfg->hbm_arena_bytes < 0 || cfg->host_arena_bytes < 0) return bad("negative arena size");
   if (!host_only) {
     if (!cfg->hbm_arena || ((uintptr_t)cfg->hbm_arena & 255)) return bad("hbm_arena must be a 256-byte aligned device pointer");
@@ -485,8 +488,10 @@ int orbit_create(const orbit_config *cfg, orbit_ctx **out) {
   sh.max_chunks = (int)ceil_div(sh.max_tokens, ch);
   sh.window = cfg->decode_window;
   sh.slots = cfg->prefetch_slots;
+  sh.zero_copy = zero_copy;
   const int64_t arena_pages = cfg->hbm_arena_bytes / sh.page_bytes;
   if (arena_pages > 0x7FFFFFF0) return bad("hbm arena has too many pages");
+  if (cfg->host_arena_bytes / sh.page_bytes > 0x7FFFFFF0) return bad("host arena has too many pages");
   c->hs.init(sh, arena_pages, cfg->host_arena_bytes / sh.page_bytes);
   c->host_dirty.assign(sh.L, 0);
   c->copy_timed.assign(sh.L, 0);
@@ -498,8 +503,9 @@ int orbit_create(const orbit_config *cfg, orbit_ctx **out) {
 
   if (!host_only) {
     orbit_ctx *p = c.get();
-    auto hipbad = [&](hipError_t e, const char *what) {
+    auto hipbad = [&](hipError_t e, const char *what) {  // releases what was created so far
       g_create_error = std::string(what) + ": " + hipGetErrorString(e);
+      orbit_destroy(c.release());
       return ORBIT_E_HIP;
     };
 #define CREATE_CHECK(x)                                \
@@ -799,8 +805,11 @@ int orbit_step(orbit_ctx *c, const void *q, const void *k_new, const void *v_new
       ap.r0 = r0;
       HIPCHECK(c, launch_append(ap, c->cs));
     }
-    for (int r = 0; r < nreq; ++r)
-      if (hs.reqs[r].layers[l].tier == 1) hbm_bytes += (int64_t)hs.reqs[r].layers[l].len * tok_bytes;
+    for (int r = 0; r < nreq; ++r) {
+      const LayerKV &lk = hs.reqs[r].layers[l];
+      if (lk.tier == 1) hbm_bytes += (int64_t)lk.len * tok_bytes;
+      else if (sh.zero_copy) c->copy_bytes[l] += ceil_div(lk.len, sh.P) * sh.page_bytes;  // read over the link by the kernel
+    }
     if (b >= 0) find_live(c, l)->consumed = true;
     rc = attention_impl(c, l, (const uint16_t *)q + l * q_stride, (uint16_t *)out + l * q_stride, nullptr, true);
     if (rc) return rc;
@@ -854,7 +863,7 @@ int64_t orbit_get_pages(orbit_ctx *c, int64_t req_id, int32_t layer, int32_t *ti
   const int64_t n = lk.tier == 1 ? (int64_t)lk.pages.size() : (r >= 0 ? q.reserved : lk.host_cap);
   if (pages_out)
     for (int64_t i = 0; i < n && i < cap; ++i)
-      pages_out[i] = lk.tier == 1 ? lk.pages[i] : (r >= 0 ? lk.stage_page0 + (int32_t)i : -1);
+      pages_out[i] = lk.tier == 1 ? lk.pages[i] : (r >= 0 && lk.stage_page0 >= 0 ? lk.stage_page0 + (int32_t)i : -1);
   return n;
 }
 

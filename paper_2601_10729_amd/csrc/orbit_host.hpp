@@ -30,6 +30,7 @@ struct Shape {
   int max_chunks = 0;   // per request
   int window = 0;       // decode window (tokens)
   int slots = 1;        // staging region = slots * B_buf
+  bool zero_copy = false;  // offloaded blocks are read in place: no staging region at all
 };
 
 enum PageOpKind { OP_HBM_TO_HOST = 0, OP_HOST_TO_HBM = 1, OP_HBM_TO_HBM = 2, OP_HOST_TO_HOST = 3 };
@@ -242,7 +243,7 @@ class HostState {
     }
     // Eq. (1)
     Eq1 e = eq1_eval(n_req, L, rb, x);
-    const int64_t staging = (int64_t)sh.slots * e.buffer;
+    const int64_t staging = sh.zero_copy ? 0 : (int64_t)sh.slots * e.buffer;
     const int64_t b_gpu = std::min<int64_t>(budget_bytes / sh.page_bytes, arena_pages);
     if (e.resident + staging > b_gpu)
       return fail(ORBIT_E_CAPACITY, "Eq.(1) violated: resident " + std::to_string(e.resident) + " + staging " +
@@ -455,7 +456,7 @@ class HostState {
     std::vector<StageBlock> nb;
     std::vector<int> bol(L, -1);
     int64_t cursor = 0;
-    for (int l = 0; l < L; ++l) {
+    for (int l = 0; l < L && !sh.zero_copy; ++l) {
       std::vector<int> off;
       int64_t n = 0;
       for (int r = 0; r < n_req; ++r)
@@ -563,6 +564,8 @@ class HostState {
         for (int i = 0; i < sh.cap_pages; ++i) row[i] = 0;
         if (lk.tier == 1)
           for (size_t i = 0; i < lk.pages.size(); ++i) row[i] = lk.pages[i];
+        else if (sh.zero_copy)  // host page p is written as ~p: the kernel reads it in place
+          for (int i = 0; i < reqs[r].reserved; ++i) row[i] = ~(int32_t)(lk.host_page0 + i);
         else
           for (int i = 0; i < reqs[r].reserved; ++i) row[i] = lk.stage_page0 + i;
         h_len[r * sh.L + l] = lk.len;

@@ -11,7 +11,8 @@ constexpr int kAppendBatch = 64;  // requests per append launch (items travel as
 
 struct AttnParams {
   const uint8_t *arena;     // device, page 0 of the HBM arena
-  const int32_t *table;     // device [max_req][L][cap_pages] page ids
+  const uint8_t *host;      // device-visible page 0 of the pinned host arena (zero-copy reads), or NULL
+  const int32_t *table;     // device [max_req][L][cap_pages] page ids; a negative id i names host page ~i
   const int32_t *lens;      // device [max_req][L] stored tokens
   const int32_t *items;     // device [n_items][4] {request, kv head, chunk, partial slot}
   const uint16_t *q;        // device [n_req][Hq][128] bf16

@@ -49,6 +49,12 @@ __device__ __forceinline__ u32x4_t load16(const uint8_t *p) {
   return *reinterpret_cast<const u32x4_t *>(p);
 }
 
+// Page ids are wave-uniform (scalar).  A negative id i names page ~i of the mapped host arena: the
+// zero-copy mode reads offloaded blocks over the host link instead of from a staging copy.
+__device__ __forceinline__ const uint8_t *page_ptr(const AttnParams &p, int id) {
+  return id >= 0 ? p.arena + (int64_t)id * p.page_bytes : p.host + (int64_t)(~id) * p.page_bytes;
+}
+
 template <bool NT>
 __device__ __forceinline__ void load_page(u32x4_t (&k)[4], u32x4_t (&v)[4], const uint8_t *ktile, const uint8_t *vtile,
                                           uint32_t lane_off) {
@@ -200,7 +206,7 @@ __global__ __launch_bounds__(256, MIN_BLOCKS) void attention_kernel(const AttnPa
   const int ntiles = (ntok + 2 * kP - 1) / (2 * kP);
   const int32_t *row = p.table + ((int64_t)r * p.L + p.layer) * p.cap_pages + tok0 / kP;
   const int64_t v_off = (int64_t)p.Hkv * kTileBytes;
-  const uint8_t *head_base = p.arena + (int64_t)g * kTileBytes;
+  const int64_t head_off = (int64_t)g * kTileBytes;
 
   bf16x8_t q[4];
   {
@@ -221,11 +227,11 @@ __global__ __launch_bounds__(256, MIN_BLOCKS) void attention_kernel(const AttnPa
   auto load_tile = [&](Tile &T, int t) {
     const int valid = ntok - 2 * kP * t;
     const int p0 = __builtin_amdgcn_readfirstlane(row[2 * t]);
-    const uint8_t *t0 = head_base + (int64_t)p0 * p.page_bytes;
+    const uint8_t *t0 = page_ptr(p, p0) + head_off;
     load_page<NT>(T.k0, T.v0, t0, t0 + v_off, lane_off);
     if (valid > kP) {
       const int p1 = __builtin_amdgcn_readfirstlane(row[2 * t + 1]);
-      const uint8_t *t1 = head_base + (int64_t)p1 * p.page_bytes;
+      const uint8_t *t1 = page_ptr(p, p1) + head_off;
       load_page<NT>(T.k1, T.v1, t1, t1 + v_off, lane_off);
     } else {
       zero_page(T.k1, T.v1);
@@ -242,14 +248,14 @@ __global__ __launch_bounds__(256, MIN_BLOCKS) void attention_kernel(const AttnPa
     auto load_half = [&](int t, bool want_v) {
       const int valid = ntok - 2 * kP * t;
       const int p0 = __builtin_amdgcn_readfirstlane(row[2 * t]);
-      const uint8_t *t0 = head_base + (int64_t)p0 * p.page_bytes + (want_v ? v_off : 0);
+      const uint8_t *t0 = page_ptr(p, p0) + head_off + (want_v ? v_off : 0);
       u32x4_t(&d0)[4] = want_v ? T.v0 : T.k0;
       u32x4_t(&d1)[4] = want_v ? T.v1 : T.k1;
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) d0[kk] = load16<NT>(t0 + (lane_off + kk * 1024u));
       if (valid > kP) {
         const int p1 = __builtin_amdgcn_readfirstlane(row[2 * t + 1]);
-        const uint8_t *t1 = head_base + (int64_t)p1 * p.page_bytes + (want_v ? v_off : 0);
+        const uint8_t *t1 = page_ptr(p, p1) + head_off + (want_v ? v_off : 0);
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) d1[kk] = load16<NT>(t1 + (lane_off + kk * 1024u));
       } else {
@@ -281,11 +287,11 @@ __global__ __launch_bounds__(256, MIN_BLOCKS) void attention_kernel(const AttnPa
     auto issue = [&](int t) {
       const int valid = ntok - 2 * kP * t;
       const int p0 = __builtin_amdgcn_readfirstlane(row[2 * t]);
-      const uint8_t *t0 = head_base + (int64_t)p0 * p.page_bytes;
+      const uint8_t *t0 = page_ptr(p, p0) + head_off;
       page_to_lds<NT>(stage, t0, t0 + v_off, lane_off);
       if (valid > kP) {
         const int p1 = __builtin_amdgcn_readfirstlane(row[2 * t + 1]);
-        const uint8_t *t1 = head_base + (int64_t)p1 * p.page_bytes;
+        const uint8_t *t1 = page_ptr(p, p1) + head_off;
         page_to_lds<NT>(stage + 8192, t1, t1 + v_off, lane_off);
       }
     };

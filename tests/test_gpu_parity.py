@@ -407,3 +407,50 @@ def test_steps_starting_from_an_empty_request():
         for layer in range(2):
             _check(out[layer], None, o.attention(layer, s))
     g.close()
+
+
+def test_zero_copy_mode_is_bit_identical_to_staged_mode():
+    """ORBIT_FLAG_ZERO_COPY: offloaded blocks are read in place from the mapped host arena.  Same
+    arithmetic in the same order, so attention and step outputs (with appends that cross a block
+    boundary and land in host pages) equal the staged mode bit for bit, and match the oracle."""
+    h = _harness()
+    w = _custom([17, 300, 1000, 2048, 31], L=3, Hq=8, Hkv=2, seed=4, steps=3,
+                placement=[[1, 0, 0], [0, 1, 0], [0, 0, 1], [1, 0, 1], [0, 0, 0]])
+    results = []
+    for zc in (False, True):
+        g = h.GpuRun(w, prefetch_slots=2, chunk_tokens=512, zero_copy=zc)
+        info = g.ctx.get_plan_info()
+        if zc:
+            assert info["staging_blocks"] == 0 and info["buffer_blocks"] > 0
+        att = [g.attention(l)[0].cpu() for l in range(w.n_layers)]
+        steps, stats = [], None
+        for s in range(3):
+            out, stats = g.step(s, want_stats=True)
+            steps.append(out.cpu())
+        offloaded = int(((1 - w.placement.astype(np.int64)) * (-(-(w.ctx_len.astype(np.int64) + 3) // 16))[:, None]).sum())
+        assert stats.link_kv_bytes == offloaded * w.page_bytes
+        results.append(att + steps)
+        if zc:
+            o = h.OracleRun(w, extra_tokens=3)
+            for _ in range(3):
+                o.append_all()
+            for layer in range(w.n_layers):
+                _check(steps[-1][layer].to(g.dev), None, o.attention(layer, 2))
+        g.close()
+    for a, b in zip(*results):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+def test_zero_copy_plan_switch_keeps_results():
+    """Promotions and demotions under the zero-copy mode: the table flips between HBM page ids
+    and in-place host page ids, outputs stay bit-identical."""
+    h = _harness()
+    w = _custom([100, 900, 2000], L=4, placement=[[1, 1, 0, 0], [1, 0, 1, 0], [0, 0, 1, 1]])
+    g = h.GpuRun(w, budget_pages=800, host_pages=2000, zero_copy=True)   # room for every plan below
+    before = [g.attention(l)[0].cpu() for l in range(4)]
+    for new_pl in ([[1, 0, 0, 1], [1, 0, 1, 0], [1, 1, 0, 0]], [[0, 0, 0, 0]] * 3, [[1, 1, 1, 1]] * 3):
+        g.ctx.plan_load(w.req_ids, w.ctx_len, np.array(new_pl, dtype=np.uint8))
+        after = [g.attention(l)[0].cpu() for l in range(4)]
+        for a, c in zip(before, after):
+            assert torch.equal(a.view(torch.int16), c.view(torch.int16))
+    g.close()

@@ -20,11 +20,11 @@ PAGE = 2 * 8 * 16 * 128 * 2        # bytes of one block for 8 kv heads
 
 
 def ctx(L=4, Hq=32, Hkv=8, max_req=8, max_tokens=8192, hbm_pages=4096, host_pages=4096, slots=1, window=0,
-        chunk=0):
+        chunk=0, zero_copy=False):
     page = 2 * Hkv * 16 * 128 * 2
     return OrbitContext(n_layers=L, n_q_heads=Hq, n_kv_heads=Hkv, max_requests=max_req,
                         max_tokens_per_request=max_tokens, prefetch_slots=slots, decode_window=window,
-                        chunk_tokens=chunk, host_only=True, hbm_arena_bytes=hbm_pages * page,
+                        chunk_tokens=chunk, host_only=True, zero_copy=zero_copy, hbm_arena_bytes=hbm_pages * page,
                         host_arena_bytes=host_pages * page)
 
 
@@ -447,3 +447,37 @@ def test_empty_batch_and_bad_calls():
     with pytest.raises(OrbitError) as e:
         c.plan_load([1], [8193], np.ones((1, 2), dtype=np.uint8))               # beyond max_tokens_per_request
     assert e.value.code == orbit.ORBIT_E_INVAL
+
+
+def test_zero_copy_mode_charges_no_prefetch_buffer():
+    """ORBIT_FLAG_ZERO_COPY drops the B_buf term of Eq. (1): a budget that holds exactly the
+    resident blocks is accepted (the staged mode rejects it), nothing is scheduled for copying,
+    and offloaded layers have no staging pages."""
+    lens = np.array([100, 900, 2000], dtype=np.int32)
+    pl = np.array([[1, 1, 0, 0], [1, 0, 1, 0], [0, 0, 1, 1]], dtype=np.uint8)
+    ids = np.array([5, 6, 7], dtype=np.int64)
+    res, buf, need1, host = orbit_plan_check(lens, pl, 16, 1, 0)
+    _, _, need0, _ = orbit_plan_check(lens, pl, 16, 0, 0)
+    assert need0 == res == ref.resident_blocks(ref.blocks(lens), pl) and need1 == res + buf and buf > 0
+    staged = ctx(slots=1)
+    with pytest.raises(OrbitError) as e:
+        staged.plan_load(ids, lens, pl, res * PAGE)
+    assert e.value.code == orbit.ORBIT_E_CAPACITY
+    c = ctx(zero_copy=True, slots=3)
+    c.plan_load(ids, lens, pl, res * PAGE)
+    info = c.get_plan_info()
+    assert info["staging_blocks"] == 0 and info["resident_blocks"] == res and info["host_blocks"] == host
+    assert len(c.get_copy_schedule()) == 0
+    for r, rid in enumerate(ids):
+        for l in range(4):
+            pg = c.get_pages(int(rid), l)
+            assert pg["tier"] == pl[r, l] and pg["length"] == lens[r]
+            if pg["tier"] == 0:
+                assert pg["host_first_page"] >= 0 and (pg["pages"] == -1).all()
+            else:
+                assert (pg["pages"] >= 0).all() and (pg["pages"] < res).all()
+    for l in range(4):
+        c.kv_prefetch(l)                       # a no-op in this mode
+    with pytest.raises(OrbitError) as e:
+        c.plan_load(ids, lens, pl, (res - 1) * PAGE)
+    assert e.value.code == orbit.ORBIT_E_CAPACITY

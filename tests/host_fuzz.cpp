@@ -39,7 +39,11 @@ static void check_layout(const HostState &hs) {
         CHECK(lk.host_page0 >= 0 && lk.host_page0 + lk.host_cap <= hs.host_pages);
         CHECK(lk.host_cap >= ceil_div(lk.len, hs.sh.P));
         runs.push_back({lk.host_page0, lk.host_page0 + lk.host_cap});
-        if (active) {
+        if (active && hs.sh.zero_copy) {
+          CHECK(lk.stage_page0 < 0 && hs.info.staging_blocks == 0 && hs.blocks.empty());
+          const int32_t *row = &hs.h_table[((size_t)(&q - hs.reqs.data()) * hs.sh.L + l) * hs.sh.cap_pages];
+          for (int i = 0; i < q.reserved; ++i) CHECK(~row[i] == lk.host_page0 + i);   // in-place host page ids
+        } else if (active) {
           CHECK(lk.stage_page0 >= hs.info.staging_first_page);
           CHECK(lk.stage_page0 + q.reserved <= hs.info.staging_first_page + hs.info.staging_blocks);
         }
@@ -79,6 +83,7 @@ int main(int argc, char **argv) {
   sh.max_chunks = (int)ceil_div(sh.max_tokens, sh.chunk_tokens);
   sh.window = rnd(0, 40);
   sh.slots = rnd(1, 3);
+  sh.zero_copy = rnd(0, 3) == 0;
   HostState hs;
   hs.init(sh, 3000, 3000);
   std::vector<int64_t> known_ids;

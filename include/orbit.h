@@ -214,7 +214,11 @@ ORBIT_API int orbit_decode_attention(orbit_ctx *ctx, int32_t layer, const void *
 /* For l = 0..L-1 in order: append k_new[l], v_new[l] to every request, then attend q[l] over
  * the grown cache into out[l]; prefetches run ahead on copy_stream.
  * q, out: device [L][n_req][Hq][D] bf16; k_new, v_new: device [L][n_req][Hkv][D] bf16.
- * stats: NULL, or host memory to fill; filling it blocks until the step has finished. */
+ * stats: NULL, or host memory to fill; filling it blocks until the step has finished.
+ * ORBIT_E_STATE (no plan, an empty plan, decode window used up, a prefetched layer left
+ * unattended) and ORBIT_E_INVAL (NULL pointer) are detected before anything is enqueued and
+ * change nothing.  ORBIT_E_HIP can strike mid-step: the layers already enqueued keep their
+ * appended token, so the context is then only good for orbit_destroy. */
 ORBIT_API int orbit_step(orbit_ctx *ctx, const void *q, const void *k_new, const void *v_new, void *out,
                orbit_step_stats *stats);
 

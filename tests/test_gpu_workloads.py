@@ -102,3 +102,31 @@ def test_bench_configuration_full_step_sampled():
                 break
     _check_groups(h, w, out, None, lens, samples, step=0)
     g.close()
+
+
+def test_bench_configuration_every_output_is_placement_invariant():
+    """A property checked on EVERY output element at full size: the 8B-shaped batch-16 workload
+    attended under its 75 %-resident placement (streamed layers through the staging ranges) and
+    again after a plan switch to all-resident gives bit-identical outputs for all 32 layers."""
+    import harness as h
+    w = make_workload("llama8b_b16", 0)
+    all_res = int(w.blocks().sum()) * w.n_layers
+    host_blocks = int(((1 - w.placement.astype(np.int64)) * w.blocks()[:, None]).sum())
+    g = h.GpuRun(w, prefetch_slots=2, budget_pages=all_res + 8, host_pages=host_blocks + 8)
+    qs = [g.q_layer(l) for l in range(w.n_layers)]
+    outs = []
+    for pl in (None, np.ones_like(w.placement)):
+        if pl is not None:
+            g.ctx.plan_load(w.req_ids, w.ctx_len, pl)
+            info = g.ctx.get_plan_info()
+            assert info["moved_to_hbm_blocks"] == host_blocks and info["moved_to_host_blocks"] == 0
+        o = torch.empty((w.n_layers, w.n_req, w.n_q_heads, w.head_dim), dtype=torch.bfloat16, device=g.dev)
+        torch.cuda.synchronize()
+        for l in range(w.n_layers):
+            g.ctx.decode_attention(l, qs[l], o[l], None)
+        g.cs.synchronize()
+        g.xs.synchronize()
+        assert torch.isfinite(o.float()).all()
+        outs.append(o)
+    assert torch.equal(outs[0].view(torch.int16), outs[1].view(torch.int16))
+    g.close()

@@ -350,9 +350,10 @@ def test_alternative_kernel_builds_match_oracle(variant, monkeypatch):
     g.close()
 
 
-@pytest.mark.parametrize("seed", range(6))
+@pytest.mark.parametrize("seed", range(10))
 def test_random_shapes_lengths_and_placements(seed):
-    """Seeded random head shapes, chunk sizes, staging-range counts, lengths and placements."""
+    """Seeded random head shapes, chunk sizes, staging-range counts, lengths and placements; odd
+    seeds read the offloaded blocks in place (zero-copy mode)."""
     h = _harness()
     rng = np.random.default_rng(100 + seed)
     Hkv = int(rng.choice([1, 2, 4, 8]))
@@ -362,7 +363,8 @@ def test_random_shapes_lengths_and_placements(seed):
     lens = [int(x) for x in rng.integers(1, 2600, size=B)]
     pl = rng.integers(0, 2, size=(B, L)).astype(np.uint8)
     w = _custom(lens, L=L, Hq=Hkv * G, Hkv=Hkv, seed=seed, placement=pl, steps=2)
-    g = h.GpuRun(w, prefetch_slots=int(rng.integers(1, 4)), chunk_tokens=int(rng.choice([0, 32, 96, 512, 2048])))
+    g = h.GpuRun(w, prefetch_slots=int(rng.integers(1, 4)), chunk_tokens=int(rng.choice([0, 32, 96, 512, 2048])),
+                 zero_copy=seed % 2 == 1)
     o = h.OracleRun(w, extra_tokens=2)
     for layer in range(L):
         out, out32 = g.attention(layer)

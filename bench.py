@@ -33,23 +33,27 @@ WORKLOAD_TEXT = {
 }
 
 
-def measure_link_peak(torch, nbytes=1 << 30, reps=4):
-    """Pinned host -> device copy rate of one large transfer (GB/s), the link roofline."""
-    src = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
+def measure_link_peak(torch, sizes=(1 << 20, 16 << 20, 256 << 20, 1 << 30), reps=4):
+    """Pinned host -> device copy rate (GB/s) of single transfers of 1 MiB .. 1 GiB: the best one is
+    the link roofline.  Returns (peak, {size in MiB: GB/s})."""
+    src = torch.empty(max(sizes), dtype=torch.uint8, pin_memory=True)
     src.fill_(1)
-    dst = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
+    dst = torch.empty(max(sizes), dtype=torch.uint8, device="cuda:0")
     dst.copy_(src, non_blocking=True)
     torch.cuda.synchronize()
-    best = 0.0
-    for _ in range(reps):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        dst.copy_(src, non_blocking=True)
-        e1.record()
-        torch.cuda.synchronize()
-        best = max(best, nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    sweep = {}
+    for n in sizes:
+        best = 0.0
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            dst[:n].copy_(src[:n], non_blocking=True)
+            e1.record()
+            torch.cuda.synchronize()
+            best = max(best, n / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+        sweep[str(n >> 20)] = best
     del src, dst
-    return best
+    return max(sweep.values()), sweep
 
 
 def cpu_baseline(w, n_req_sample=16, n_layers_sample=3):
@@ -132,7 +136,7 @@ def main():
             break
         n_req = w.n_req - 1            # this host cannot pin that much: drop the last request and say so
 
-    link_peak = measure_link_peak(torch)
+    link_peak, link_sweep = measure_link_peak(torch)
     t_setup = time.perf_counter()
     # the arena is sized so that the all-resident variant of the same workload also fits
     all_res = int(w.blocks(2 * total_steps).sum()) * w.n_layers
@@ -232,7 +236,7 @@ def main():
         link = {"bytes_per_step": link_bytes / K, "copy_busy_ms_per_step": float(np.mean(copy_ms)),
                 "achieved": rate, "measured_peak": link_peak, "unit": "GB/s",
                 "frac_of_measured_peak": rate / link_peak, "stall_ms_per_step": float(np.mean(stall_ms)),
-                "attn_ms_per_step": float(np.sum(attn_ms) / K),
+                "attn_ms_per_step": float(np.sum(attn_ms) / K), "peak_sweep_gbs_by_mib": link_sweep,
                 "overlap_efficiency": max(float(np.mean(copy_ms)), float(np.sum(attn_ms) / K)) / ms_per_step_events}
 
     # the planner's cost model fed with what was just measured (per-layer compute time, link rate):

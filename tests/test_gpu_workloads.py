@@ -130,3 +130,25 @@ def test_bench_configuration_every_output_is_placement_invariant():
         outs.append(o)
     assert torch.equal(outs[0].view(torch.int16), outs[1].view(torch.int16))
     g.close()
+
+
+def test_full_size_layer_every_element_against_oracle():
+    """One whole launch at the bench workload's real shape (16 requests, 8K-32K tokens each, a mix of
+    resident and streamed requests) compared with the oracle on EVERY output element."""
+    import harness as h
+    w = make_workload("llama8b_b16", 0)
+    col = int(np.argmax((w.placement == 0).sum(axis=0)))          # the layer with most streamed requests
+    w1 = dataclasses.replace(w, n_layers=1, placement=w.placement[:, col:col + 1].copy())
+    assert 0 < int(w1.placement.sum()) < w1.n_req
+    g = h.GpuRun(w1, prefetch_slots=2)
+    out, out32 = g.attention(0)
+    want = h.OracleRun(w1).attention(0)
+    ma, rl = h.errors(out, want)
+    assert ma <= MAX_ABS and rl <= REL_L2, (ma, rl)
+    _, rl32 = h.errors(out32, want)
+    assert rl32 <= REL_L2_F32, rl32
+    # per (request, head) rows as well: no single short row hides inside the global norm
+    d = out.to(torch.float64).cpu().numpy() - want
+    row = np.sqrt((d * d).sum(-1) / (want * want).sum(-1))
+    assert row.max() <= 2 * REL_L2, float(row.max())
+    g.close()

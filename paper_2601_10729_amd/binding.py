@@ -67,7 +67,8 @@ EXPORTS = ["orbit_create", "orbit_destroy", "orbit_last_error", "orbit_plan_chec
            "orbit_get_plan_info", "orbit_request_pause", "orbit_request_drop", "orbit_kv_fill", "orbit_kv_read", "orbit_kv_append", "orbit_kv_prefetch",
            "orbit_decode_attention", "orbit_step", "orbit_get_pages", "orbit_get_work_items",
            "orbit_get_copy_schedule", "orbit_distance_options", "orbit_distance_pattern", "orbit_model_latency",
-           "orbit_plan_search", "orbit_deposit_create", "orbit_deposit_destroy", "orbit_deposit_push",
+           "orbit_plan_search", "orbit_planner_create", "orbit_planner_destroy", "orbit_planner_submit",
+           "orbit_planner_poll", "orbit_deposit_create", "orbit_deposit_destroy", "orbit_deposit_push",
            "orbit_deposit_finish", "orbit_deposit_release", "orbit_deposit_stats", "orbit_profile_mismatch",
            "orbit_profile_ewma"]
 
@@ -111,6 +112,11 @@ def lib() -> C.CDLL:
     L.orbit_distance_pattern.argtypes = [i32, i32, u8p]
     L.orbit_model_latency.argtypes = [i32, i32, i64p, u8p, C.c_double, f64p, f64p, f64p]
     L.orbit_plan_search.argtypes = [i32, i32, i64p, i64, i32, C.c_double, f64p, i64, u8p, f64p, i64p]
+    L.orbit_planner_create.argtypes = [C.POINTER(vp)]
+    L.orbit_planner_destroy.argtypes = [vp]
+    L.orbit_planner_submit.argtypes = [vp, i32, i32, i64p, i64, i32, C.c_double, f64p, i64]
+    L.orbit_planner_submit.restype = i64
+    L.orbit_planner_poll.argtypes = [vp, i32, i64p, u8p, i64, f64p, i64p]
     L.orbit_deposit_create.argtypes = [C.c_double, C.POINTER(vp)]
     L.orbit_deposit_destroy.argtypes = [vp]
     L.orbit_deposit_push.argtypes = [vp, i32, C.c_double]
@@ -208,6 +214,59 @@ def orbit_plan_search(blocks, n_layers: int, gpu_blocks: int, blocks_per_time: f
     if rc != 0:
         raise OrbitError(rc, "orbit_plan_search: no feasible placement" if rc == ORBIT_E_CAPACITY else "orbit_plan_search")
     return t.value, _unbitmap(bm, n_layers), ev.value
+
+
+class BackgroundPlanner:
+    """The planner in its own thread (orbit_planner_* calls): submit the next iteration's problem,
+    collect the finished plan one iteration later."""
+
+    def __init__(self):
+        self._L = lib()
+        h = C.c_void_p()
+        rc = self._L.orbit_planner_create(C.byref(h))
+        if rc != 0:
+            raise OrbitError(rc, "orbit_planner_create")
+        self._h = h
+        self._shape = {}          # ticket -> (n_req, n_layers), to size the bitmap buffer
+
+    def submit(self, blocks, n_layers: int, gpu_blocks: int, blocks_per_time: float, comp,
+               prefetch_slots: int = 1, max_evals: int = 100000) -> int:
+        b, cp = _np(blocks, np.int64), _np(comp, np.float64)
+        t = self._L.orbit_planner_submit(self._h, len(b), n_layers, b.ctypes.data_as(C.POINTER(C.c_int64)),
+                                         int(gpu_blocks), prefetch_slots, float(blocks_per_time),
+                                         cp.ctypes.data_as(C.POINTER(C.c_double)), int(max_evals))
+        if t <= 0:
+            raise OrbitError(int(t), "orbit_planner_submit")
+        self._shape[int(t)] = (len(b), n_layers)
+        return int(t)
+
+    def poll(self, wait: bool = False):
+        """None if no plan is ready; else (ticket, T_batch, placement [B][L], evaluations).  Raises
+        OrbitError(ORBIT_E_CAPACITY) if the collected job found nothing feasible."""
+        cap = max([n * ((l + 7) // 8) for n, l in self._shape.values()] + [1])
+        bm = np.zeros(cap, dtype=np.uint8)
+        ticket, t, ev = C.c_int64(), C.c_double(), C.c_int64()
+        rc = self._L.orbit_planner_poll(self._h, 1 if wait else 0, C.byref(ticket), bm.ctypes.data_as(C.POINTER(C.c_uint8)),
+                                        cap, C.byref(t), C.byref(ev))
+        if rc == 0:
+            return None
+        n, l = self._shape.get(ticket.value, (0, 1))
+        self._shape = {k: v for k, v in self._shape.items() if k > ticket.value}
+        if rc < 0:
+            raise OrbitError(rc, "orbit_planner_poll: no feasible placement" if rc == ORBIT_E_CAPACITY else "orbit_planner_poll")
+        bpr = (l + 7) // 8
+        return ticket.value, t.value, _unbitmap(bm[:n * bpr].reshape(n, bpr), l), ev.value
+
+    def close(self):
+        if self._h is not None:
+            self._L.orbit_planner_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 class TokenDeposit:

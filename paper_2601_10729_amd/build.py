@@ -6,9 +6,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liborbit.so")
 SOURCES = ["orbit_kernels.hip", "orbit_api.hip"]
-DEPS = SOURCES + ["orbit_kernels.h", "orbit_host.hpp", "orbit_planner.hpp", "orbit_deposit.hpp", os.path.join("..", "..", "include", "orbit.h")]
+DEPS = SOURCES + ["orbit_kernels.h", "orbit_host.hpp", "orbit_planner.hpp", "orbit_deposit.hpp", "orbit_async_planner.hpp", os.path.join("..", "..", "include", "orbit.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-pthread", "-Wall", "-Wno-unused-command-line-argument"]
 
 
 def is_stale() -> bool:

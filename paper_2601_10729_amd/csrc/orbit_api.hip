@@ -16,6 +16,7 @@
 #include "orbit_kernels.h"
 #include "orbit_planner.hpp"
 #include "orbit_deposit.hpp"
+#include "orbit_async_planner.hpp"
 
 using namespace orbit;
 
@@ -26,6 +27,12 @@ constexpr int kDefaultChunkTokens = 1024;
 
 struct orbit_deposit {
   Deposit d;
+};
+
+struct orbit_planner {
+  AsyncPlanner a;
+  PlanDone held;      // a collected result that did not fit the caller's buffer yet
+  bool has_held = false;
 };
 
 struct orbit_ctx {
@@ -439,6 +446,59 @@ int orbit_plan_search(int32_t n_req, int32_t n_layers, const int64_t *blocks, in
     for (int l = 0; l < n_layers; ++l)
       if (res.x[(size_t)r * n_layers + l]) bitmap_out[r * bpr + l / 8] |= (uint8_t)(1u << (l % 8));
   return ORBIT_OK;
+}
+
+int orbit_planner_create(orbit_planner **out) {
+  if (!out) return ORBIT_E_INVAL;
+  *out = new orbit_planner();
+  return ORBIT_OK;
+}
+int orbit_planner_destroy(orbit_planner *p) {
+  if (!p) return ORBIT_E_INVAL;
+  delete p;
+  return ORBIT_OK;
+}
+int64_t orbit_planner_submit(orbit_planner *p, int32_t n_req, int32_t n_layers, const int64_t *blocks, int64_t gpu_blocks,
+                             int32_t prefetch_slots, double blocks_per_time, const double *comp, int64_t max_evals) {
+  if (!p || !planner_args_ok(n_req, n_layers, blocks, blocks_per_time, comp) || prefetch_slots < 1 || gpu_blocks < 0 ||
+      max_evals < 1)
+    return ORBIT_E_INVAL;
+  PlanJob j;
+  j.n_req = n_req;
+  j.L = n_layers;
+  j.slots = prefetch_slots;
+  j.gpu_blocks = gpu_blocks;
+  j.max_evals = max_evals;
+  j.bandwidth = blocks_per_time;
+  j.blocks.assign(blocks, blocks + n_req);
+  j.comp.assign(comp, comp + n_layers);
+  return p->a.submit(std::move(j));
+}
+int orbit_planner_poll(orbit_planner *p, int32_t wait, int64_t *ticket_out, uint8_t *bitmap_out, int64_t bitmap_cap,
+                       double *t_batch, int64_t *evals_out) {
+  if (!p) return ORBIT_E_INVAL;
+  PlanDone fresh;
+  if (p->a.poll(wait != 0, fresh)) {  // a newer result supersedes one the caller could not take
+    p->held = std::move(fresh);
+    p->has_held = true;
+  }
+  if (!p->has_held) return 0;
+  const PlanDone &d = p->held;
+  if (ticket_out) *ticket_out = d.ticket;
+  if (evals_out) *evals_out = d.res.evals;
+  if (!(d.res.t < std::numeric_limits<double>::infinity())) {
+    p->has_held = false;
+    return ORBIT_E_CAPACITY;
+  }
+  const int bpr = (d.L + 7) / 8;
+  if ((int64_t)d.n_req * bpr > bitmap_cap || (d.n_req > 0 && !bitmap_out)) return ORBIT_E_INVAL;
+  if (t_batch) *t_batch = d.res.t;
+  for (int i = 0; i < d.n_req * bpr; ++i) bitmap_out[i] = 0;
+  for (int r = 0; r < d.n_req; ++r)
+    for (int l = 0; l < d.L; ++l)
+      if (d.res.x[(size_t)r * d.L + l]) bitmap_out[r * bpr + l / 8] |= (uint8_t)(1u << (l % 8));
+  p->has_held = false;
+  return 1;
 }
 
 int orbit_create(const orbit_config *cfg, orbit_ctx **out) {

@@ -456,3 +456,52 @@ def test_zero_copy_plan_switch_keeps_results():
         for a, c in zip(before, after):
             assert torch.equal(a.view(torch.int16), c.view(torch.int16))
     g.close()
+
+
+def test_background_planner_one_iteration_ahead_drives_the_plans():
+    """The executor loop of Section 4: while step s runs on the GPU, the planner thread solves the
+    plan for step s+1 under that step's block budget; the finished plan is installed (stream
+    ordered) before step s+1.  Whatever plans come out, outputs equal an all-resident run."""
+    h = _harness()
+    from paper_2601_10729_amd import BackgroundPlanner
+    from workloads import gen_q_steps, gen_kv
+    L, B, S = 8, 4, 6
+    w = _custom([300, 1200, 90, 2100], L=L, steps=S)
+    total = int(w.blocks(2 * S).sum()) * L
+    budgets = [total + 8, int(total * 0.8), int(total * 0.55), int(total * 0.9), int(total * 0.5), int(total * 0.7)]
+    comp = np.full(L, 0.02)
+
+    def run(planned: bool):
+        g = h.GpuRun(w, placement=np.ones((B, L), np.uint8), prefetch_slots=2, budget_pages=total + 8,
+                     host_pages=total * 3, decode_window=S, max_tokens=int(w.ctx_len.max()) + 2 * S + 16)
+        dev = g.dev
+        q = torch.stack([torch.stack([gen_q_steps(w.seed, l, int(rid), 0, S, w.n_q_heads, w.head_dim, dev)
+                                      for rid in w.req_ids], dim=1) for l in range(L)], dim=1).contiguous()
+        kv = [[gen_kv(w.seed, l, int(rid), int(w.ctx_len[r]), S, w.n_kv_heads, w.head_dim, dev)
+               for r, rid in enumerate(w.req_ids)] for l in range(L)]
+        k_new = torch.stack([torch.stack([kv[l][r][0] for r in range(B)], dim=1) for l in range(L)], dim=1).contiguous()
+        v_new = torch.stack([torch.stack([kv[l][r][1] for r in range(B)], dim=1) for l in range(L)], dim=1).contiguous()
+        outs = torch.zeros((S, L, B, w.n_q_heads, w.head_dim), dtype=torch.bfloat16, device=dev)
+        torch.cuda.synchronize()
+        planner = BackgroundPlanner() if planned else None
+        offloaded = []
+        for s in range(S):
+            if planned and s + 1 < S:                      # problem of the NEXT iteration, solved during this step
+                b_next = -(-(w.ctx_len.astype(np.int64) + s + 1 + S) // 16)        # blocks plan_load will reserve
+                planner.submit(b_next, L, budgets[s + 1], 50.0, comp, prefetch_slots=2)
+            g.ctx.step(q[s], k_new[s], v_new[s], outs[s])  # enqueued, not waited for
+            if planned and s + 1 < S:
+                _, _, x, _ = planner.poll(wait=True)
+                g.ctx.plan_load(w.req_ids, w.ctx_len + s + 1, x, budgets[s + 1] * w.page_bytes)
+                offloaded.append(int((x == 0).sum()))
+        g.cs.synchronize()
+        g.xs.synchronize()
+        res = outs.cpu()
+        if planned:
+            planner.close()
+            assert max(offloaded) > 0 and len(set(offloaded)) > 1     # the budgets really forced different plans
+        g.close()
+        return res
+
+    a, b = run(True), run(False)
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))

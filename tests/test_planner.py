@@ -174,3 +174,73 @@ def test_descent_mode_is_feasible_and_not_worse_than_uniform():
                        if ref.feasible(b, np.tile(lm.distance_pattern(L, c), (n_req, 1)), cap, 2))
     assert t <= best_uniform + 1e-9
     assert abs(t - lm.simulate_prefetch(x, b, bw, comp)[0]) <= 1e-9 * t
+
+
+# ------------------------------------------------------------------ background planner (Section 4)
+
+def test_background_planner_delivers_the_same_plans_one_iteration_later():
+    """The planner thread solves the next iteration's problem while the caller does other work;
+    what it delivers equals the synchronous search, tickets grow, a newer result supersedes an
+    uncollected one, and an infeasible job surfaces as ORBIT_E_CAPACITY."""
+    rng = np.random.default_rng(3)
+    L = 8
+    comp = rng.uniform(0.5, 1.5, size=L)
+    p = orbit.BackgroundPlanner()
+    assert p.poll() is None and p.poll(wait=True) is None          # nothing submitted yet
+    last = 0
+    for it in range(6):
+        b = rng.integers(1, 30, size=4)
+        budget = int(b.sum() * L * rng.uniform(0.4, 1.0))
+        t = p.submit(b, L, budget, 3.0, comp, prefetch_slots=1 + it % 2)
+        assert t > last
+        last = t
+        try:
+            want = orbit.orbit_plan_search(b, L, budget, 3.0, comp, prefetch_slots=1 + it % 2)
+        except orbit.OrbitError as e:
+            assert e.code == orbit.ORBIT_E_CAPACITY
+            with pytest.raises(orbit.OrbitError) as e2:
+                p.poll(wait=True)
+            assert e2.value.code == orbit.ORBIT_E_CAPACITY
+            continue
+        ticket, tb, x, ev = p.poll(wait=True)
+        assert ticket == t and tb == want[0] and ev == want[2] and np.array_equal(x, want[1])
+        assert p.poll() is None                                     # collected exactly once
+    # two submissions, one collection: the newest finished plan is what comes back
+    b1, b2 = np.array([5, 9, 2]), np.array([20, 1, 1])
+    p.submit(b1, L, 10 ** 6, 3.0, comp)
+    t2 = p.submit(b2, L, 40, 3.0, comp)
+    ticket, tb, x, _ = p.poll(wait=True)
+    want = orbit.orbit_plan_search(b2, L, 40, 3.0, comp)
+    assert ticket == t2 and tb == want[0] and np.array_equal(x, want[1])
+    assert p.poll(wait=True) is None
+    # infeasible: nothing fits into zero blocks with a prefetch buffer
+    p.submit(np.array([4, 4]), L, 0, 3.0, comp)
+    with pytest.raises(orbit.OrbitError) as e:
+        p.poll(wait=True)
+    assert e.value.code == orbit.ORBIT_E_CAPACITY
+    with pytest.raises(orbit.OrbitError):
+        p.submit(np.array([-1]), L, 10, 3.0, comp)
+    p.close()
+
+
+def test_background_planner_runs_while_the_caller_works():
+    """A long search (large pruned space, exhaustive) is in flight while the caller keeps polling
+    without blocking; destroying a planner with a job in flight joins cleanly."""
+    L = 32
+    comp = np.full(L, 1.0)
+    b = np.arange(1, 6) * 7
+    p = orbit.BackgroundPlanner()
+    t = p.submit(b, L, int(b.sum() * L * 0.7), 2.0, comp, max_evals=200000)       # 11^5 = 161051 points
+    polls = 0
+    while True:
+        got = p.poll()
+        polls += 1
+        if got is not None:
+            break
+        import time
+        time.sleep(0.01)
+    assert got[0] == t and got[3] > 1000
+    want = orbit.orbit_plan_search(b, L, int(b.sum() * L * 0.7), 2.0, comp, max_evals=200000)
+    assert got[1] == want[0] and np.array_equal(got[2], want[1])
+    p.submit(b, L, int(b.sum() * L * 0.7), 2.0, comp, max_evals=200000)
+    p.close()                                                       # job still running: must not hang or crash

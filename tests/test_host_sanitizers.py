@@ -19,3 +19,13 @@ def test_host_logic_under_asan_ubsan(tmp_path):
         res = subprocess.run([exe, str(seed), "250"], capture_output=True, text=True)
         assert res.returncode == 0, res.stdout + res.stderr
         assert "host fuzz ok" in res.stdout
+
+
+@pytest.mark.skipif(shutil.which("g++") is None, reason="g++ not available")
+def test_background_planner_under_tsan(tmp_path):
+    exe = str(tmp_path / "planner_thread_check")
+    subprocess.run(["g++", "-std=c++17", "-O1", "-g", "-fsanitize=thread", "-static-libtsan", "-pthread",
+                    os.path.join(HERE, "planner_thread_check.cpp"), "-o", exe], check=True)
+    res = subprocess.run([exe], capture_output=True, text=True)
+    assert res.returncode == 0, res.stdout + res.stderr
+    assert "planner threads ok" in res.stdout and "ThreadSanitizer" not in res.stderr

@@ -1,0 +1,138 @@
+"""Stateful GPU test: seeded random sequences of plan switches (requests leaving, joining, being
+resumed; random placements and budgets), pauses, drops and decode steps on one context.  After
+every operation the KV of a random (request, layer) is read back and must equal the generator's
+values bit for bit (whatever migrations, evictions and relocations happened in between), and
+after every step one layer's output is checked against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+from workloads import gen_kv, gen_q
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS, REL_L2 = 1e-2, 5e-3
+L, HQ, HKV, D, P = 3, 8, 2, 128, 16
+PAGE = 2 * HKV * P * D * 2
+MAX_REQ, WINDOW, MAX_TOKENS = 6, 4, 1500
+HBM_PAGES, HOST_PAGES = 1400, 6000
+SEED = 21
+
+
+def _oracle_layer(layer, rids, lens, step_no):
+    from oracle import reference as ref
+    n_pages = int(sum(-(-n // P) for n in lens)) + 3
+    st = ref.PagedStore(1, HKV, D, P, n_pages, seed=step_no)
+    for rid, n in zip(rids, lens):
+        st.add_request(rid)
+        k, v = gen_kv(SEED, layer, rid, 0, n, HKV, D, "cpu")
+        st.write(rid, 0, 0, k, v)
+    q = torch.stack([gen_q(SEED, layer, rid, step_no, HQ, D, "cpu") for rid in rids])
+    return ref.decode_attention(st, 0, rids, q, HQ)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_random_operation_sequences(seed, n_ops=36):
+    from paper_2601_10729_amd import OrbitContext, OrbitError, orbit_plan_check, ORBIT_E_CAPACITY, ORBIT_E_HOST_CAPACITY
+    import harness as h
+    rng = np.random.default_rng(500 + seed)
+    dev = torch.device("cuda:0")
+    zero_copy = seed % 2 == 1
+    slots = int(rng.integers(1, 3))
+    hbm = torch.empty(HBM_PAGES * PAGE, dtype=torch.uint8, device=dev)
+    host = torch.empty(HOST_PAGES * PAGE, dtype=torch.uint8, pin_memory=True)
+    cs, xs = torch.cuda.Stream(device=dev), torch.cuda.Stream(device=dev)
+    ctx = OrbitContext(n_layers=L, n_q_heads=HQ, n_kv_heads=HKV, max_requests=MAX_REQ, max_tokens_per_request=MAX_TOKENS,
+                       prefetch_slots=slots, chunk_tokens=int(rng.choice([0, 64, 256])), decode_window=WINDOW,
+                       zero_copy=zero_copy, hbm_arena=hbm, host_arena=host, compute_stream=cs, copy_stream=xs)
+    order, length, paused = [], {}, {}      # plan order of active ids, id -> stored tokens, paused id -> tokens
+    next_id, steps_since_plan, step_no, n_steps, n_switches = 100, 0, 0, 0, 0
+
+    def sync():
+        cs.synchronize()
+        xs.synchronize()
+        torch.cuda.synchronize()
+
+    def check_kv(rid):
+        layer, n = int(rng.integers(L)), length[rid]
+        k = torch.empty((n, HKV, D), dtype=torch.bfloat16, device=dev)
+        v = torch.empty_like(k)
+        sync()
+        ctx.kv_read(rid, layer, 0, n, k, v)
+        sync()
+        wk, wv = gen_kv(SEED, layer, rid, 0, n, HKV, D, dev)
+        assert torch.equal(k.view(torch.int16), wk.view(torch.int16)), (rid, layer)
+        assert torch.equal(v.view(torch.int16), wv.view(torch.int16)), (rid, layer)
+
+    for op_no in range(n_ops):
+        op = rng.choice(["plan", "step", "step", "pause", "drop"]) if order else "plan"
+        if op == "plan":
+            ids = [r for r in order if rng.random() < 0.8]
+            ids += [r for r in paused if rng.random() < 0.5]
+            ids = ids[:MAX_REQ]
+            fresh = []
+            while len(ids) < MAX_REQ and (rng.random() < 0.5 or not ids):
+                ids.append(next_id)
+                fresh.append(next_id)
+                next_id += 1
+            ids = [int(x) for x in rng.permutation(ids)]
+            lens = [length.get(r, paused.get(r)) if r not in fresh else int(rng.integers(1, 700)) for r in ids]
+            pl = rng.integers(0, 2, size=(len(ids), L)).astype(np.uint8)
+            _, _, need, _ = orbit_plan_check(lens, pl, P, 0 if zero_copy else slots, WINDOW)
+            budget = max(0, min(HBM_PAGES, need + int(rng.integers(-40, 200))))   # sometimes too small on purpose
+            try:
+                ctx.plan_load(ids, lens, pl, budget * PAGE)
+            except OrbitError as e:
+                assert e.code in (ORBIT_E_CAPACITY, ORBIT_E_HOST_CAPACITY), e
+                assert budget < need or e.code == ORBIT_E_HOST_CAPACITY
+            else:
+                for r in order:
+                    if r not in ids:
+                        del length[r]                                          # dropped by the plan
+                for r, n in zip(ids, lens):
+                    paused.pop(r, None)
+                    length[r] = n
+                order = ids
+                for r in fresh:
+                    for layer in range(L):
+                        k, v = gen_kv(SEED, layer, r, 0, length[r], HKV, D, dev)
+                        sync()
+                        ctx.kv_fill(r, layer, 0, k, v)
+                        sync()
+                steps_since_plan = 0
+                n_switches += 1
+        elif op == "step" and steps_since_plan < WINDOW:
+            B = len(order)
+            q = torch.stack([torch.stack([gen_q(SEED, layer, r, step_no, HQ, D, dev) for r in order]) for layer in range(L)])
+            kn = torch.stack([torch.stack([gen_kv(SEED, layer, r, length[r], 1, HKV, D, dev)[0][0] for r in order])
+                              for layer in range(L)])
+            vn = torch.stack([torch.stack([gen_kv(SEED, layer, r, length[r], 1, HKV, D, dev)[1][0] for r in order])
+                              for layer in range(L)])
+            out = torch.empty((L, B, HQ, D), dtype=torch.bfloat16, device=dev)
+            sync()
+            ctx.step(q.contiguous(), kn.contiguous(), vn.contiguous(), out)
+            sync()
+            for r in order:
+                length[r] += 1
+            layer = int(rng.integers(L))
+            want = _oracle_layer(layer, order, [length[r] for r in order], step_no)
+            ma, rl = h.errors(out[layer], want)
+            assert ma <= MAX_ABS and rl <= REL_L2, (op_no, layer, ma, rl)
+            steps_since_plan += 1
+            step_no += 1
+            n_steps += 1
+        elif op == "pause" and len(order) > 1:
+            r = int(rng.choice(order))
+            ctx.request_pause(r)
+            order.remove(r)
+            paused[r] = length.pop(r)
+            steps_since_plan = 0
+        elif op == "drop" and paused:
+            r = int(rng.choice(list(paused)))
+            ctx.request_drop(r)
+            del paused[r]
+        if order:
+            check_kv(int(rng.choice(order)))
+    assert n_steps >= 3 and n_switches >= 3
+    sync()
+    ctx.destroy()

@@ -188,8 +188,14 @@ ORBIT_API int orbit_kv_read(orbit_ctx *ctx, int64_t req_id, int32_t layer, int64
  * compute_stream.  A new block is started only when the length is a multiple of 16; it comes
  * from the blocks the plan reserved (ORBIT_E_STATE once the decode window is used up).  For an
  * offloaded layer the token is written straight to its host slot, and also into the staging
- * copy if that layer is currently prefetched.  Lengths are kept per (request, layer). */
+ * copy if that layer is currently prefetched (compute_stream first waits, stream-side, for that
+ * copy to land, so the transfer cannot overwrite the token).  Lengths are kept per (request, layer). */
 ORBIT_API int orbit_kv_append(orbit_ctx *ctx, int64_t req_id, int32_t layer, const void *k, const void *v);
+
+/* The same for every request of the plan at once (what a model's layer does during decode):
+ * k, v device [n_req][Hkv][D] bf16 in plan order, one launch per 64 requests.  All or nothing:
+ * ORBIT_E_STATE, with no length changed, if any request has used up its decode window. */
+ORBIT_API int orbit_kv_append_batch(orbit_ctx *ctx, int32_t layer, const void *k, const void *v);
 
 /* ---- a4/a5: prefetch and gating (Section 3.3.1, "Scheduling KV Prefetching") ---------------- */
 

@@ -64,7 +64,7 @@ class orbit_plan_info(C.Structure):
 
 
 EXPORTS = ["orbit_create", "orbit_destroy", "orbit_last_error", "orbit_plan_check", "orbit_plan_load",
-           "orbit_get_plan_info", "orbit_request_pause", "orbit_request_drop", "orbit_kv_fill", "orbit_kv_read", "orbit_kv_append", "orbit_kv_prefetch",
+           "orbit_get_plan_info", "orbit_request_pause", "orbit_request_drop", "orbit_kv_fill", "orbit_kv_read", "orbit_kv_append", "orbit_kv_append_batch", "orbit_kv_prefetch",
            "orbit_decode_attention", "orbit_step", "orbit_get_pages", "orbit_get_work_items",
            "orbit_get_copy_schedule", "orbit_distance_options", "orbit_distance_pattern", "orbit_model_latency",
            "orbit_plan_search", "orbit_planner_create", "orbit_planner_destroy", "orbit_planner_submit",
@@ -98,6 +98,7 @@ def lib() -> C.CDLL:
     L.orbit_kv_fill.argtypes = [vp, i64, i32, i64, i64, vp, vp]
     L.orbit_kv_read.argtypes = [vp, i64, i32, i64, i64, vp, vp]
     L.orbit_kv_append.argtypes = [vp, i64, i32, vp, vp]
+    L.orbit_kv_append_batch.argtypes = [vp, i32, vp, vp]
     L.orbit_kv_prefetch.argtypes = [vp, i32]
     L.orbit_decode_attention.argtypes = [vp, i32, vp, vp, vp]
     L.orbit_step.argtypes = [vp, vp, vp, vp, vp, C.POINTER(orbit_step_stats)]
@@ -403,6 +404,9 @@ class OrbitContext:
 
     def kv_append(self, req_id: int, layer: int, k, v):
         self._check(self._L.orbit_kv_append(self._h, int(req_id), layer, _ptr(k), _ptr(v)))
+
+    def kv_append_batch(self, layer: int, k, v):
+        self._check(self._L.orbit_kv_append_batch(self._h, layer, _ptr(k), _ptr(v)))
 
     def kv_prefetch(self, layer: int):
         self._check(self._L.orbit_kv_prefetch(self._h, layer))

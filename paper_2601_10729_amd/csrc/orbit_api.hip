@@ -756,12 +756,65 @@ static int append_item(orbit_ctx *c, int r, int layer, AppendItem &item) {
   return ORBIT_OK;
 }
 
+// An append into a layer whose prefetch is in flight also writes the staging copy: the compute
+// stream must first see that copy landed, or the transfer could overwrite the new token.
+static int wait_for_live_copy(orbit_ctx *c, int layer) {
+  LiveBlock *lb = find_live(c, layer);
+  if (lb && !lb->consumed && !c->host_only) HIPCHECK(c, hipStreamWaitEvent(c->cs, c->ev_ready[layer], 0));
+  return ORBIT_OK;
+}
+
+// One token for every request of the plan, in plan order: k, v device [n_req][Hkv][D].
+// mark_dirty: remember that host pages of this layer were written on the compute stream, so that the
+// layer's next prefetch orders itself behind them.  orbit_step does not need the mark: there a
+// staging range is refilled only after the layer that read it last has finished, and that layer
+// was enqueued on the compute stream after this append.
+static int append_layer(orbit_ctx *c, int l, const uint16_t *k, const uint16_t *v, bool mark_dirty) {
+  HostState &hs = c->hs;
+  const Shape &sh = hs.sh;
+  const int nreq = (int)hs.reqs.size();
+  int rc;
+  for (int r0 = 0; r0 < nreq; r0 += kAppendBatch) {
+    AppendParams ap{};
+    const int n = std::min(kAppendBatch, nreq - r0);
+    for (int i = 0; i < n; ++i) {
+      if ((rc = append_item(c, r0 + i, l, ap.items[i]))) return rc;
+      if (mark_dirty && hs.reqs[r0 + i].layers[l].tier == 0) c->host_dirty[l] = 1;
+    }
+    if (c->host_only) continue;
+    ap.arena = c->arena;
+    ap.lens = c->d_len;
+    ap.k = k + (int64_t)r0 * sh.Hkv * sh.D;
+    ap.v = v + (int64_t)r0 * sh.Hkv * sh.D;
+    ap.page_bytes = sh.page_bytes;
+    ap.L = sh.L;
+    ap.layer = l;
+    ap.Hkv = sh.Hkv;
+    ap.n = n;
+    ap.r0 = r0;
+    HIPCHECK(c, launch_append(ap, c->cs));
+  }
+  return ORBIT_OK;
+}
+
+int orbit_kv_append_batch(orbit_ctx *c, int32_t layer, const void *k, const void *v) {
+  int rc = check_layer(c, layer);
+  if (rc) return rc;
+  if (!c->host_only && (!k || !v)) return set_err(c, ORBIT_E_INVAL, "null argument");
+  for (const Req &q : c->hs.reqs)  // all or nothing: checked before any length moves
+    if (q.layers[layer].len / c->hs.sh.P >= q.reserved)
+      return set_err(c, ORBIT_E_STATE, "decode window used up: a request needs a block the plan did not reserve");
+  if ((rc = wait_for_live_copy(c, layer))) return rc;
+  return append_layer(c, layer, (const uint16_t *)k, (const uint16_t *)v, true);
+}
+
 int orbit_kv_append(orbit_ctx *c, int64_t req_id, int32_t layer, const void *k, const void *v) {
   int rc = check_layer(c, layer);
   if (rc) return rc;
   if (!k || !v) return set_err(c, ORBIT_E_INVAL, "null argument");
   const int r = c->hs.find(req_id);
   if (r < 0) return set_err(c, ORBIT_E_NOT_FOUND, "unknown request id");
+  if ((rc = wait_for_live_copy(c, layer))) return rc;
   AppendParams ap{};
   if ((rc = append_item(c, r, layer, ap.items[0]))) return rc;
   if (c->hs.reqs[r].layers[layer].tier == 0) c->host_dirty[layer] = 1;
@@ -847,24 +900,7 @@ int orbit_step(orbit_ctx *c, const void *q, const void *k_new, const void *v_new
       }
     }
     // a3: append this layer's new token of every request (the staging copy is live: it gets the token too)
-    for (int r0 = 0; r0 < nreq; r0 += kAppendBatch) {
-      AppendParams ap{};
-      const int n = std::min(kAppendBatch, nreq - r0);
-      for (int i = 0; i < n; ++i)
-        if ((rc = append_item(c, r0 + i, l, ap.items[i]))) return rc;
-      if (c->host_only) continue;
-      ap.arena = c->arena;
-      ap.lens = c->d_len;
-      ap.k = (const uint16_t *)k_new + l * kv_stride + (int64_t)r0 * sh.Hkv * sh.D;
-      ap.v = (const uint16_t *)v_new + l * kv_stride + (int64_t)r0 * sh.Hkv * sh.D;
-      ap.page_bytes = sh.page_bytes;
-      ap.L = sh.L;
-      ap.layer = l;
-      ap.Hkv = sh.Hkv;
-      ap.n = n;
-      ap.r0 = r0;
-      HIPCHECK(c, launch_append(ap, c->cs));
-    }
+    if ((rc = append_layer(c, l, (const uint16_t *)k_new + l * kv_stride, (const uint16_t *)v_new + l * kv_stride, false))) return rc;
     for (int r = 0; r < nreq; ++r) {
       const LayerKV &lk = hs.reqs[r].layers[l];
       if (lk.tier == 1) hbm_bytes += (int64_t)lk.len * tok_bytes;

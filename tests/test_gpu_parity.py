@@ -505,3 +505,37 @@ def test_background_planner_one_iteration_ahead_drives_the_plans():
 
     a, b = run(True), run(False)
     assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+def test_per_layer_calls_equal_orbit_step():
+    """What a model's decode loop does, layer by layer (prefetch ahead, batched append, attention),
+    gives the outputs of orbit_step bit for bit."""
+    h = _harness()
+    w = _custom([17, 300, 1000, 2048, 31], L=4, Hq=8, Hkv=2, seed=6, steps=3,
+                placement=[[1, 0, 0, 1], [0, 1, 0, 1], [0, 0, 1, 1], [1, 0, 1, 0], [0, 0, 0, 0]])
+    results = []
+    for per_layer in (False, True):
+        g = h.GpuRun(w, prefetch_slots=2, chunk_tokens=256)
+        outs = []
+        for s in range(3):
+            if not per_layer:
+                out, _ = g.step(s)
+            else:
+                q = g.q_all(s)
+                k_new, v_new = g.kv_new_all()
+                out = torch.empty((w.n_layers, w.n_req, w.n_q_heads, w.head_dim), dtype=torch.bfloat16, device=g.dev)
+                torch.cuda.synchronize()
+                g.ctx.kv_prefetch(0)
+                for l in range(w.n_layers):
+                    if l + 1 < w.n_layers:
+                        g.ctx.kv_prefetch(l + 1)                 # runs ahead of this layer's attention
+                    g.ctx.kv_append_batch(l, k_new[l], v_new[l])
+                    g.ctx.decode_attention(l, q[l], out[l], None)
+                g.cs.synchronize()
+                g.xs.synchronize()
+                g.len += 1
+            outs.append(out.cpu())
+        results.append(outs)
+        g.close()
+    for a, b in zip(*results):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))

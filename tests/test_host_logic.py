@@ -481,3 +481,24 @@ def test_zero_copy_mode_charges_no_prefetch_buffer():
     with pytest.raises(OrbitError) as e:
         c.plan_load(ids, lens, pl, (res - 1) * PAGE)
     assert e.value.code == orbit.ORBIT_E_CAPACITY
+
+
+def test_batched_append_is_all_or_nothing():
+    """orbit_kv_append_batch grows every request of the plan by one token in a layer; when any
+    request has used up its reserved blocks nothing changes for anyone."""
+    c = ctx(L=2, window=2)
+    ids = np.array([1, 2], dtype=np.int64)
+    lens = np.array([13, 30], dtype=np.int32)          # reserved: ceil(15/16) = 1 and ceil(32/16) = 2 blocks
+    c.plan_load(ids, lens, np.ones((2, 2), dtype=np.uint8), 64 * PAGE)
+    for step in range(2):
+        for l in range(2):
+            c.kv_append_batch(l, None, None)
+    assert [c.get_pages(1, l)["length"] for l in range(2)] == [15, 15]
+    assert [c.get_pages(2, l)["length"] for l in range(2)] == [32, 32]
+    with pytest.raises(OrbitError) as e:
+        c.kv_append_batch(0, None, None)                # request 2 would need a third block; request 1 still has room
+    assert e.value.code == orbit.ORBIT_E_STATE
+    assert c.get_pages(1, 0)["length"] == 15 and c.get_pages(2, 0)["length"] == 32
+    c.plan_load(ids, np.array([15, 32], dtype=np.int32), np.ones((2, 2), dtype=np.uint8), 64 * PAGE)
+    c.kv_append_batch(0, None, None)
+    assert c.get_pages(1, 0)["length"] == 16 and c.get_pages(2, 0)["length"] == 33

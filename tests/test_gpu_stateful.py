@@ -2,7 +2,8 @@
 resumed; random placements and budgets), pauses, drops and decode steps on one context.  After
 every operation the KV of a random (request, layer) is read back and must equal the generator's
 values bit for bit (whatever migrations, evictions and relocations happened in between), and
-after every step one layer's output is checked against the oracle."""
+after every step (run through orbit_step or through the per-layer calls in varying order) one
+layer's output is checked against the oracle."""
 import numpy as np
 import pytest
 import torch
@@ -109,8 +110,23 @@ def test_random_operation_sequences(seed, n_ops=36):
             vn = torch.stack([torch.stack([gen_kv(SEED, layer, r, length[r], 1, HKV, D, dev)[1][0] for r in order])
                               for layer in range(L)])
             out = torch.empty((L, B, HQ, D), dtype=torch.bfloat16, device=dev)
+            q, kn, vn = q.contiguous(), kn.contiguous(), vn.contiguous()
             sync()
-            ctx.step(q.contiguous(), kn.contiguous(), vn.contiguous(), out)
+            how = rng.choice(["step", "prefetch first", "append first", "no prefetch"])
+            if how == "step":
+                ctx.step(q, kn, vn, out)
+            else:                                   # the same step through the per-layer calls, in varying order
+                for layer in range(L):
+                    if how == "prefetch first":
+                        ctx.kv_prefetch(layer)
+                    if rng.random() < 0.5:
+                        ctx.kv_append_batch(layer, kn[layer], vn[layer])
+                    else:
+                        for i, r in enumerate(order):
+                            ctx.kv_append(r, layer, kn[layer, i], vn[layer, i])
+                    if how == "append first":
+                        ctx.kv_prefetch(layer)
+                    ctx.decode_attention(layer, q[layer], out[layer], None)
             sync()
             for r in order:
                 length[r] += 1

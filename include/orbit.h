@@ -43,6 +43,8 @@ extern "C" {
 #define ORBIT_E_NOT_FOUND     -4  /* unknown request id                                        */
 #define ORBIT_E_STATE         -5  /* call not valid now (no plan, window expired, ...)         */
 #define ORBIT_E_HIP           -6  /* a HIP runtime call failed                                 */
+#define ORBIT_E_NOMEM         -7  /* a host allocation failed; the call changed nothing it can
+                                     undo, but the context should be destroyed                 */
 
 #define ORBIT_MAX_LAYERS   128
 #define ORBIT_MAX_REQUESTS 256

@@ -17,13 +17,13 @@ from . import build as _build
 
 ORBIT_OK = 0
 ORBIT_E_INVAL, ORBIT_E_CAPACITY, ORBIT_E_HOST_CAPACITY = -1, -2, -3
-ORBIT_E_NOT_FOUND, ORBIT_E_STATE, ORBIT_E_HIP = -4, -5, -6
+ORBIT_E_NOT_FOUND, ORBIT_E_STATE, ORBIT_E_HIP, ORBIT_E_NOMEM = -4, -5, -6, -7
 ORBIT_MAX_LAYERS, ORBIT_MAX_REQUESTS = 128, 256
 ORBIT_FLAG_HOST_ONLY = 1
 ORBIT_FLAG_ZERO_COPY = 2
 
 _ERR_NAMES = {-1: "ORBIT_E_INVAL", -2: "ORBIT_E_CAPACITY", -3: "ORBIT_E_HOST_CAPACITY",
-              -4: "ORBIT_E_NOT_FOUND", -5: "ORBIT_E_STATE", -6: "ORBIT_E_HIP"}
+              -4: "ORBIT_E_NOT_FOUND", -5: "ORBIT_E_STATE", -6: "ORBIT_E_HIP", -7: "ORBIT_E_NOMEM"}
 
 
 class OrbitError(RuntimeError):

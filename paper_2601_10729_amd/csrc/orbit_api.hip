@@ -325,7 +325,7 @@ extern "C" {
 const char *orbit_last_error(orbit_ctx *ctx) { return ctx ? ctx->err.c_str() : g_create_error.c_str(); }
 
 int orbit_plan_check(int32_t n_req, int32_t n_layers, int32_t page_tokens, const int32_t *ctx_len,
-                     const uint8_t *placement_bitmap, int32_t prefetch_slots, int32_t decode_window, int64_t *out4) {
+                     const uint8_t *placement_bitmap, int32_t prefetch_slots, int32_t decode_window, int64_t *out4) try {
   if (n_req < 0 || n_layers < 1 || page_tokens < 1 || prefetch_slots < 0 || decode_window < 0 || !out4) return ORBIT_E_INVAL;
   if (n_req > 0 && (!ctx_len || !placement_bitmap)) return ORBIT_E_INVAL;
   std::vector<int64_t> b(n_req);
@@ -341,64 +341,80 @@ int orbit_plan_check(int32_t n_req, int32_t n_layers, int32_t page_tokens, const
   out4[2] = e.resident + (int64_t)prefetch_slots * e.buffer;
   out4[3] = e.host;
   return ORBIT_OK;
+} catch (const std::exception &) {
+  return ORBIT_E_NOMEM;
 }
 
-int orbit_deposit_create(double slo_interval, orbit_deposit **out) {
+int orbit_deposit_create(double slo_interval, orbit_deposit **out) try {
   if (!out || !(slo_interval > 0.0)) return ORBIT_E_INVAL;
   *out = new orbit_deposit();
   (*out)->d.slo = slo_interval;
   return ORBIT_OK;
+} catch (const std::exception &) {
+  return ORBIT_E_NOMEM;
 }
 int orbit_deposit_destroy(orbit_deposit *d) {
   if (!d) return ORBIT_E_INVAL;
   delete d;
   return ORBIT_OK;
 }
-int orbit_deposit_push(orbit_deposit *d, int32_t token, double now) {
+int orbit_deposit_push(orbit_deposit *d, int32_t token, double now) try {
   if (!d) return ORBIT_E_INVAL;
   if (d->d.finished) return ORBIT_E_STATE;
   if (!d->d.gen.empty() && now < d->d.gen.back()) return ORBIT_E_INVAL;
   d->d.push(token, now);
   return ORBIT_OK;
+} catch (const std::exception &) {
+  return ORBIT_E_NOMEM;
 }
-int orbit_deposit_finish(orbit_deposit *d, double now) {
+int orbit_deposit_finish(orbit_deposit *d, double now) try {
   if (!d) return ORBIT_E_INVAL;
   d->d.finished = true;
   d->d.finish_time = now;
   return ORBIT_OK;
+} catch (const std::exception &) {
+  return ORBIT_E_NOMEM;
 }
-int64_t orbit_deposit_release(orbit_deposit *d, double now, int32_t *tokens_out, double *times_out, int64_t cap) {
+int64_t orbit_deposit_release(orbit_deposit *d, double now, int32_t *tokens_out, double *times_out, int64_t cap) try {
   if (!d || cap < 0 || (cap > 0 && (!tokens_out || !times_out))) return ORBIT_E_INVAL;
   int64_t n = 0;
   while (n < cap && d->d.pop_due(now, tokens_out + n, times_out + n)) ++n;
   return n;
+} catch (const std::exception &) {
+  return ORBIT_E_NOMEM;
 }
-int orbit_deposit_stats(orbit_deposit *d, int64_t *out4) {
+int orbit_deposit_stats(orbit_deposit *d, int64_t *out4) try {
   if (!d || !out4) return ORBIT_E_INVAL;
   out4[0] = (int64_t)d->d.tok.size();
   out4[1] = d->d.delivered;
   out4[2] = d->d.visible_violations;
   out4[3] = d->d.max_size;
   return ORBIT_OK;
+} catch (const std::exception &) {
+  return ORBIT_E_NOMEM;
 }
 int orbit_profile_mismatch(double predicted, double observed, double fraction) {
   return profile_mismatch(predicted, observed, fraction) ? 1 : 0;
 }
-int orbit_profile_ewma(double *profile, const double *observed, int64_t n, double weight) {
+int orbit_profile_ewma(double *profile, const double *observed, int64_t n, double weight) try {
   if (n < 0 || (n > 0 && (!profile || !observed)) || !(weight >= 0.0 && weight <= 1.0)) return ORBIT_E_INVAL;
   profile_ewma(profile, observed, n, weight);
   return ORBIT_OK;
+} catch (const std::exception &) {
+  return ORBIT_E_NOMEM;
 }
 
-int orbit_distance_options(int32_t n_layers, int32_t *counts_out, int32_t cap) {
+int orbit_distance_options(int32_t n_layers, int32_t *counts_out, int32_t cap) try {
   if (n_layers < 1 || n_layers > ORBIT_MAX_LAYERS) return ORBIT_E_INVAL;
   std::vector<int> v = distance_counts(n_layers);
   if (counts_out)
     for (int i = 0; i < (int)v.size() && i < cap; ++i) counts_out[i] = v[i];
   return (int)v.size();
+} catch (const std::exception &) {
+  return ORBIT_E_NOMEM;
 }
 
-int orbit_distance_pattern(int32_t n_layers, int32_t offload_count, uint8_t *row_out) {
+int orbit_distance_pattern(int32_t n_layers, int32_t offload_count, uint8_t *row_out) try {
   if (n_layers < 1 || n_layers > ORBIT_MAX_LAYERS || offload_count < 0 || offload_count > n_layers || !row_out)
     return ORBIT_E_INVAL;
   std::vector<uint8_t> x(n_layers);
@@ -407,6 +423,8 @@ int orbit_distance_pattern(int32_t n_layers, int32_t offload_count, uint8_t *row
   for (int l = 0; l < n_layers; ++l)
     if (x[l]) row_out[l / 8] |= (uint8_t)(1u << (l % 8));
   return ORBIT_OK;
+} catch (const std::exception &) {
+  return ORBIT_E_NOMEM;
 }
 
 static bool planner_args_ok(int32_t n_req, int32_t n_layers, const int64_t *blocks, double bw, const double *comp) {
@@ -420,7 +438,7 @@ static bool planner_args_ok(int32_t n_req, int32_t n_layers, const int64_t *bloc
 }
 
 int orbit_model_latency(int32_t n_req, int32_t n_layers, const int64_t *blocks, const uint8_t *placement_bitmap,
-                        double blocks_per_time, const double *comp, double *stall_out, double *t_batch) {
+                        double blocks_per_time, const double *comp, double *stall_out, double *t_batch) try {
   if (!planner_args_ok(n_req, n_layers, blocks, blocks_per_time, comp) || !t_batch) return ORBIT_E_INVAL;
   if (n_req > 0 && !placement_bitmap) return ORBIT_E_INVAL;
   std::vector<uint8_t> x((size_t)n_req * n_layers);
@@ -428,11 +446,13 @@ int orbit_model_latency(int32_t n_req, int32_t n_layers, const int64_t *blocks, 
     for (int l = 0; l < n_layers; ++l) x[(size_t)r * n_layers + l] = bitmap_get(placement_bitmap, n_layers, r, l);
   *t_batch = simulate_prefetch(n_req, n_layers, x.data(), blocks, blocks_per_time, comp, stall_out);
   return ORBIT_OK;
+} catch (const std::exception &) {
+  return ORBIT_E_NOMEM;
 }
 
 int orbit_plan_search(int32_t n_req, int32_t n_layers, const int64_t *blocks, int64_t gpu_blocks, int32_t prefetch_slots,
                       double blocks_per_time, const double *comp, int64_t max_evals, uint8_t *bitmap_out,
-                      double *t_batch, int64_t *evals_out) {
+                      double *t_batch, int64_t *evals_out) try {
   if (!planner_args_ok(n_req, n_layers, blocks, blocks_per_time, comp) || prefetch_slots < 1 || gpu_blocks < 0 ||
       max_evals < 1 || !t_batch || (n_req > 0 && !bitmap_out))
     return ORBIT_E_INVAL;
@@ -446,12 +466,16 @@ int orbit_plan_search(int32_t n_req, int32_t n_layers, const int64_t *blocks, in
     for (int l = 0; l < n_layers; ++l)
       if (res.x[(size_t)r * n_layers + l]) bitmap_out[r * bpr + l / 8] |= (uint8_t)(1u << (l % 8));
   return ORBIT_OK;
+} catch (const std::exception &) {
+  return ORBIT_E_NOMEM;
 }
 
-int orbit_planner_create(orbit_planner **out) {
+int orbit_planner_create(orbit_planner **out) try {
   if (!out) return ORBIT_E_INVAL;
   *out = new orbit_planner();
   return ORBIT_OK;
+} catch (const std::exception &) {
+  return ORBIT_E_NOMEM;
 }
 int orbit_planner_destroy(orbit_planner *p) {
   if (!p) return ORBIT_E_INVAL;
@@ -459,7 +483,7 @@ int orbit_planner_destroy(orbit_planner *p) {
   return ORBIT_OK;
 }
 int64_t orbit_planner_submit(orbit_planner *p, int32_t n_req, int32_t n_layers, const int64_t *blocks, int64_t gpu_blocks,
-                             int32_t prefetch_slots, double blocks_per_time, const double *comp, int64_t max_evals) {
+                             int32_t prefetch_slots, double blocks_per_time, const double *comp, int64_t max_evals) try {
   if (!p || !planner_args_ok(n_req, n_layers, blocks, blocks_per_time, comp) || prefetch_slots < 1 || gpu_blocks < 0 ||
       max_evals < 1)
     return ORBIT_E_INVAL;
@@ -473,9 +497,11 @@ int64_t orbit_planner_submit(orbit_planner *p, int32_t n_req, int32_t n_layers, 
   j.blocks.assign(blocks, blocks + n_req);
   j.comp.assign(comp, comp + n_layers);
   return p->a.submit(std::move(j));
+} catch (const std::exception &) {
+  return ORBIT_E_NOMEM;
 }
 int orbit_planner_poll(orbit_planner *p, int32_t wait, int64_t *ticket_out, uint8_t *bitmap_out, int64_t bitmap_cap,
-                       double *t_batch, int64_t *evals_out) {
+                       double *t_batch, int64_t *evals_out) try {
   if (!p) return ORBIT_E_INVAL;
   PlanDone fresh;
   if (p->a.poll(wait != 0, fresh)) {  // a newer result supersedes one the caller could not take
@@ -499,9 +525,11 @@ int orbit_planner_poll(orbit_planner *p, int32_t wait, int64_t *ticket_out, uint
       if (d.res.x[(size_t)r * d.L + l]) bitmap_out[r * bpr + l / 8] |= (uint8_t)(1u << (l % 8));
   p->has_held = false;
   return 1;
+} catch (const std::exception &) {
+  return ORBIT_E_NOMEM;
 }
 
-int orbit_create(const orbit_config *cfg, orbit_ctx **out) {
+int orbit_create(const orbit_config *cfg, orbit_ctx **out) try {
   auto bad = [&](const char *m) {
     g_create_error = m;
     return ORBIT_E_INVAL;
@@ -552,6 +580,10 @@ int orbit_create(const orbit_config *cfg, orbit_ctx **out) {
   const int64_t arena_pages = cfg->hbm_arena_bytes / sh.page_bytes;
   if (arena_pages > 0x7FFFFFF0) return bad("hbm arena has too many pages");
   if (cfg->host_arena_bytes / sh.page_bytes > 0x7FFFFFF0) return bad("host arena has too many pages");
+  if ((int64_t)sh.max_req * sh.max_chunks * sh.Hkv > 0x7FFFFFF0)
+    return bad("max_requests x max_tokens_per_request / chunk_tokens x n_kv_heads exceeds 2^31 work items");
+  if ((int64_t)sh.max_req * sh.L * sh.cap_pages > ((int64_t)1 << 34))
+    return bad("page table (max_requests x n_layers x blocks per request) would exceed 2^34 entries");
   c->hs.init(sh, arena_pages, cfg->host_arena_bytes / sh.page_bytes);
   c->host_dirty.assign(sh.L, 0);
   c->copy_timed.assign(sh.L, 0);
@@ -615,6 +647,9 @@ int orbit_create(const orbit_config *cfg, orbit_ctx **out) {
   }
   *out = c.release();
   return ORBIT_OK;
+} catch (const std::exception &e) {
+  g_create_error = std::string("host allocation failed: ") + e.what();
+  return ORBIT_E_NOMEM;
 }
 
 int orbit_destroy(orbit_ctx *c) {
@@ -657,7 +692,7 @@ int orbit_destroy(orbit_ctx *c) {
 }
 
 int orbit_plan_load(orbit_ctx *c, int32_t n_req, const int64_t *req_ids, const int32_t *ctx_len,
-                    const uint8_t *placement_bitmap, int64_t hbm_budget_bytes) {
+                    const uint8_t *placement_bitmap, int64_t hbm_budget_bytes) try {
   if (!c) return ORBIT_E_INVAL;
   for (auto &lb : c->hs.live)
     if (!lb.consumed) return set_err(c, ORBIT_E_STATE, "a prefetched layer was never attended; finish it before a new plan");
@@ -667,9 +702,11 @@ int orbit_plan_load(orbit_ctx *c, int32_t n_req, const int64_t *req_ids, const i
   c->items_valid = false;
   std::fill(c->host_dirty.begin(), c->host_dirty.end(), 0);
   return apply_plan_gpu(c, phases);
+} catch (const std::exception &e) {  // nothing may unwind through the C ABI
+  return c ? set_err(c, ORBIT_E_NOMEM, std::string("host allocation failed: ") + e.what()) : ORBIT_E_NOMEM;
 }
 
-int orbit_request_pause(orbit_ctx *c, int64_t req_id) {
+int orbit_request_pause(orbit_ctx *c, int64_t req_id) try {
   if (!c) return ORBIT_E_INVAL;
   if (!c->hs.has_plan) return set_err(c, ORBIT_E_STATE, "no plan installed");
   for (auto &lb : c->hs.live)
@@ -680,19 +717,25 @@ int orbit_request_pause(orbit_ctx *c, int64_t req_id) {
   c->items_valid = false;
   std::fill(c->host_dirty.begin(), c->host_dirty.end(), 0);
   return apply_plan_gpu(c, phases);
+} catch (const std::exception &e) {  // nothing may unwind through the C ABI
+  return c ? set_err(c, ORBIT_E_NOMEM, std::string("host allocation failed: ") + e.what()) : ORBIT_E_NOMEM;
 }
 
-int orbit_request_drop(orbit_ctx *c, int64_t req_id) {
+int orbit_request_drop(orbit_ctx *c, int64_t req_id) try {
   if (!c) return ORBIT_E_INVAL;
   int rc = c->hs.drop_paused(req_id);
   return rc ? set_err(c, rc, c->hs.err) : ORBIT_OK;
+} catch (const std::exception &e) {  // nothing may unwind through the C ABI
+  return c ? set_err(c, ORBIT_E_NOMEM, std::string("host allocation failed: ") + e.what()) : ORBIT_E_NOMEM;
 }
 
-int orbit_get_plan_info(orbit_ctx *c, orbit_plan_info *out) {
+int orbit_get_plan_info(orbit_ctx *c, orbit_plan_info *out) try {
   if (!c || !out) return ORBIT_E_INVAL;
   if (!c->hs.has_plan) return set_err(c, ORBIT_E_STATE, "no plan installed");
   *out = c->hs.info;
   return ORBIT_OK;
+} catch (const std::exception &e) {  // nothing may unwind through the C ABI
+  return c ? set_err(c, ORBIT_E_NOMEM, std::string("host allocation failed: ") + e.what()) : ORBIT_E_NOMEM;
 }
 
 static int fill_or_read(orbit_ctx *c, bool write, int64_t req_id, int32_t layer, int64_t first, int64_t n, void *k, void *v) {
@@ -726,13 +769,17 @@ static int fill_or_read(orbit_ctx *c, bool write, int64_t req_id, int32_t layer,
 }
 
 int orbit_kv_fill(orbit_ctx *c, int64_t req_id, int32_t layer, int64_t first_token, int64_t n_tokens, const void *k,
-                  const void *v) {
+                  const void *v) try {
   return fill_or_read(c, true, req_id, layer, first_token, n_tokens, (void *)k, (void *)v);
+} catch (const std::exception &e) {  // nothing may unwind through the C ABI
+  return c ? set_err(c, ORBIT_E_NOMEM, std::string("host allocation failed: ") + e.what()) : ORBIT_E_NOMEM;
 }
 
 int orbit_kv_read(orbit_ctx *c, int64_t req_id, int32_t layer, int64_t first_token, int64_t n_tokens, void *k_out,
-                  void *v_out) {
+                  void *v_out) try {
   return fill_or_read(c, false, req_id, layer, first_token, n_tokens, k_out, v_out);
+} catch (const std::exception &e) {  // nothing may unwind through the C ABI
+  return c ? set_err(c, ORBIT_E_NOMEM, std::string("host allocation failed: ") + e.what()) : ORBIT_E_NOMEM;
 }
 
 // Bookkeeping of one appended token; returns the kernel item.
@@ -797,7 +844,7 @@ static int append_layer(orbit_ctx *c, int l, const uint16_t *k, const uint16_t *
   return ORBIT_OK;
 }
 
-int orbit_kv_append_batch(orbit_ctx *c, int32_t layer, const void *k, const void *v) {
+int orbit_kv_append_batch(orbit_ctx *c, int32_t layer, const void *k, const void *v) try {
   int rc = check_layer(c, layer);
   if (rc) return rc;
   if (!c->host_only && (!k || !v)) return set_err(c, ORBIT_E_INVAL, "null argument");
@@ -806,9 +853,11 @@ int orbit_kv_append_batch(orbit_ctx *c, int32_t layer, const void *k, const void
       return set_err(c, ORBIT_E_STATE, "decode window used up: a request needs a block the plan did not reserve");
   if ((rc = wait_for_live_copy(c, layer))) return rc;
   return append_layer(c, layer, (const uint16_t *)k, (const uint16_t *)v, true);
+} catch (const std::exception &e) {  // nothing may unwind through the C ABI
+  return c ? set_err(c, ORBIT_E_NOMEM, std::string("host allocation failed: ") + e.what()) : ORBIT_E_NOMEM;
 }
 
-int orbit_kv_append(orbit_ctx *c, int64_t req_id, int32_t layer, const void *k, const void *v) {
+int orbit_kv_append(orbit_ctx *c, int64_t req_id, int32_t layer, const void *k, const void *v) try {
   int rc = check_layer(c, layer);
   if (rc) return rc;
   if (!k || !v) return set_err(c, ORBIT_E_INVAL, "null argument");
@@ -832,26 +881,32 @@ int orbit_kv_append(orbit_ctx *c, int64_t req_id, int32_t layer, const void *k, 
   ap.r0 = r;
   HIPCHECK(c, launch_append(ap, c->cs));
   return ORBIT_OK;
+} catch (const std::exception &e) {  // nothing may unwind through the C ABI
+  return c ? set_err(c, ORBIT_E_NOMEM, std::string("host allocation failed: ") + e.what()) : ORBIT_E_NOMEM;
 }
 
-int orbit_kv_prefetch(orbit_ctx *c, int32_t layer) {
+int orbit_kv_prefetch(orbit_ctx *c, int32_t layer) try {
   int rc = check_layer(c, layer);
   if (rc) return rc;
   rc = prefetch_impl(c, layer);
   if (rc == 1) return set_err(c, ORBIT_E_STATE, "staging range still needed by a prefetched layer not yet attended");
   return rc;
+} catch (const std::exception &e) {  // nothing may unwind through the C ABI
+  return c ? set_err(c, ORBIT_E_NOMEM, std::string("host allocation failed: ") + e.what()) : ORBIT_E_NOMEM;
 }
 
-int orbit_decode_attention(orbit_ctx *c, int32_t layer, const void *q, void *out, float *out_f32) {
+int orbit_decode_attention(orbit_ctx *c, int32_t layer, const void *q, void *out, float *out_f32) try {
   int rc = check_layer(c, layer);
   if (rc) return rc;
   if (c->hs.reqs.empty()) return set_err(c, ORBIT_E_STATE, "the plan has no request");
   if (!c->host_only && (!q || !out)) return set_err(c, ORBIT_E_INVAL, "null argument");
   c->timing = false;
   return attention_impl(c, layer, q, out, out_f32, false);
+} catch (const std::exception &e) {  // nothing may unwind through the C ABI
+  return c ? set_err(c, ORBIT_E_NOMEM, std::string("host allocation failed: ") + e.what()) : ORBIT_E_NOMEM;
 }
 
-int orbit_step(orbit_ctx *c, const void *q, const void *k_new, const void *v_new, void *out, orbit_step_stats *stats) {
+int orbit_step(orbit_ctx *c, const void *q, const void *k_new, const void *v_new, void *out, orbit_step_stats *stats) try {
   if (!c) return ORBIT_E_INVAL;
   HostState &hs = c->hs;
   if (!hs.has_plan || hs.reqs.empty()) return set_err(c, ORBIT_E_STATE, "no plan (or an empty one) installed");
@@ -942,10 +997,12 @@ int orbit_step(orbit_ctx *c, const void *q, const void *k_new, const void *v_new
   }
   c->timing = false;
   return ORBIT_OK;
+} catch (const std::exception &e) {  // nothing may unwind through the C ABI
+  return c ? set_err(c, ORBIT_E_NOMEM, std::string("host allocation failed: ") + e.what()) : ORBIT_E_NOMEM;
 }
 
 int64_t orbit_get_pages(orbit_ctx *c, int64_t req_id, int32_t layer, int32_t *tier, int64_t *host_first_page,
-                        int32_t *length, int32_t *pages_out, int64_t cap) {
+                        int32_t *length, int32_t *pages_out, int64_t cap) try {
   int rc = check_layer(c, layer);
   if (rc) return rc;
   const int r = c->hs.find(req_id);
@@ -961,9 +1018,11 @@ int64_t orbit_get_pages(orbit_ctx *c, int64_t req_id, int32_t layer, int32_t *ti
     for (int64_t i = 0; i < n && i < cap; ++i)
       pages_out[i] = lk.tier == 1 ? lk.pages[i] : (r >= 0 && lk.stage_page0 >= 0 ? lk.stage_page0 + (int32_t)i : -1);
   return n;
+} catch (const std::exception &e) {  // nothing may unwind through the C ABI
+  return c ? set_err(c, ORBIT_E_NOMEM, std::string("host allocation failed: ") + e.what()) : ORBIT_E_NOMEM;
 }
 
-int64_t orbit_get_work_items(orbit_ctx *c, int32_t layer, int32_t *items_out, int64_t cap) {
+int64_t orbit_get_work_items(orbit_ctx *c, int32_t layer, int32_t *items_out, int64_t cap) try {
   int rc = check_layer(c, layer);
   if (rc) return rc;
   std::vector<int32_t> items;
@@ -973,9 +1032,11 @@ int64_t orbit_get_work_items(orbit_ctx *c, int32_t layer, int32_t *items_out, in
   if (items_out)
     for (int64_t i = 0; i < n * 4 && i < cap * 4; ++i) items_out[i] = items[i];
   return n;
+} catch (const std::exception &e) {  // nothing may unwind through the C ABI
+  return c ? set_err(c, ORBIT_E_NOMEM, std::string("host allocation failed: ") + e.what()) : ORBIT_E_NOMEM;
 }
 
-int64_t orbit_get_copy_schedule(orbit_ctx *c, int32_t *rows_out, int64_t cap) {
+int64_t orbit_get_copy_schedule(orbit_ctx *c, int32_t *rows_out, int64_t cap) try {
   if (!c) return ORBIT_E_INVAL;
   if (!c->hs.has_plan) return set_err(c, ORBIT_E_STATE, "no plan installed");
   int64_t n = 0;
@@ -992,6 +1053,8 @@ int64_t orbit_get_copy_schedule(orbit_ctx *c, int32_t *rows_out, int64_t cap) {
       ++n;
     }
   return n;
+} catch (const std::exception &e) {  // nothing may unwind through the C ABI
+  return c ? set_err(c, ORBIT_E_NOMEM, std::string("host allocation failed: ") + e.what()) : ORBIT_E_NOMEM;
 }
 
 }  // extern "C"

@@ -42,7 +42,11 @@ def test_library_exports_every_declared_symbol():
 
 def test_create_rejects_unsupported_shapes():
     for kw in (dict(head_dim=64), dict(page_tokens=32), dict(n_q_heads=30), dict(n_q_heads=136, n_kv_heads=8),
-               dict(chunk_tokens=100), dict(prefetch_slots=0), dict(max_requests=0)):
+               dict(chunk_tokens=100), dict(prefetch_slots=0), dict(max_requests=0),
+               # index ranges: work items beyond 2^31, a page table beyond 2^34 entries
+               dict(max_tokens_per_request=1 << 24, chunk_tokens=32, n_kv_heads=128, n_q_heads=128, n_layers=128,
+                    max_requests=256),
+               dict(max_tokens_per_request=1 << 24, n_layers=128, max_requests=256)):
         args = dict(n_layers=2, n_q_heads=32, n_kv_heads=8, max_requests=4, max_tokens_per_request=1024,
                     host_only=True, hbm_arena_bytes=PAGE * 64, host_arena_bytes=PAGE * 64)
         args.update(kw)

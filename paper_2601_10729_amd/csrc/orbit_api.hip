@@ -831,7 +831,7 @@ static int append_layer(orbit_ctx *c, int l, const uint16_t *k, const uint16_t *
     if (c->host_only) continue;
     ap.arena = c->arena;
     ap.lens = c->d_len;
-    ap.k = k + (int64_t)r0 * sh.Hkv * sh.D;
+    ap.k = k + (int64_t)r0 * sh.Hkv * sh.D;  // non-NULL here: host-only contexts left the loop above
     ap.v = v + (int64_t)r0 * sh.Hkv * sh.D;
     ap.page_bytes = sh.page_bytes;
     ap.L = sh.L;
@@ -955,14 +955,17 @@ int orbit_step(orbit_ctx *c, const void *q, const void *k_new, const void *v_new
       }
     }
     // a3: append this layer's new token of every request (the staging copy is live: it gets the token too)
-    if ((rc = append_layer(c, l, (const uint16_t *)k_new + l * kv_stride, (const uint16_t *)v_new + l * kv_stride, false))) return rc;
+    if ((rc = append_layer(c, l, k_new ? (const uint16_t *)k_new + l * kv_stride : nullptr,
+                           v_new ? (const uint16_t *)v_new + l * kv_stride : nullptr, false)))
+      return rc;
     for (int r = 0; r < nreq; ++r) {
       const LayerKV &lk = hs.reqs[r].layers[l];
       if (lk.tier == 1) hbm_bytes += (int64_t)lk.len * tok_bytes;
       else if (sh.zero_copy) c->copy_bytes[l] += ceil_div(lk.len, sh.P) * sh.page_bytes;  // read over the link by the kernel
     }
     if (b >= 0) find_live(c, l)->consumed = true;
-    rc = attention_impl(c, l, (const uint16_t *)q + l * q_stride, (uint16_t *)out + l * q_stride, nullptr, true);
+    rc = attention_impl(c, l, q ? (const uint16_t *)q + l * q_stride : nullptr, out ? (uint16_t *)out + l * q_stride : nullptr,
+                        nullptr, true);
     if (rc) return rc;
     if (b >= 0 && (rc = pump())) return rc;
   }

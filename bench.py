@@ -103,6 +103,8 @@ def main():
                          "(no staging region, no host->staging copies); a measured alternative, not the default")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-resident-variant", action="store_true")
+    ap.add_argument("--no-searched-variant", action="store_true",
+                    help="do not install and time the plan found by the pruned search")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 1 GiB device-to-device copies (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -120,7 +122,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     K, W = args.steps, args.warmup
-    total_steps = W + 2 * K + 4          # warm-up, timed, timed-with-events, all-resident variant
+    total_steps = W + 2 * K + 8          # warm-up, timed, timed-with-events, searched-plan and all-resident variants
     from paper_2601_10729_amd import orbit_plan_check
     n_req = args.n_req
     while True:
@@ -144,8 +146,12 @@ def main():
     pages = (max(need, all_res) if fits_resident else need) + 8
     if w.hbm_budget_bytes is not None:
         pages = max(pages, w.hbm_budget_bytes // w.page_bytes)
+    # head-room in the pinned arena for the switch to the searched plan: its demotions are placed
+    # before the promotions release the old runs, so both splits are held for a moment
+    host_pages = min(int(host_blocks * 2.2) + 8, int(args.max_host_gib * (1 << 30)) // w.page_bytes)
+    host_pages = max(host_pages, host_blocks + 8)
     g = harness.GpuRun(w, prefetch_slots=slots, chunk_tokens=args.chunk_tokens,
-                       budget_pages=pages, host_pages=host_blocks + 8, zero_copy=args.zero_copy,
+                       budget_pages=pages, host_pages=host_pages, zero_copy=args.zero_copy,
                        max_tokens=int(w.ctx_len.max()) + 2 * total_steps + 32)
     B, L = w.n_req, w.n_layers
     # per-step inputs, generated once and resident in HBM: [S][L][B][...]
@@ -252,16 +258,40 @@ def main():
         pred, _ = orbit_model_latency(b_now, w.placement, blocks_per_ms, per_layer)
         t_s = time.perf_counter()
         try:
-            t_plan, x_plan, evals = orbit_plan_search(b_now, L, need, blocks_per_ms,
-                                                      per_layer, prefetch_slots=slots, max_evals=20000)
+            t_paper, x_paper, evals = orbit_plan_search(b_now, L, need, blocks_per_ms,
+                                                        per_layer, prefetch_slots=slots, max_evals=20000)
+            search_ms = (time.perf_counter() - t_s) * 1e3
+            # the same counts and distances with request r's pattern rotated by r layers (ours): installed below
+            t_plan, x_plan, _ = orbit_plan_search(b_now, L, need, blocks_per_ms, per_layer, prefetch_slots=slots,
+                                                  max_evals=20000, stagger=True)
             planner = {"predicted_ms_for_this_placement": pred, "observed_ms": ms_per_step_events,
                        "relative_gap": abs(pred - ms_per_step_events) / pred,
+                       "paper_space_plan_predicted_ms": t_paper, "paper_space_plan_resident_fraction":
+                       float((x_paper * b_now[:, None]).sum() / (b_now.sum() * L)),
                        "searched_plan_predicted_ms": t_plan, "searched_plan_resident_fraction":
                        float((x_plan * b_now[:, None]).sum() / (b_now.sum() * L)),
-                       "search_budget_blocks": need, "search_evaluations": evals, "search_ms": (time.perf_counter() - t_s) * 1e3}
+                       "searched_plan_space": "distance-driven counts, staggered by request",
+                       "search_budget_blocks": need, "search_evaluations": evals, "search_ms": search_ms}
         except Exception as e:                                   # infeasible under the pruned space
             planner = {"predicted_ms_for_this_placement": pred, "observed_ms": ms_per_step_events,
                        "relative_gap": abs(pred - ms_per_step_events) / pred, "search": str(e)}
+
+    # closing the loop: install the searched plan (a stream-ordered switch) and time it against its prediction
+    if planner and "searched_plan_predicted_ms" in planner and not args.no_searched_variant and fits_resident:
+        try:
+            drain()
+            cur = w.ctx_len.astype(np.int64) + step_no[0]
+            g.ctx.plan_load(w.req_ids, cur.astype(np.int32), x_plan)
+            run_step()
+            drain()
+            sts = [run_step(True) for _ in range(3)]
+            drain()
+            obs = float(np.mean([s.step_ms for s in sts]))
+            planner["searched_plan_observed_ms"] = obs
+            planner["searched_plan_relative_gap"] = abs(obs - t_plan) / t_plan
+        except Exception as e:                                   # e.g. the host arena cannot hold its offloaded blocks
+            planner["searched_plan_observed_ms"] = None
+            planner["searched_plan_note"] = str(e)
 
     # all-resident variant of the same workload: the kernel's HBM rate without the link in the way
     resident = None

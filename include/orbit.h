@@ -261,6 +261,15 @@ ORBIT_API int orbit_plan_search(int32_t n_req, int32_t n_layers, const int64_t *
                                 int32_t prefetch_slots, double blocks_per_time, const double *comp,
                                 int64_t max_evals, uint8_t *bitmap_out, double *t_batch, int64_t *evals_out);
 
+/* The same search over a wider space of our own: request r (plan order) takes its distance-driven
+ * pattern rotated right by r layers.  Counts and distances are the paper's; the rotation keeps
+ * requests from offloading the same layers, which shrinks B_buf in Eq. (1) and evens out the
+ * link load.  Same arguments, results and errors as orbit_plan_search. */
+ORBIT_API int orbit_plan_search_staggered(int32_t n_req, int32_t n_layers, const int64_t *blocks, int64_t gpu_blocks,
+                                          int32_t prefetch_slots, double blocks_per_time, const double *comp,
+                                          int64_t max_evals, uint8_t *bitmap_out, double *t_batch,
+                                          int64_t *evals_out);
+
 /* Background planner (Section 4: the planner runs in its own thread and solves one decode
  * iteration ahead; the executor collects the finished plan in the next iteration and hands it to
  * orbit_plan_load).  One worker thread per handle.  orbit_planner_submit copies its arguments

@@ -175,16 +175,17 @@ def candidate_counts(n_layers: int) -> List[int]:
 
 
 def exhaustive_search(b: Sequence[int], n_layers: int, gpu_blocks: int, prefetch_slots: int,
-                      bandwidth: float, comp: Sequence[float]):
+                      bandwidth: float, comp: Sequence[float], stagger: bool = False):
     """Minimum-latency feasible plan over all per-request candidate combinations; ties go to
-    the lexicographically first index vector.  Returns (T, placement) or (inf, None)."""
+    the lexicographically first index vector.  Returns (T, placement) or (inf, None).
+    ``stagger`` (not in the paper): request r's pattern is rotated right by r layers."""
     import itertools
     from . import reference as ref
     cands = candidate_counts(n_layers)
     pats = [distance_pattern(n_layers, c) for c in cands]
     best_t, best_x = math.inf, None
     for combo in itertools.product(range(len(cands)), repeat=len(b)):
-        x = np.stack([pats[i] for i in combo])
+        x = np.stack([np.roll(pats[i], r % n_layers) if stagger else pats[i] for r, i in enumerate(combo)])
         if not ref.feasible(b, x, gpu_blocks, prefetch_slots):
             continue
         t, _ = simulate_prefetch(x, b, bandwidth, comp)

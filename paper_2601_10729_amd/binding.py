@@ -67,7 +67,7 @@ EXPORTS = ["orbit_create", "orbit_destroy", "orbit_last_error", "orbit_plan_chec
            "orbit_get_plan_info", "orbit_request_pause", "orbit_request_drop", "orbit_kv_fill", "orbit_kv_read", "orbit_kv_append", "orbit_kv_append_batch", "orbit_kv_prefetch",
            "orbit_decode_attention", "orbit_step", "orbit_get_pages", "orbit_get_work_items",
            "orbit_get_copy_schedule", "orbit_distance_options", "orbit_distance_pattern", "orbit_model_latency",
-           "orbit_plan_search", "orbit_planner_create", "orbit_planner_destroy", "orbit_planner_submit",
+           "orbit_plan_search", "orbit_plan_search_staggered", "orbit_planner_create", "orbit_planner_destroy", "orbit_planner_submit",
            "orbit_planner_poll", "orbit_deposit_create", "orbit_deposit_destroy", "orbit_deposit_push",
            "orbit_deposit_finish", "orbit_deposit_release", "orbit_deposit_stats", "orbit_profile_mismatch",
            "orbit_profile_ewma"]
@@ -113,6 +113,7 @@ def lib() -> C.CDLL:
     L.orbit_distance_pattern.argtypes = [i32, i32, u8p]
     L.orbit_model_latency.argtypes = [i32, i32, i64p, u8p, C.c_double, f64p, f64p, f64p]
     L.orbit_plan_search.argtypes = [i32, i32, i64p, i64, i32, C.c_double, f64p, i64, u8p, f64p, i64p]
+    L.orbit_plan_search_staggered.argtypes = L.orbit_plan_search.argtypes
     L.orbit_planner_create.argtypes = [C.POINTER(vp)]
     L.orbit_planner_destroy.argtypes = [vp]
     L.orbit_planner_submit.argtypes = [vp, i32, i32, i64p, i64, i32, C.c_double, f64p, i64]
@@ -204,12 +205,14 @@ def orbit_model_latency(blocks, placement, blocks_per_time: float, comp):
 
 
 def orbit_plan_search(blocks, n_layers: int, gpu_blocks: int, blocks_per_time: float, comp,
-                      prefetch_slots: int = 1, max_evals: int = 100000):
-    """(T_batch, placement [B][L], evaluations) of the best plan in the pruned space."""
+                      prefetch_slots: int = 1, max_evals: int = 100000, stagger: bool = False):
+    """(T_batch, placement [B][L], evaluations) of the best plan in the pruned space; ``stagger``
+    selects orbit_plan_search_staggered (request r's pattern rotated by r layers)."""
     b, cp = _np(blocks, np.int64), _np(comp, np.float64)
     bm = np.zeros((len(b), (n_layers + 7) // 8), dtype=np.uint8)
     t, ev = C.c_double(), C.c_int64()
-    rc = lib().orbit_plan_search(len(b), n_layers, b.ctypes.data_as(C.POINTER(C.c_int64)), int(gpu_blocks),
+    fn = lib().orbit_plan_search_staggered if stagger else lib().orbit_plan_search
+    rc = fn(len(b), n_layers, b.ctypes.data_as(C.POINTER(C.c_int64)), int(gpu_blocks),
                                  prefetch_slots, float(blocks_per_time), cp.ctypes.data_as(C.POINTER(C.c_double)),
                                  int(max_evals), bm.ctypes.data_as(C.POINTER(C.c_uint8)), C.byref(t), C.byref(ev))
     if rc != 0:

@@ -450,13 +450,13 @@ int orbit_model_latency(int32_t n_req, int32_t n_layers, const int64_t *blocks, 
   return ORBIT_E_NOMEM;
 }
 
-int orbit_plan_search(int32_t n_req, int32_t n_layers, const int64_t *blocks, int64_t gpu_blocks, int32_t prefetch_slots,
+static int plan_search_entry(bool stagger, int32_t n_req, int32_t n_layers, const int64_t *blocks, int64_t gpu_blocks, int32_t prefetch_slots,
                       double blocks_per_time, const double *comp, int64_t max_evals, uint8_t *bitmap_out,
-                      double *t_batch, int64_t *evals_out) try {
+                      double *t_batch, int64_t *evals_out) {
   if (!planner_args_ok(n_req, n_layers, blocks, blocks_per_time, comp) || prefetch_slots < 1 || gpu_blocks < 0 ||
       max_evals < 1 || !t_batch || (n_req > 0 && !bitmap_out))
     return ORBIT_E_INVAL;
-  SearchResult res = plan_search(n_req, n_layers, blocks, gpu_blocks, prefetch_slots, blocks_per_time, comp, max_evals);
+  SearchResult res = plan_search(n_req, n_layers, blocks, gpu_blocks, prefetch_slots, blocks_per_time, comp, max_evals, stagger);
   if (evals_out) *evals_out = res.evals;
   if (!(res.t < std::numeric_limits<double>::infinity())) return ORBIT_E_CAPACITY;
   *t_batch = res.t;
@@ -466,6 +466,22 @@ int orbit_plan_search(int32_t n_req, int32_t n_layers, const int64_t *blocks, in
     for (int l = 0; l < n_layers; ++l)
       if (res.x[(size_t)r * n_layers + l]) bitmap_out[r * bpr + l / 8] |= (uint8_t)(1u << (l % 8));
   return ORBIT_OK;
+}
+
+int orbit_plan_search(int32_t n_req, int32_t n_layers, const int64_t *blocks, int64_t gpu_blocks, int32_t prefetch_slots,
+                      double blocks_per_time, const double *comp, int64_t max_evals, uint8_t *bitmap_out,
+                      double *t_batch, int64_t *evals_out) try {
+  return plan_search_entry(false, n_req, n_layers, blocks, gpu_blocks, prefetch_slots, blocks_per_time, comp, max_evals,
+                           bitmap_out, t_batch, evals_out);
+} catch (const std::exception &) {
+  return ORBIT_E_NOMEM;
+}
+
+int orbit_plan_search_staggered(int32_t n_req, int32_t n_layers, const int64_t *blocks, int64_t gpu_blocks,
+                                int32_t prefetch_slots, double blocks_per_time, const double *comp, int64_t max_evals,
+                                uint8_t *bitmap_out, double *t_batch, int64_t *evals_out) try {
+  return plan_search_entry(true, n_req, n_layers, blocks, gpu_blocks, prefetch_slots, blocks_per_time, comp, max_evals,
+                           bitmap_out, t_batch, evals_out);
 } catch (const std::exception &) {
   return ORBIT_E_NOMEM;
 }

@@ -125,8 +125,11 @@ inline bool eq1_fits(int n_req, int L, const uint8_t *x, const int64_t *b, int64
   return resident + (int64_t)slots * buffer <= gpu_blocks;
 }
 
+// stagger: request r takes its pattern rotated right by r layers, so that requests do not all
+// offload the same layers (an extension of the paper's space: same counts and distances, a
+// smaller prefetch buffer and a smoother link load).
 inline SearchResult plan_search(int n_req, int L, const int64_t *b, int64_t gpu_blocks, int slots, double bandwidth,
-                                const double *comp, int64_t max_evals) {
+                                const double *comp, int64_t max_evals, bool stagger = false) {
   SearchResult res;
   std::vector<int> cands{0};
   {
@@ -139,8 +142,12 @@ inline SearchResult plan_search(int n_req, int L, const int64_t *b, int64_t gpu_
   std::vector<std::vector<uint8_t>> pat(nc, std::vector<uint8_t>(L));
   for (int i = 0; i < nc; ++i) distance_pattern(L, cands[i], pat[i].data());
   std::vector<uint8_t> x((size_t)n_req * L);
+  auto put = [&](std::vector<uint8_t> &dst, int r, int i) {  // row r <- candidate i, rotated if staggered
+    const int shift = stagger ? r % L : 0;
+    for (int l = 0; l < L; ++l) dst[(size_t)r * L + (l + shift) % L] = pat[i][l];
+  };
   auto eval = [&](const std::vector<int> &choice) -> double {
-    for (int r = 0; r < n_req; ++r) std::copy(pat[choice[r]].begin(), pat[choice[r]].end(), x.begin() + (size_t)r * L);
+    for (int r = 0; r < n_req; ++r) put(x, r, choice[r]);
     if (!eq1_fits(n_req, L, x.data(), b, gpu_blocks, slots)) return std::numeric_limits<double>::infinity();
     ++res.evals;
     return simulate_prefetch(n_req, L, x.data(), b, bandwidth, comp, nullptr);
@@ -148,7 +155,7 @@ inline SearchResult plan_search(int n_req, int L, const int64_t *b, int64_t gpu_
   auto keep = [&](const std::vector<int> &choice, double t) {
     res.t = t;
     res.x.assign((size_t)n_req * L, 1);
-    for (int r = 0; r < n_req; ++r) std::copy(pat[choice[r]].begin(), pat[choice[r]].end(), res.x.begin() + (size_t)r * L);
+    for (int r = 0; r < n_req; ++r) put(res.x, r, choice[r]);
   };
   double space = 1.0;
   for (int r = 0; r < n_req; ++r) space *= nc;

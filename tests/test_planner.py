@@ -158,6 +158,11 @@ def test_library_search_matches_brute_force_and_picks_the_papers_plan():
             continue
         t, x, _ = orbit.orbit_plan_search(b, L, cap, bw, comp, prefetch_slots=slots)
         assert abs(t - tw) <= 1e-9 * tw and x.tolist() == xw.tolist()
+        # the staggered space (request r's pattern rotated by r layers), against the same brute force
+        ts, xs = lm.exhaustive_search(b, L, cap, slots, bw, comp, stagger=True)
+        t2, x2, _ = orbit.orbit_plan_search(b, L, cap, bw, comp, prefetch_slots=slots, stagger=True)
+        assert abs(t2 - ts) <= 1e-9 * ts and x2.tolist() == xs.tolist()
+        assert sorted((x2 == 0).sum(axis=1).tolist()) != [] and ref.feasible(b, x2, cap, slots)
 
 
 def test_descent_mode_is_feasible_and_not_worse_than_uniform():
@@ -244,3 +249,22 @@ def test_background_planner_runs_while_the_caller_works():
     assert got[1] == want[0] and np.array_equal(got[2], want[1])
     p.submit(b, L, int(b.sum() * L * 0.7), 2.0, comp, max_evals=200000)
     p.close()                                                       # job still running: must not hang or crash
+
+
+def test_staggered_patterns_need_a_smaller_prefetch_buffer():
+    """Same offload counts, rotated per request: Eq. (1)'s B_buf shrinks, so a budget that rejects
+    the aligned plan admits the staggered one, and the search exploits it."""
+    L, n_req = 32, 8
+    b = np.full(n_req, 100)
+    row = lm.distance_pattern(L, 8)                                  # every 4th layer offloaded
+    aligned = np.tile(row, (n_req, 1))
+    rotated = np.stack([np.roll(row, r) for r in range(n_req)])
+    assert ref.prefetch_buffer_blocks(b, aligned) == 800 and ref.prefetch_buffer_blocks(b, rotated) == 200
+    comp, bw = np.full(L, 1.0), 50.0
+    cap = ref.resident_blocks(b, rotated) + 2 * 200                   # fits rotated, not aligned
+    assert ref.feasible(b, rotated, cap, 2) and not ref.feasible(b, aligned, cap, 2)
+    t_plain, _, _ = orbit.orbit_plan_search(b, L, cap, bw, comp, prefetch_slots=2, max_evals=5000)
+    t_stag, x_stag, _ = orbit.orbit_plan_search(b, L, cap, bw, comp, prefetch_slots=2, max_evals=5000, stagger=True)
+    assert ref.feasible(b, x_stag, cap, 2)
+    assert t_stag < t_plain
+    assert abs(t_stag - lm.simulate_prefetch(x_stag, b, bw, comp)[0]) <= 1e-9 * t_stag

@@ -273,7 +273,7 @@ ORBIT_API int orbit_plan_search_staggered(int32_t n_req, int32_t n_layers, const
 /* Background planner (Section 4: the planner runs in its own thread and solves one decode
  * iteration ahead; the executor collects the finished plan in the next iteration and hands it to
  * orbit_plan_load).  One worker thread per handle.  orbit_planner_submit copies its arguments
- * (same meaning as orbit_plan_search) and returns a ticket > 0 at once; a submission replaces
+ * (same meaning as orbit_plan_search; flags: 0 or ORBIT_SEARCH_STAGGER) and returns a ticket > 0 at once; a submission replaces
  * one that has not started yet.  orbit_planner_poll delivers the newest finished plan not yet
  * collected: returns 1 and fills ticket_out / bitmap_out ([n_req][ceil(L/8)], bitmap_cap bytes
  * available) / t_batch / evals_out, 0 if none is ready, ORBIT_E_CAPACITY if that job found
@@ -283,9 +283,10 @@ ORBIT_API int orbit_plan_search_staggered(int32_t n_req, int32_t n_layers, const
 typedef struct orbit_planner orbit_planner;
 ORBIT_API int orbit_planner_create(orbit_planner **out);
 ORBIT_API int orbit_planner_destroy(orbit_planner *p);
+#define ORBIT_SEARCH_STAGGER 1    /* orbit_planner_submit flag: search as orbit_plan_search_staggered does */
 ORBIT_API int64_t orbit_planner_submit(orbit_planner *p, int32_t n_req, int32_t n_layers, const int64_t *blocks,
                                        int64_t gpu_blocks, int32_t prefetch_slots, double blocks_per_time,
-                                       const double *comp, int64_t max_evals);
+                                       const double *comp, int64_t max_evals, int32_t flags);
 ORBIT_API int orbit_planner_poll(orbit_planner *p, int32_t wait, int64_t *ticket_out, uint8_t *bitmap_out,
                                  int64_t bitmap_cap, double *t_batch, int64_t *evals_out);
 

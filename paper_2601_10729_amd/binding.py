@@ -116,7 +116,7 @@ def lib() -> C.CDLL:
     L.orbit_plan_search_staggered.argtypes = L.orbit_plan_search.argtypes
     L.orbit_planner_create.argtypes = [C.POINTER(vp)]
     L.orbit_planner_destroy.argtypes = [vp]
-    L.orbit_planner_submit.argtypes = [vp, i32, i32, i64p, i64, i32, C.c_double, f64p, i64]
+    L.orbit_planner_submit.argtypes = [vp, i32, i32, i64p, i64, i32, C.c_double, f64p, i64, i32]
     L.orbit_planner_submit.restype = i64
     L.orbit_planner_poll.argtypes = [vp, i32, i64p, u8p, i64, f64p, i64p]
     L.orbit_deposit_create.argtypes = [C.c_double, C.POINTER(vp)]
@@ -234,11 +234,11 @@ class BackgroundPlanner:
         self._shape = {}          # ticket -> (n_req, n_layers), to size the bitmap buffer
 
     def submit(self, blocks, n_layers: int, gpu_blocks: int, blocks_per_time: float, comp,
-               prefetch_slots: int = 1, max_evals: int = 100000) -> int:
+               prefetch_slots: int = 1, max_evals: int = 100000, stagger: bool = False) -> int:
         b, cp = _np(blocks, np.int64), _np(comp, np.float64)
         t = self._L.orbit_planner_submit(self._h, len(b), n_layers, b.ctypes.data_as(C.POINTER(C.c_int64)),
                                          int(gpu_blocks), prefetch_slots, float(blocks_per_time),
-                                         cp.ctypes.data_as(C.POINTER(C.c_double)), int(max_evals))
+                                         cp.ctypes.data_as(C.POINTER(C.c_double)), int(max_evals), 1 if stagger else 0)
         if t <= 0:
             raise OrbitError(int(t), "orbit_planner_submit")
         self._shape[int(t)] = (len(b), n_layers)

@@ -499,9 +499,10 @@ int orbit_planner_destroy(orbit_planner *p) {
   return ORBIT_OK;
 }
 int64_t orbit_planner_submit(orbit_planner *p, int32_t n_req, int32_t n_layers, const int64_t *blocks, int64_t gpu_blocks,
-                             int32_t prefetch_slots, double blocks_per_time, const double *comp, int64_t max_evals) try {
+                             int32_t prefetch_slots, double blocks_per_time, const double *comp, int64_t max_evals,
+                             int32_t flags) try {
   if (!p || !planner_args_ok(n_req, n_layers, blocks, blocks_per_time, comp) || prefetch_slots < 1 || gpu_blocks < 0 ||
-      max_evals < 1)
+      max_evals < 1 || (flags & ~ORBIT_SEARCH_STAGGER))
     return ORBIT_E_INVAL;
   PlanJob j;
   j.n_req = n_req;
@@ -510,6 +511,7 @@ int64_t orbit_planner_submit(orbit_planner *p, int32_t n_req, int32_t n_layers, 
   j.gpu_blocks = gpu_blocks;
   j.max_evals = max_evals;
   j.bandwidth = blocks_per_time;
+  j.stagger = (flags & ORBIT_SEARCH_STAGGER) != 0;
   j.blocks.assign(blocks, blocks + n_req);
   j.comp.assign(comp, comp + n_layers);
   return p->a.submit(std::move(j));

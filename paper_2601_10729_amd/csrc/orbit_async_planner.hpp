@@ -19,6 +19,7 @@ struct PlanJob {
   int n_req = 0, L = 0, slots = 1;
   int64_t gpu_blocks = 0, max_evals = 0;
   double bandwidth = 0;
+  bool stagger = false;
   std::vector<int64_t> blocks;
   std::vector<double> comp;
 };
@@ -78,7 +79,7 @@ class AsyncPlanner {
       d.n_req = job.n_req;
       d.L = job.L;
       d.res = plan_search(job.n_req, job.L, job.blocks.data(), job.gpu_blocks, job.slots, job.bandwidth,
-                          job.comp.data(), job.max_evals);
+                          job.comp.data(), job.max_evals, job.stagger);
       {
         std::lock_guard<std::mutex> g(mu_);
         done_ = std::move(d);

@@ -196,11 +196,12 @@ def test_background_planner_delivers_the_same_plans_one_iteration_later():
     for it in range(6):
         b = rng.integers(1, 30, size=4)
         budget = int(b.sum() * L * rng.uniform(0.4, 1.0))
-        t = p.submit(b, L, budget, 3.0, comp, prefetch_slots=1 + it % 2)
+        stag = it % 3 == 0
+        t = p.submit(b, L, budget, 3.0, comp, prefetch_slots=1 + it % 2, stagger=stag)
         assert t > last
         last = t
         try:
-            want = orbit.orbit_plan_search(b, L, budget, 3.0, comp, prefetch_slots=1 + it % 2)
+            want = orbit.orbit_plan_search(b, L, budget, 3.0, comp, prefetch_slots=1 + it % 2, stagger=stag)
         except orbit.OrbitError as e:
             assert e.code == orbit.ORBIT_E_CAPACITY
             with pytest.raises(orbit.OrbitError) as e2:

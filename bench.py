@@ -256,6 +256,15 @@ def main():
         blocks_per_ms = (link_bytes / (sum(copy_ms) * 1e-3) / 1e3) / w.page_bytes
         b_now = -(-(w.ctx_len.astype(np.int64) + W + 2 * K) // w.page_tokens)
         pred, _ = orbit_model_latency(b_now, w.placement, blocks_per_ms, per_layer)
+        # profile refresh as the controller would do it: moving average of the per-layer compute times over the
+        # timed steps, and the re-planning trigger on the gap between prediction and observation
+        from paper_2601_10729_amd import orbit_profile_ewma, orbit_profile_mismatch
+        per_step = (np.asarray(attn_ms, dtype=np.float64) + np.asarray(comb_ms, dtype=np.float64)).reshape(K, L)
+        profile = per_step[0].copy()
+        for row in per_step[1:]:
+            profile = orbit_profile_ewma(profile, row, 0.25)
+        pred_ewma, _ = orbit_model_latency(b_now, w.placement, blocks_per_ms, profile)
+        replan = bool(orbit_profile_mismatch(pred_ewma, ms_per_step_events, 0.05))
         t_s = time.perf_counter()
         try:
             t_paper, x_paper, evals = orbit_plan_search(b_now, L, need, blocks_per_ms,
@@ -271,6 +280,7 @@ def main():
                        "searched_plan_predicted_ms": t_plan, "searched_plan_resident_fraction":
                        float((x_plan * b_now[:, None]).sum() / (b_now.sum() * L)),
                        "searched_plan_space": "distance-driven counts, staggered by request",
+                       "ewma_profile_predicted_ms": pred_ewma, "replan_triggered_at_5_percent": replan,
                        "search_budget_blocks": need, "search_evaluations": evals, "search_ms": search_ms}
         except Exception as e:                                   # infeasible under the pruned space
             planner = {"predicted_ms_for_this_placement": pred, "observed_ms": ms_per_step_events,

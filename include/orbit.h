@@ -261,6 +261,9 @@ ORBIT_API int orbit_plan_search(int32_t n_req, int32_t n_layers, const int64_t *
                                 int32_t prefetch_slots, double blocks_per_time, const double *comp,
                                 int64_t max_evals, uint8_t *bitmap_out, double *t_batch, int64_t *evals_out);
 
+#define ORBIT_SEARCH_STAGGER 1    /* flag of orbit_plan_search_or_pause and orbit_planner_submit: search the
+                                     staggered space of orbit_plan_search_staggered                */
+
 /* The same search over a wider space of our own: request r (plan order) takes its distance-driven
  * pattern rotated right by r layers.  Counts and distances are the paper's; the rotation keeps
  * requests from offloading the same layers, which shrinks B_buf in Eq. (1) and evens out the
@@ -269,6 +272,19 @@ ORBIT_API int orbit_plan_search_staggered(int32_t n_req, int32_t n_layers, const
                                           int32_t prefetch_slots, double blocks_per_time, const double *comp,
                                           int64_t max_evals, uint8_t *bitmap_out, double *t_batch,
                                           int64_t *evals_out);
+
+/* Pause-Resume fallback (Section 3.4) in its capacity form: when no placement of the batch
+ * satisfies Eq. (1), the request with the largest sum of KV blocks and deposited tokens is
+ * paused (ties: the later request) and the search runs again on the rest, until a plan exists.
+ * deposited_tokens[r] >= 0: tokens waiting in request r's Token-Deposit.  flags: 0 or
+ * ORBIT_SEARCH_STAGGER.  paused_out[r] = 1 marks the victims (hand them to orbit_request_pause and
+ * leave them out of orbit_plan_load); bitmap_out keeps one row per original request (rows of
+ * paused requests are all ones and unused).  Returns the number of paused requests (0 = the whole
+ * batch fits) or a negative error; never ORBIT_E_CAPACITY, since an empty batch always fits. */
+ORBIT_API int orbit_plan_search_or_pause(int32_t n_req, int32_t n_layers, const int64_t *blocks,
+                                         const int64_t *deposited_tokens, int64_t gpu_blocks, int32_t prefetch_slots,
+                                         double blocks_per_time, const double *comp, int64_t max_evals, int32_t flags,
+                                         uint8_t *bitmap_out, uint8_t *paused_out, double *t_batch);
 
 /* Background planner (Section 4: the planner runs in its own thread and solves one decode
  * iteration ahead; the executor collects the finished plan in the next iteration and hands it to
@@ -283,7 +299,6 @@ ORBIT_API int orbit_plan_search_staggered(int32_t n_req, int32_t n_layers, const
 typedef struct orbit_planner orbit_planner;
 ORBIT_API int orbit_planner_create(orbit_planner **out);
 ORBIT_API int orbit_planner_destroy(orbit_planner *p);
-#define ORBIT_SEARCH_STAGGER 1    /* orbit_planner_submit flag: search as orbit_plan_search_staggered does */
 ORBIT_API int64_t orbit_planner_submit(orbit_planner *p, int32_t n_req, int32_t n_layers, const int64_t *blocks,
                                        int64_t gpu_blocks, int32_t prefetch_slots, double blocks_per_time,
                                        const double *comp, int64_t max_evals, int32_t flags);

@@ -192,3 +192,27 @@ def exhaustive_search(b: Sequence[int], n_layers: int, gpu_blocks: int, prefetch
         if t < best_t - 1e-12:
             best_t, best_x = t, x
     return best_t, best_x
+
+
+def pause_victim(b: Sequence[int], deposited: Sequence[int]) -> int:
+    """Section 3.4, "Pause-Resume Fallback": the victim is the request with the largest sum of KV
+    blocks and deposited tokens (our tie rule: the later request)."""
+    score = [int(x) + int(d) for x, d in zip(b, deposited)]
+    best = max(score)
+    return max(i for i, v in enumerate(score) if v == best)
+
+
+def search_or_pause(b: Sequence[int], deposited: Sequence[int], n_layers: int, gpu_blocks: int, prefetch_slots: int,
+                    bandwidth: float, comp: Sequence[float], stagger: bool = False):
+    """Pause requests, one victim at a time, until the exhaustive search finds a feasible plan for
+    the rest.  Returns (T, placement of the kept requests in original order, paused index list)."""
+    keep = list(range(len(b)))
+    paused = []
+    while True:
+        if not keep:
+            return float(sum(comp)), None, paused
+        t, x = exhaustive_search([b[i] for i in keep], n_layers, gpu_blocks, prefetch_slots, bandwidth, comp, stagger)
+        if x is not None:
+            return t, x, paused
+        v = pause_victim([b[i] for i in keep], [deposited[i] for i in keep])
+        paused.append(keep.pop(v))

@@ -67,7 +67,7 @@ EXPORTS = ["orbit_create", "orbit_destroy", "orbit_last_error", "orbit_plan_chec
            "orbit_get_plan_info", "orbit_request_pause", "orbit_request_drop", "orbit_kv_fill", "orbit_kv_read", "orbit_kv_append", "orbit_kv_append_batch", "orbit_kv_prefetch",
            "orbit_decode_attention", "orbit_step", "orbit_get_pages", "orbit_get_work_items",
            "orbit_get_copy_schedule", "orbit_distance_options", "orbit_distance_pattern", "orbit_model_latency",
-           "orbit_plan_search", "orbit_plan_search_staggered", "orbit_planner_create", "orbit_planner_destroy", "orbit_planner_submit",
+           "orbit_plan_search", "orbit_plan_search_staggered", "orbit_plan_search_or_pause", "orbit_planner_create", "orbit_planner_destroy", "orbit_planner_submit",
            "orbit_planner_poll", "orbit_deposit_create", "orbit_deposit_destroy", "orbit_deposit_push",
            "orbit_deposit_finish", "orbit_deposit_release", "orbit_deposit_stats", "orbit_profile_mismatch",
            "orbit_profile_ewma"]
@@ -114,6 +114,7 @@ def lib() -> C.CDLL:
     L.orbit_model_latency.argtypes = [i32, i32, i64p, u8p, C.c_double, f64p, f64p, f64p]
     L.orbit_plan_search.argtypes = [i32, i32, i64p, i64, i32, C.c_double, f64p, i64, u8p, f64p, i64p]
     L.orbit_plan_search_staggered.argtypes = L.orbit_plan_search.argtypes
+    L.orbit_plan_search_or_pause.argtypes = [i32, i32, i64p, i64p, i64, i32, C.c_double, f64p, i64, i32, u8p, u8p, f64p]
     L.orbit_planner_create.argtypes = [C.POINTER(vp)]
     L.orbit_planner_destroy.argtypes = [vp]
     L.orbit_planner_submit.argtypes = [vp, i32, i32, i64p, i64, i32, C.c_double, f64p, i64, i32]
@@ -218,6 +219,25 @@ def orbit_plan_search(blocks, n_layers: int, gpu_blocks: int, blocks_per_time: f
     if rc != 0:
         raise OrbitError(rc, "orbit_plan_search: no feasible placement" if rc == ORBIT_E_CAPACITY else "orbit_plan_search")
     return t.value, _unbitmap(bm, n_layers), ev.value
+
+
+def orbit_plan_search_or_pause(blocks, deposited_tokens, n_layers: int, gpu_blocks: int, blocks_per_time: float, comp,
+                               prefetch_slots: int = 1, max_evals: int = 100000, stagger: bool = False):
+    """Pause-Resume fallback: (T_batch, placement [B][L], paused [B] of 0/1).  Requests are paused,
+    largest blocks + deposited tokens first, until the rest has a feasible plan."""
+    b, dep, cp = _np(blocks, np.int64), _np(deposited_tokens, np.int64), _np(comp, np.float64)
+    assert len(b) == len(dep)
+    bm = np.zeros((len(b), (n_layers + 7) // 8), dtype=np.uint8)
+    paused = np.zeros(max(len(b), 1), dtype=np.uint8)
+    t = C.c_double()
+    rc = lib().orbit_plan_search_or_pause(len(b), n_layers, b.ctypes.data_as(C.POINTER(C.c_int64)),
+                                          dep.ctypes.data_as(C.POINTER(C.c_int64)), int(gpu_blocks), prefetch_slots,
+                                          float(blocks_per_time), cp.ctypes.data_as(C.POINTER(C.c_double)), int(max_evals),
+                                          1 if stagger else 0, bm.ctypes.data_as(C.POINTER(C.c_uint8)),
+                                          paused.ctypes.data_as(C.POINTER(C.c_uint8)), C.byref(t))
+    if rc < 0:
+        raise OrbitError(rc, "orbit_plan_search_or_pause")
+    return t.value, _unbitmap(bm, n_layers), paused[:len(b)].copy()
 
 
 class BackgroundPlanner:

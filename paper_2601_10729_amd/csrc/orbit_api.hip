@@ -486,6 +486,29 @@ int orbit_plan_search_staggered(int32_t n_req, int32_t n_layers, const int64_t *
   return ORBIT_E_NOMEM;
 }
 
+int orbit_plan_search_or_pause(int32_t n_req, int32_t n_layers, const int64_t *blocks, const int64_t *deposited_tokens,
+                               int64_t gpu_blocks, int32_t prefetch_slots, double blocks_per_time, const double *comp,
+                               int64_t max_evals, int32_t flags, uint8_t *bitmap_out, uint8_t *paused_out, double *t_batch) try {
+  if (!planner_args_ok(n_req, n_layers, blocks, blocks_per_time, comp) || prefetch_slots < 1 || gpu_blocks < 0 ||
+      max_evals < 1 || !t_batch || (flags & ~ORBIT_SEARCH_STAGGER) || (n_req > 0 && (!bitmap_out || !paused_out || !deposited_tokens)))
+    return ORBIT_E_INVAL;
+  for (int r = 0; r < n_req; ++r)
+    if (deposited_tokens[r] < 0) return ORBIT_E_INVAL;
+  FallbackResult fr = plan_search_or_pause(n_req, n_layers, blocks, deposited_tokens, gpu_blocks, prefetch_slots,
+                                           blocks_per_time, comp, max_evals, (flags & ORBIT_SEARCH_STAGGER) != 0);
+  *t_batch = fr.res.t;
+  const int bpr = (n_layers + 7) / 8;
+  for (int i = 0; i < n_req * bpr; ++i) bitmap_out[i] = 0;
+  for (int r = 0; r < n_req; ++r) {
+    paused_out[r] = fr.paused[r];
+    for (int l = 0; l < n_layers; ++l)
+      if (fr.res.x[(size_t)r * n_layers + l]) bitmap_out[r * bpr + l / 8] |= (uint8_t)(1u << (l % 8));
+  }
+  return fr.n_paused;
+} catch (const std::exception &) {
+  return ORBIT_E_NOMEM;
+}
+
 int orbit_planner_create(orbit_planner **out) try {
   if (!out) return ORBIT_E_INVAL;
   *out = new orbit_planner();

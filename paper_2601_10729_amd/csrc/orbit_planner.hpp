@@ -211,4 +211,43 @@ inline SearchResult plan_search(int n_req, int L, const int64_t *b, int64_t gpu_
   return res;
 }
 
+// Pause-Resume fallback of Section 3.4 in its capacity form: while no placement of the remaining
+// requests satisfies Eq. (1), the request with the largest sum of KV blocks and deposited tokens
+// leaves the batch (ties: the later request), and the search runs again.  paused[r] = 1 marks the
+// victims; res.x has one row per ORIGINAL request (rows of paused requests are all 1 and unused).
+struct FallbackResult {
+  SearchResult res;
+  std::vector<uint8_t> paused;
+  int n_paused = 0;
+};
+
+inline FallbackResult plan_search_or_pause(int n_req, int L, const int64_t *b, const int64_t *deposited, int64_t gpu_blocks,
+                                           int slots, double bandwidth, const double *comp, int64_t max_evals, bool stagger) {
+  FallbackResult out;
+  out.paused.assign(n_req, 0);
+  std::vector<int> keep(n_req);
+  for (int r = 0; r < n_req; ++r) keep[r] = r;
+  for (;;) {
+    std::vector<int64_t> bk(keep.size());
+    for (size_t i = 0; i < keep.size(); ++i) bk[i] = b[keep[i]];
+    SearchResult sr = plan_search((int)keep.size(), L, bk.data(), gpu_blocks, slots, bandwidth, comp, max_evals, stagger);
+    out.res.evals += sr.evals;
+    if (sr.t < std::numeric_limits<double>::infinity()) {
+      out.res.t = sr.t;
+      out.res.exhaustive = sr.exhaustive;
+      out.res.x.assign((size_t)n_req * L, 1);
+      for (size_t i = 0; i < keep.size(); ++i)
+        std::copy(sr.x.begin() + i * L, sr.x.begin() + (i + 1) * L, out.res.x.begin() + (size_t)keep[i] * L);
+      return out;
+    }
+    // infeasible even with everything offloaded: pick the victim
+    size_t v = 0;
+    for (size_t i = 1; i < keep.size(); ++i)
+      if (b[keep[i]] + deposited[keep[i]] >= b[keep[v]] + deposited[keep[v]]) v = i;
+    out.paused[keep[v]] = 1;
+    ++out.n_paused;
+    keep.erase(keep.begin() + v);
+  }
+}
+
 }  // namespace orbit

@@ -269,3 +269,56 @@ def test_staggered_patterns_need_a_smaller_prefetch_buffer():
     assert ref.feasible(b, x_stag, cap, 2)
     assert t_stag < t_plain
     assert abs(t_stag - lm.simulate_prefetch(x_stag, b, bw, comp)[0]) <= 1e-9 * t_stag
+
+
+# ------------------------------------------------------------------ Pause-Resume fallback (Section 3.4)
+
+def test_pause_victim_rule():
+    """Section 3.4: the victim is the request with the largest sum of KV blocks and deposited
+    tokens.  Hand-worked: blocks (10, 40, 25) alone pick request 1; 30 deposited tokens on request 2
+    make it 55 > 40 and move the choice; a tie goes to the later request (our rule)."""
+    assert lm.pause_victim([10, 40, 25], [0, 0, 0]) == 1
+    assert lm.pause_victim([10, 40, 25], [0, 0, 30]) == 2
+    assert lm.pause_victim([10, 40, 25], [35, 5, 20]) == 2           # 45, 45, 45: the last of the tied
+    assert lm.pause_victim([7], [0]) == 0
+
+
+def test_fallback_pauses_until_the_rest_fits():
+    L, comp, bw = 6, [1.0] * 6, 3.0
+    # everything fits: nobody is paused and the plan equals the plain search
+    t, x, paused = orbit.orbit_plan_search_or_pause([3, 6], [0, 0], L, 70, bw, comp)
+    t0, x0, _ = orbit.orbit_plan_search([3, 6], L, 70, bw, comp)
+    assert paused.tolist() == [0, 0] and t == t0 and x.tolist() == x0.tolist()
+    # 12 blocks, one prefetch buffer: with every layer offloaded Eq. (1) needs B_buf = 3 + 6 = 9 <= 12, so the
+    # pair still has a feasible (if slow) plan and nobody is paused
+    _, _, paused = orbit.orbit_plan_search_or_pause([3, 6], [0, 0], L, 12, bw, comp)
+    assert paused.tolist() == [0, 0]
+    # 8 blocks: B_buf = 9 > 8 -> request 1 (6 blocks) is paused; request 0 alone (3 <= 8) stays
+    t, x, paused = orbit.orbit_plan_search_or_pause([3, 6], [0, 0], L, 8, bw, comp)
+    assert paused.tolist() == [0, 1] and ref.feasible([3], x[:1], 8)
+    # deposited tokens move the choice: request 0 now scores 3 + 5 = 8 > 6
+    _, _, paused = orbit.orbit_plan_search_or_pause([3, 6], [5, 0], L, 8, bw, comp)
+    assert paused.tolist() == [1, 0]
+    # nothing fits at all: everyone is paused, the empty batch costs the compute time only
+    t, _, paused = orbit.orbit_plan_search_or_pause([3, 6], [0, 0], L, 2, bw, comp)
+    assert paused.tolist() == [1, 1] and t == 6.0
+    rng = np.random.default_rng(9)
+    n_paused_total = 0
+    for _ in range(25):
+        n_req, L = int(rng.integers(1, 4)), int(rng.integers(2, 7))
+        b = rng.integers(1, 30, size=n_req)
+        dep = rng.integers(0, 20, size=n_req)
+        comp = rng.uniform(0.5, 2.0, size=L)
+        bw = float(rng.uniform(1.0, 10.0))
+        slots = int(rng.integers(1, 3))
+        cap = int(b.sum() * rng.uniform(0.2, 2.0))
+        stag = bool(rng.integers(0, 2))
+        tw, xw, pw = lm.search_or_pause(b, dep, L, cap, slots, bw, comp, stagger=stag)
+        t, x, paused = orbit.orbit_plan_search_or_pause(b, dep, L, cap, bw, comp, prefetch_slots=slots, stagger=stag)
+        assert sorted(np.flatnonzero(paused).tolist()) == sorted(pw)
+        assert abs(t - tw) <= 1e-9 * tw
+        kept = [i for i in range(n_req) if not paused[i]]
+        if kept:
+            assert x[kept].tolist() == xw.tolist() and ref.feasible(b[kept], x[kept], cap, slots)
+        n_paused_total += len(pw)
+    assert n_paused_total > 5

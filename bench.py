@@ -185,10 +185,20 @@ def main():
     drain()
     t0 = time.perf_counter()
     host_enqueue = 0.0
+    # The host runs at most RUN_AHEAD steps ahead of the GPU, as a serving loop that samples a token per step
+    # would (it cannot run ahead at all): hundreds of queued copies and launches otherwise fill the runtime's
+    # queues and the enqueue calls themselves start to block at awkward points.
+    RUN_AHEAD = 2
+    done = []
     for _ in range(K):
+        if len(done) >= RUN_AHEAD:
+            done.pop(0).synchronize()
         th = time.perf_counter()
         run_step()
         host_enqueue += time.perf_counter() - th     # host time spent enqueueing the step (no GPU wait inside)
+        ev = torch.cuda.Event()
+        ev.record(g.cs)
+        done.append(ev)
     drain()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / K
 

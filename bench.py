@@ -101,6 +101,8 @@ def main():
     ap.add_argument("--zero-copy", action="store_true",
                     help="ORBIT_FLAG_ZERO_COPY: the attention kernel reads offloaded blocks in place over the link "
                          "(no staging region, no host->staging copies); a measured alternative, not the default")
+    ap.add_argument("--run-ahead", type=int, default=2,
+                    help="steps the host may be ahead of the GPU in the timed loop (0 = no bound)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-resident-variant", action="store_true")
     ap.add_argument("--no-searched-variant", action="store_true",
@@ -188,10 +190,10 @@ def main():
     # The host runs at most RUN_AHEAD steps ahead of the GPU, as a serving loop that samples a token per step
     # would (it cannot run ahead at all): hundreds of queued copies and launches otherwise fill the runtime's
     # queues and the enqueue calls themselves start to block at awkward points.
-    RUN_AHEAD = 2
+    RUN_AHEAD = args.run_ahead
     done = []
     for _ in range(K):
-        if len(done) >= RUN_AHEAD:
+        if RUN_AHEAD > 0 and len(done) >= RUN_AHEAD:
             done.pop(0).synchronize()
         th = time.perf_counter()
         run_step()

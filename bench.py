@@ -347,6 +347,8 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(dataclasses.replace(w, ctx_len=(w.ctx_len + W).astype(np.int32)))
+        # the same rate applied to the whole step's KV bytes: an extrapolation from the sample, not a measurement
+        cpu["extrapolated_seconds_per_step"] = step_bytes / (cpu["value"] * 1e9)
 
     line = {
         "metric": "effective KV GB/s per decode step (HBM + host link)",

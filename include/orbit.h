@@ -258,7 +258,9 @@ ORBIT_API int orbit_model_latency(int32_t n_req, int32_t n_layers, const int64_t
 /* Searches the pruned space (per request: keep all, the D(L) distance-driven counts, offload all)
  * for the placement of minimum modelled latency that satisfies Eq. (1) with gpu_blocks and
  * prefetch_slots.  Exhaustive if the space has at most max_evals points (ties: fewest offloads
- * for the earliest request), coordinate descent from the best uniform plan otherwise.
+ * for the earliest request); otherwise coordinate descent from the best uniform plan, which stops
+ * with the best plan found so far once max_evals placements have been simulated (the uniform
+ * plans, one per candidate count, are always tried, so *evals_out <= max(max_evals, D(L) + 2)).
  * bitmap_out: [n_req][ceil(L/8)].  Returns ORBIT_E_CAPACITY if nothing is feasible (the
  * planner's "infeasible", after which the paper pauses a request). */
 ORBIT_API int orbit_plan_search(int32_t n_req, int32_t n_layers, const int64_t *blocks, int64_t gpu_blocks,

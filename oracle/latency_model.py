@@ -1,23 +1,19 @@
 """Oracle for the planner's cost model (test infrastructure; never imported by the product).
 
-Three things, each written from the paper's text:
+Two things, each written from the paper's text:
 
-* ``distance_offload_counts`` / ``distance_pattern`` – the distance-driven placements of
+* ``distance_offload_counts`` / ``distance_pattern`` - the distance-driven placements of
   Section 3.3.2: offloading every N-th layer; the per-request candidates are the distinct
   values of floor(L/k), k = 2..L, whose number D(L) is at most 2*floor(sqrt(L)) - 1.
-* ``algorithm1_as_printed`` – Algorithm 1 (Section 3.3.1) step by step, in its own notation
-  (All, Pending, Cur, DestL, elapsed, comp_prev, beta = B/n, need = size/beta).
-* ``simulate_prefetch`` – the rules that Algorithm 1 is said to model ("Scheduling KV
-  Prefetching"): layers run strictly in order; a layer starts only when its KV is on the GPU;
-  a request has one stream and at most one layer in flight, and fetches its next offloaded
-  layer as soon as the previously fetched one has been executed; active streams share the
-  bandwidth evenly and a finished stream's share is redistributed.  Written as an
-  event-driven processor-sharing simulation.
+* ``simulate_prefetch`` - the decode latency of a placement under the prefetch rules of
+  Section 3.3.1 ("Scheduling KV Prefetching"), the rules Algorithm 1 is said to apply: exact
+  rational arithmetic, even link sharing tracked with one shared service counter and a heap of
+  landing marks.  It reproduces the stall totals the paper prints for its example (Section
+  2.3: 9 and 12 block-transfer units for the uniform placement, none for the request-wise one).
 
-The two disagree on the paper's own example (Section 2.3): with 3 blocks per layer-time both
-give 9 for placement A at step 1, but at step 16 the printed algorithm gives 11 where the text
-says 12; the simulation gives 9 and 12 when stalls are counted in block-transfer units
-(stall time x B).  The planner in the library therefore uses the simulation; see the tests.
+Pins (tests/test_planner.py): the example's totals, single-request recurrences worked by hand,
+the two-stream sharing closed form, the equivalence of a uniform placement with one request of
+the summed size, bounds and monotonicity.
 """
 from __future__ import annotations
 
@@ -52,118 +48,86 @@ def distance_pattern(n_layers: int, count: int) -> np.ndarray:
     return x
 
 
-# ----------------------------------------------------------------------------- Algorithm 1
-
-def _can_start(pending, cur, x, layer):
-    """Tasks that may be promoted at the boundary before `layer` (1-based): a request whose
-    stream is idle starts its next offloaded layer if the current layer's KV is on the GPU
-    (condition 1) or if that next layer IS the current layer (it is needed now)."""
-    busy = {r for (r, _l) in cur}
-    out = []
-    for r in range(x.shape[0]):
-        if r in busy:
-            continue
-        nxt = [l for (rr, l) in pending if rr == r and l >= layer]
-        if not nxt:
-            continue
-        l2 = min(nxt)
-        if l2 == layer or x[r, layer - 1] == 1:
-            out.append((r, l2))
-    return out
-
-
-def algorithm1_as_printed(x: np.ndarray, b: Sequence[float], bandwidth: float,
-                          comp: Sequence[float]) -> Tuple[float, List[float]]:
-    """T_batch and per-layer stalls exactly as Algorithm 1 states them."""
-    x = np.asarray(x)
-    n_req, n_layers = x.shape
-    size = {(r, l): float(b[r]) for r in range(n_req) for l in range(1, n_layers + 1) if x[r, l - 1] == 0}
-    pending = set(size)
-    cur: List[Tuple[int, int]] = []
-    stall_tot, comp_tot, comp_prev = 0.0, 0.0, 0.0
-    stalls = []
-    for layer in range(1, n_layers + 1):
-        q = _can_start(pending, cur, x, layer)
-        for e in q:
-            pending.discard(e)
-            cur.append(e)
-        dest = {e for e in cur if e[1] == layer}
-        cur.sort(key=lambda e: (size[e], e))
-        elapsed, n, stall_l = 0.0, len(cur), 0.0
-        while dest:
-            beta = bandwidth / n
-            need = size[cur[0]] / beta
-            elapsed += need
-            if elapsed > comp_prev:
-                stall_l = elapsed - comp_prev
-            dest.discard(cur[0])
-            cur.pop(0)
-            n -= 1
-        stall_tot += stall_l
-        comp_tot += comp[layer - 1]
-        comp_prev = comp[layer - 1]
-        stalls.append(stall_l)
-    return comp_tot + stall_tot, stalls
-
-
-# ----------------------------------------------------------------------------- simulation
+# ----------------------------------------------------------------------------- latency model
 
 def simulate_prefetch(x: np.ndarray, b: Sequence[float], bandwidth: float,
                       comp: Sequence[float]) -> Tuple[float, List[float]]:
-    """(T_batch, stall time per layer) under the prefetch rules of Section 3.3.1.
+    """(T_batch, stall time in front of each layer) for placement ``x`` under the prefetch rules
+    of Section 3.3.1, "Scheduling KV Prefetching", in exact rational arithmetic.
 
-    `b[r]` blocks per offloaded layer of request r, `bandwidth` blocks per unit time,
-    `comp[l]` compute time of layer l.  Stall in block units is stall time x bandwidth.
+    ``b[r]`` blocks per offloaded layer of request r, ``bandwidth`` blocks per unit time,
+    ``comp[l]`` compute time of layer l.  A stall in block units is stall time x bandwidth.
+
+    The rules, as that paragraph gives them:
+      * layers execute strictly in order, and layer l starts only when the previous layer has
+        finished and every offloaded KV of layer l has arrived; the wait in between is the stall;
+      * a request owns one prefetch buffer and one stream, so it has at most one layer in
+        flight, and the buffer stays taken until the layer it holds has executed (condition 1);
+      * transfers are launched greedily: at the boundary before a layer, every request whose
+        buffer is free starts fetching its next offloaded layer, if it has one (condition 2);
+      * the streams that are still transferring (condition 3) divide the link evenly, and when
+        one finishes its share goes to the others.
+
+    Even sharing is tracked with one shared service counter instead of per-stream remainders:
+    ``served`` is the number of blocks every stream in flight has received since time zero, so a
+    transfer of ``b`` blocks launched when the counter reads ``s`` lands when it reads ``s + b``,
+    and while ``n`` streams are in flight the counter advances by ``bandwidth / n`` per unit time.
+    Landing marks are kept in a heap.  All quantities are ``fractions.Fraction`` (a float is an
+    exact rational), so there is no tolerance anywhere; results are rounded to float on return.
     """
+    import heapq
+    from fractions import Fraction
+
     x = np.asarray(x)
     n_req, n_layers = x.shape
-    remaining = [0.0] * n_req       # blocks still to move of the request's task in flight
-    target = [0] * n_req            # layer (1-based) being fetched or held, 0 = none
-    active = [False] * n_req
+    link = Fraction(float(bandwidth))
+    size = [Fraction(float(v)) for v in b]
+    work = [Fraction(float(c)) for c in comp]
 
-    def advance(limit: float, need_layer: int) -> float:
-        """Share the bandwidth among active streams for `limit` time, or (limit < 0) until
-        every transfer for `need_layer` is complete.  Returns the time that passed."""
-        passed = 0.0
-        while True:
-            live = [r for r in range(n_req) if active[r]]
-            if limit < 0 and not any(target[r] == need_layer for r in live):
-                return passed
-            if not live or (limit >= 0 and passed >= limit):
-                return passed if limit < 0 else limit
-            rate = bandwidth / len(live)
-            dt = min(remaining[r] for r in live) / rate
-            if limit >= 0 and passed + dt > limit:
-                dt = limit - passed
-                for r in live:
-                    remaining[r] -= rate * dt
-                return limit
-            for r in live:
-                remaining[r] -= rate * dt
-            passed += dt
-            for r in live:
-                if remaining[r] <= 1e-12 * max(1.0, float(b[r])):
-                    remaining[r] = 0.0
-                    active[r] = False         # data is now held in the request's buffer
+    served = Fraction(0)
+    in_flight: list = []                    # heap of (landing mark, request)
+    holds = [0] * n_req                     # 1-based layer sitting in (or travelling to) the request's buffer
 
-    stalls, total = [], 0.0
+    def next_offloaded(r: int, first: int) -> int:
+        for l in range(first, n_layers + 1):
+            if x[r, l - 1] == 0:
+                return l
+        return 0
+
+    stalls: List[Fraction] = []
     for layer in range(1, n_layers + 1):
-        for r in range(n_req):                 # boundary before `layer`: greedy launches
-            if active[r] or target[r] >= layer:
-                continue                       # in flight, or holding a layer not yet executed
-            nxt = [l for l in range(layer, n_layers + 1) if x[r, l - 1] == 0]
-            if nxt:
-                target[r] = nxt[0]
-                remaining[r] = float(b[r])
-                active[r] = remaining[r] > 0
-        stall = advance(-1.0, layer)
-        stalls.append(stall)
-        advance(float(comp[layer - 1]), layer)
-        total += stall + comp[layer - 1]
+        # boundary before `layer`: greedy launches
         for r in range(n_req):
-            if target[r] == layer and not active[r]:
-                target[r] = 0                  # executed: the buffer may be reused
-    return total, stalls
+            if holds[r] == 0:
+                holds[r] = next_offloaded(r, layer)
+                if holds[r] and size[r] > 0:
+                    heapq.heappush(in_flight, (served + size[r], r))
+        # stall: the link keeps running until nothing destined for `layer` is in flight
+        waited = Fraction(0)
+        while any(holds[r] == layer for _, r in in_flight):
+            mark, _ = in_flight[0]
+            waited += (mark - served) * len(in_flight) / link
+            served = mark
+            heapq.heappop(in_flight)
+        stalls.append(waited)
+        # the layer executes; transfers for later layers continue underneath
+        left = work[layer - 1]
+        while in_flight and left > 0:
+            mark, _ = in_flight[0]
+            until_landing = (mark - served) * len(in_flight) / link
+            if until_landing <= left:
+                left -= until_landing
+                served = mark
+                heapq.heappop(in_flight)
+            else:
+                served += left * link / len(in_flight)
+                left = Fraction(0)
+        # executed: buffers that held this layer are free again
+        for r in range(n_req):
+            if holds[r] == layer:
+                holds[r] = 0
+    total = sum(work, Fraction(0)) + sum(stalls, Fraction(0))
+    return float(total), [float(s) for s in stalls]
 
 
 # ----------------------------------------------------------------------------- brute-force search

@@ -48,7 +48,7 @@ inline double simulate_prefetch(int n_req, int L, const uint8_t *x, const int64_
                                 const double *comp, double *stall_out) {
   std::vector<double> remaining(n_req, 0.0);
   std::vector<int> target(n_req, 0);
-  std::vector<uint8_t> active(n_req, 0);
+  std::vector<uint8_t> active(n_req, 0), was(n_req, 0);
   auto advance = [&](double limit, int need_layer) -> double {
     double passed = 0.0;
     for (;;) {
@@ -72,7 +72,7 @@ inline double simulate_prefetch(int n_req, int L, const uint8_t *x, const int64_
           if (active[r]) remaining[r] -= rate * dt;
         return limit;
       }
-      std::vector<uint8_t> was = active;
+      was = active;  // same size: no allocation
       for (int r = 0; r < n_req; ++r)
         if (was[r]) remaining[r] -= rate * dt;
       passed += dt;
@@ -177,7 +177,8 @@ inline SearchResult plan_search(int n_req, int L, const int64_t *b, int64_t gpu_
     }
     return res;
   }
-  // coordinate descent from the best uniform plan
+  // coordinate descent from the best uniform plan; it stops, keeping the best plan found, once
+  // max_evals placements have been simulated (the uniform plans are always tried)
   int best_u = -1;
   for (int i = 0; i < nc; ++i) {
     std::fill(choice.begin(), choice.end(), i);
@@ -189,12 +190,12 @@ inline SearchResult plan_search(int n_req, int L, const int64_t *b, int64_t gpu_
   }
   if (best_u < 0) return res;
   std::fill(choice.begin(), choice.end(), best_u);
-  for (int sweep = 0; sweep < 8; ++sweep) {
+  for (int sweep = 0; sweep < 8 && res.evals < max_evals; ++sweep) {
     bool improved = false;
-    for (int r = 0; r < n_req; ++r) {
+    for (int r = 0; r < n_req && res.evals < max_evals; ++r) {
       const int cur = choice[r];
       int best_i = cur;
-      for (int i = 0; i < nc; ++i) {
+      for (int i = 0; i < nc && res.evals < max_evals; ++i) {
         if (i == cur) continue;
         choice[r] = i;
         const double t = eval(choice);

@@ -62,15 +62,88 @@ def test_simulation_reproduces_the_stall_totals_of_the_papers_example():
     assert sum(stalls) == toy["placement_B"]["stalls"]["step1"] == 0
 
 
-def test_algorithm_as_printed_differs_from_the_example_at_step_16():
-    # kept as a record of why the planner uses the simulation: 9 is reproduced, 12 is not,
-    # and placement B at step 1 is not stall-free under the printed pseudo-code
-    toy = _toy()
-    L, bw, comp = toy["n_layers"], 3.0, [1.0] * toy["n_layers"]
-    A = _x(L, toy["placement_A"]["offloaded_layers_1based"])
-    assert abs(sum(lm.algorithm1_as_printed(A, [3, 6], bw, comp)[1]) - 9.0) < 1e-9
-    assert abs(sum(lm.algorithm1_as_printed(A, [4, 6], bw, comp)[1]) - 11.0) < 1e-9
-    assert sum(lm.algorithm1_as_printed(_x(L, [[], [3, 6, 9]]), [3, 6], bw, comp)[1]) > 0
+def _single_request_by_hand(offloaded_1based, size, bw, comp):
+    """One request, worked the long way: its fetches run one after the other at the full link
+    rate.  Fetch k starts at the boundary at which the layer of fetch k-1 has finished executing
+    (the first one at time zero) and takes size/bw; a layer starts at the later of "previous
+    layer finished" and "its own fetch has landed"."""
+    finish_prev, buffer_free_at, stalls = 0.0, 0.0, []
+    landed = {}
+    todo = sorted(offloaded_1based)
+    if todo:
+        landed[todo[0]] = size / bw
+    for l in range(1, len(comp) + 1):
+        start = max(finish_prev, landed.get(l, 0.0))
+        stalls.append(start - finish_prev)
+        finish_prev = start + comp[l - 1]
+        if l in landed:                                   # executed: the next fetch may start now
+            later = [k for k in todo if k > l]
+            if later:
+                landed[later[0]] = finish_prev + size / bw
+    return finish_prev, stalls
+
+
+def test_single_request_matches_the_recurrence_worked_by_hand():
+    rng = np.random.default_rng(11)
+    for _ in range(60):
+        L = int(rng.integers(1, 12))
+        off = [l for l in range(1, L + 1) if rng.random() < 0.4]
+        size, bw = int(rng.integers(1, 40)), float(rng.integers(1, 8))
+        comp = [float(c) for c in rng.integers(1, 6, size=L)]      # small integers: every quantity is exact in binary
+        t, st = lm.simulate_prefetch(_x(L, [off]), [size], bw, comp)
+        tw, sw = _single_request_by_hand(off, size, bw, comp)
+        assert abs(t - tw) < 1e-9 and np.allclose(st, sw, atol=1e-9), (off, size, bw, comp)
+
+
+def test_uniform_placement_equals_one_request_of_the_summed_size():
+    """Streams launched together that block the same layer share the link until the last one lands,
+    which is when one stream carrying all their blocks would land (the example's placement A: 3 + 6)."""
+    rng = np.random.default_rng(12)
+    for _ in range(40):
+        L, n_req = int(rng.integers(1, 10)), int(rng.integers(2, 6))
+        off = [l for l in range(1, L + 1) if rng.random() < 0.5]
+        b = rng.integers(1, 30, size=n_req)
+        comp = rng.uniform(0.2, 3.0, size=L)
+        bw = float(rng.uniform(0.5, 9.0))
+        t, st = lm.simulate_prefetch(_x(L, [off] * n_req), b, bw, comp)
+        t1, st1 = lm.simulate_prefetch(_x(L, [off]), [int(b.sum())], bw, comp)
+        assert abs(t - t1) < 1e-9 * max(1.0, t1) and np.allclose(st, st1, atol=1e-9)
+
+
+def test_two_streams_share_the_link_and_the_share_is_redistributed():
+    """Request 0 (a blocks) offloads only layer p, request 1 (c blocks) only layer q > p.  Both start
+    at time zero and halve the link; when the smaller lands the other gets all of it.  Hence the
+    smaller lands at 2*min(a, c)/B and the larger at (a + c)/B, whatever the layer times are."""
+    rng = np.random.default_rng(13)
+    for _ in range(60):
+        L = int(rng.integers(2, 9))
+        p = int(rng.integers(1, L))
+        q = int(rng.integers(p + 1, L + 1))
+        a, c = int(rng.integers(1, 40)), int(rng.integers(1, 40))
+        bw = float(rng.integers(1, 6))
+        comp = [float(v) for v in rng.integers(1, 5, size=L)]
+        land0 = (2 * min(a, c) if a <= c else a + c) / bw
+        land1 = (2 * min(a, c) if c < a else a + c) / bw
+        before_p = sum(comp[:p - 1])
+        stall_p = max(0.0, land0 - before_p)
+        before_q = sum(comp[:q - 1]) + stall_p
+        stall_q = max(0.0, land1 - before_q)
+        t, st = lm.simulate_prefetch(_x(L, [[p], [q]]), [a, c], bw, comp)
+        want = [0.0] * L
+        want[p - 1], want[q - 1] = stall_p, stall_q
+        assert np.allclose(st, want, atol=1e-9) and abs(t - (sum(comp) + stall_p + stall_q)) < 1e-9, (p, q, a, c, bw, comp)
+
+
+def test_a_busy_buffer_delays_the_next_fetch():
+    """Condition (1): while layer l of a request executes out of its prefetch buffer, that request
+    cannot fetch.  Layers 1 and 2 offloaded, 4 blocks at 2 blocks per unit, unit layer times: the first
+    fetch lands at 2 (stall 2), layer 1 runs 2..3, only then the second fetch starts and lands at 5
+    (stall 2 again), layer 2 runs 5..6, layer 3 runs 6..7."""
+    t, st = lm.simulate_prefetch(_x(3, [[1, 2]]), [4], 2.0, [1.0, 1.0, 1.0])
+    assert st == [2.0, 2.0, 0.0] and t == 7.0
+    # with a resident layer in between the second fetch hides behind it: lands at 3 + 2 = 5, layer 2 ends at 4
+    t, st = lm.simulate_prefetch(_x(3, [[1, 3]]), [4], 2.0, [1.0, 1.0, 1.0])
+    assert st == [2.0, 0.0, 1.0] and t == 6.0
 
 
 def test_simulation_closed_forms():
@@ -179,6 +252,21 @@ def test_descent_mode_is_feasible_and_not_worse_than_uniform():
                        if ref.feasible(b, np.tile(lm.distance_pattern(L, c), (n_req, 1)), cap, 2))
     assert t <= best_uniform + 1e-9
     assert abs(t - lm.simulate_prefetch(x, b, bw, comp)[0]) <= 1e-9 * t
+
+
+def test_descent_stops_at_the_evaluation_cap():
+    """max_evals bounds the descent too: it returns the best plan seen so far (never worse than the best
+    uniform plan, which is always tried) and reports how many placements it simulated."""
+    rng = np.random.default_rng(4)
+    L, n_req = 32, 24
+    b = rng.integers(512, 2048, size=n_req)
+    comp, bw = np.full(L, 0.25), 900.0
+    cap = int(b.sum() * L * 0.8)
+    t_free, _, ev_free = orbit.orbit_plan_search(b, L, cap, bw, comp, prefetch_slots=2, max_evals=100000)
+    t_cap, x_cap, ev_cap = orbit.orbit_plan_search(b, L, cap, bw, comp, prefetch_slots=2, max_evals=40)
+    assert ev_cap <= 40 < ev_free and ref.feasible(b, x_cap, cap, 2)
+    assert t_free <= t_cap + 1e-9
+    assert abs(t_cap - lm.simulate_prefetch(x_cap, b, bw, comp)[0]) <= 1e-9 * t_cap
 
 
 # ------------------------------------------------------------------ background planner (Section 4)

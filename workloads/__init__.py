@@ -10,6 +10,7 @@ from .synth import (  # noqa: F401
     gen_q,
     gen_q_steps,
     gen_kv_new,
+    gen_rising_k,
     make_workload,
     normal_bf16_table,
     pack_bitmap,

@@ -148,6 +148,21 @@ def gen_q_steps(seed: int, layer: int, req_id: int, step0: int, n_steps: int, n_
     return _draw(key, _elem_index(step0, n_steps, range(n_q_heads), n_q_heads, head_dim, device))
 
 
+def gen_rising_k(seed: int, layer: int, req_id: int, ntok: int, n_kv_heads: int, head_dim: int,
+                 total_rise: float, device="cpu"):
+    """Keys whose projection on a fixed +-1 direction grows linearly with the token index, on top
+    of quarter-amplitude seeded noise, and the unit-amplitude query along that direction.
+
+    Returns ``(k [ntok][n_kv_heads][head_dim] bf16, q_dir [head_dim] bf16)``: ``q_dir . k_t`` rises
+    by about ``total_rise`` from the first to the last token, so a running softmax maximum has to
+    move on every tile it visits.  A data recipe only: no softmax, no scaling convention."""
+    k, _ = gen_kv(seed, layer, req_id, 0, ntok, n_kv_heads, head_dim, device)
+    sign = torch.where(torch.arange(head_dim, device=device) % 3 == 0, -1.0, 1.0)
+    ramp = torch.arange(ntok, dtype=torch.float32, device=device) * (total_rise / max(ntok - 1, 1) / head_dim)
+    kf = k.float() * 0.25 + ramp.view(-1, 1, 1) * sign.view(1, 1, -1)
+    return kf.to(torch.bfloat16).contiguous(), sign.to(torch.bfloat16)
+
+
 def pack_bitmap(placement: np.ndarray) -> np.ndarray:
     """Placement matrix [B][L] of 0/1 -> row-major bitmap [B][ceil(L/8)], bit l LSB-first."""
     return np.packbits(np.asarray(placement, dtype=np.uint8), axis=1, bitorder="little")

@@ -97,8 +97,9 @@ typedef struct {
                                             mode: read over the link by the attention kernel)   */
   int64_t hbm_blocks_reserved;           /* resident blocks + staging region (left of Eq. (1))  */
   int64_t hbm_blocks_budget;             /* B_GPU                                               */
-  float   attn_ms[ORBIT_MAX_LAYERS];     /* split-K attention kernel, per layer                 */
-  float   combine_ms[ORBIT_MAX_LAYERS];  /* combine kernel, per layer                           */
+  float   attn_ms[ORBIT_MAX_LAYERS];     /* the layer's attention launch (append, split-K attention and
+                                            cross-chunk merge are one kernel)                    */
+  float   combine_ms[ORBIT_MAX_LAYERS];  /* always 0: kept so that the layout does not change   */
   float   copy_ms[ORBIT_MAX_LAYERS];     /* host -> staging copies of that layer                */
   float   stall_ms[ORBIT_MAX_LAYERS];
   int64_t link_bytes[ORBIT_MAX_LAYERS];

@@ -23,6 +23,7 @@ using namespace orbit;
 namespace {
 std::string g_create_error;
 constexpr int kDefaultChunkTokens = 1024;
+static_assert(kMaxRequests == ORBIT_MAX_REQUESTS, "per-request launch arguments are sized by ORBIT_MAX_REQUESTS");
 }  // namespace
 
 struct orbit_deposit {
@@ -42,12 +43,12 @@ struct orbit_ctx {
   hipStream_t cs = nullptr, xs = nullptr;  // compute, copy
   uint8_t *arena = nullptr;
   uint8_t *host_dev = nullptr;  // device-visible address of the pinned host arena
-  int32_t *d_table = nullptr, *d_len = nullptr, *d_items = nullptr;
+  int32_t *d_table = nullptr, *d_items = nullptr, *d_arrived = nullptr;
   float *d_pacc = nullptr, *d_pml = nullptr;
   BlitOp *d_ops = nullptr;            // device list of page copies of the last plan switch
   BlitOp *h_ops_pinned = nullptr;     // its pinned staging copy
   size_t d_ops_cap = 0;
-  int32_t *h_tab_pinned = nullptr, *h_len_pinned = nullptr;  // pinned snapshots the table uploads read
+  int32_t *h_tab_pinned = nullptr;                           // pinned snapshot the table upload reads
   hipEvent_t ev_ops = nullptr, ev_tab = nullptr;             // last use of the staging copies
   hipEvent_t ev_plan_c = nullptr, ev_plan_x = nullptr;       // stream ordering of a plan switch
   int32_t *h_items_pinned[2] = {nullptr, nullptr};
@@ -56,7 +57,7 @@ struct orbit_ctx {
   int64_t slots = 0;
   std::vector<hipEvent_t> ev_ready, ev_done;
   hipEvent_t ev_tmp = nullptr;
-  std::vector<hipEvent_t> t_wait0, t_wait1, t_attn0, t_attn1, t_comb1, t_copy0, t_copy1;
+  std::vector<hipEvent_t> t_wait0, t_wait1, t_attn0, t_attn1, t_copy0, t_copy1;
   hipEvent_t t_step0 = nullptr, t_step1 = nullptr;
   std::vector<uint8_t> host_dirty;    // per layer: host pages written since the last ordering point
   std::vector<uint8_t> copy_timed;    // per layer: t_copy0/1 recorded in this step
@@ -65,7 +66,7 @@ struct orbit_ctx {
   int64_t n_items = 0;
   bool items_valid = false;
   float scale_log2 = 0.f;
-  int variant = 0;
+  AttnParams attn_args{};               // launch arguments, kept here because of their size
   bool timing = false;
   std::string err;
 };
@@ -183,8 +184,11 @@ int ensure_work_items(orbit_ctx *c, int layer) {
   return ORBIT_OK;
 }
 
-// Waits for the layer's staging data (prefetching it first if nobody did), then attention + combine.
-int attention_impl(orbit_ctx *c, int layer, const void *q, void *out, float *out_f32, bool wait_done_already) {
+// Waits for the layer's staging data (prefetching it first if nobody did), then the attention launch.
+// k_new / v_new non-null: the lengths already count a token whose rows are still in those buffers; the
+// kernel attends to it and stores it (append fused into the launch).
+int attention_impl(orbit_ctx *c, int layer, const void *q, void *out, float *out_f32, bool wait_done_already,
+                   const uint16_t *k_new = nullptr, const uint16_t *v_new = nullptr) {
   HostState &hs = c->hs;
   const Shape &sh = hs.sh;
   const int nreq = (int)hs.reqs.size();
@@ -204,15 +208,19 @@ int attention_impl(orbit_ctx *c, int layer, const void *q, void *out, float *out
   }
   if (!c->host_only) {
     if (c->timing) HIPCHECK(c, hipEventRecord(c->t_attn0[layer], c->cs));
-    AttnParams ap{};
+    AttnParams &ap = c->attn_args;  // the per-request part is rewritten below; the rest is cheap to refill
     ap.arena = c->arena;
     ap.host = c->host_dev;
     ap.table = c->d_table;
-    ap.lens = c->d_len;
     ap.items = c->d_items;
     ap.q = (const uint16_t *)q;
     ap.pacc = c->d_pacc;
     ap.pml = c->d_pml;
+    ap.arrived = c->d_arrived;
+    ap.out = (uint16_t *)out;
+    ap.out_f32 = out_f32;
+    ap.k_new = k_new;
+    ap.v_new = v_new;
     ap.page_bytes = sh.page_bytes;
     ap.L = sh.L;
     ap.layer = layer;
@@ -221,27 +229,17 @@ int attention_impl(orbit_ctx *c, int layer, const void *q, void *out, float *out
     ap.Hkv = sh.Hkv;
     ap.G = sh.G;
     ap.chunk_tokens = sh.chunk_tokens;
+    ap.max_chunks = sh.max_chunks;
     ap.n_items = (int32_t)c->n_items;
     ap.scale_log2 = c->scale_log2;
-    ap.variant = c->variant;
+    for (int r = 0; r < nreq; ++r) {
+      const LayerKV &lk = hs.reqs[r].layers[layer];
+      ap.req[r].n_tok = lk.len;
+      // a staged block has a second home: the host run that the next step's prefetch reads
+      ap.req[r].host_page0 = (k_new && lk.tier == 0 && !sh.zero_copy) ? (int32_t)lk.host_page0 : -1;
+    }
     HIPCHECK(c, launch_attention(ap, c->cs));
     if (c->timing) HIPCHECK(c, hipEventRecord(c->t_attn1[layer], c->cs));
-    CombineParams cp{};
-    cp.pacc = c->d_pacc;
-    cp.pml = c->d_pml;
-    cp.lens = c->d_len;
-    cp.out = (uint16_t *)out;
-    cp.out_f32 = out_f32;
-    cp.L = sh.L;
-    cp.layer = layer;
-    cp.Hq = sh.Hq;
-    cp.Hkv = sh.Hkv;
-    cp.G = sh.G;
-    cp.chunk_tokens = sh.chunk_tokens;
-    cp.max_chunks = sh.max_chunks;
-    cp.n_req = nreq;
-    HIPCHECK(c, launch_combine(cp, c->cs));
-    if (c->timing) HIPCHECK(c, hipEventRecord(c->t_comb1[layer], c->cs));
     if (staged) HIPCHECK(c, hipEventRecord(c->ev_done[layer], c->cs));
   }
   return ORBIT_OK;
@@ -257,7 +255,7 @@ int check_layer(orbit_ctx *c, int layer) {
 // GPU side of a plan switch, without any host-side stream synchronisation: the copy stream first
 // waits for everything already enqueued on the compute stream, then runs the page migrations
 // (one blit per phase, in order); the compute stream waits for them and then receives the new
-// page table and lengths.  The pinned staging copies are reused only after their last transfer.
+// page table (lengths travel with every launch).  The pinned staging copies are reused only after their last transfer.
 int apply_plan_gpu(orbit_ctx *c, const std::vector<std::vector<PageOp>> &phases) {
   if (c->host_only) return ORBIT_OK;
   const HostState &hs = c->hs;
@@ -307,12 +305,10 @@ int apply_plan_gpu(orbit_ctx *c, const std::vector<std::vector<PageOp>> &phases)
   HIPCHECK(c, hipStreamWaitEvent(c->cs, c->ev_plan_x, 0));
   const size_t n_req = hs.reqs.size();
   if (n_req > 0) {
-    const size_t nt = n_req * sh.L * sh.cap_pages, nl = n_req * sh.L;
+    const size_t nt = n_req * sh.L * sh.cap_pages;
     HIPCHECK(c, hipEventSynchronize(c->ev_tab));
     std::memcpy(c->h_tab_pinned, hs.h_table.data(), nt * sizeof(int32_t));
-    std::memcpy(c->h_len_pinned, hs.h_len.data(), nl * sizeof(int32_t));
     HIPCHECK(c, hipMemcpyAsync(c->d_table, c->h_tab_pinned, nt * sizeof(int32_t), hipMemcpyHostToDevice, c->cs));
-    HIPCHECK(c, hipMemcpyAsync(c->d_len, c->h_len_pinned, nl * sizeof(int32_t), hipMemcpyHostToDevice, c->cs));
     HIPCHECK(c, hipEventRecord(c->ev_tab, c->cs));
   }
   return ORBIT_OK;
@@ -632,7 +628,6 @@ int orbit_create(const orbit_config *cfg, orbit_ctx **out) try {
   const float scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)sh.D);
   c->scale_log2 = (float)((double)scale * 1.4426950408889634);
   c->slots = (int64_t)sh.max_req * sh.max_chunks * sh.Hkv;
-  if (const char *v = std::getenv("ORBIT_ATTN_VARIANT")) c->variant = std::atoi(v);
 
   if (!host_only) {
     orbit_ctx *p = c.get();
@@ -655,18 +650,17 @@ int orbit_create(const orbit_config *cfg, orbit_ctx **out) try {
       p->host_dev = (uint8_t *)dp;
     }
     CREATE_CHECK(hipMalloc((void **)&p->d_table, c->hs.h_table.size() * sizeof(int32_t)));
-    CREATE_CHECK(hipMalloc((void **)&p->d_len, c->hs.h_len.size() * sizeof(int32_t)));
+    CREATE_CHECK(hipMalloc((void **)&p->d_arrived, (size_t)sh.max_req * sh.Hkv * sizeof(int32_t)));
     CREATE_CHECK(hipMalloc((void **)&p->d_items, (size_t)c->slots * 4 * sizeof(int32_t)));
     CREATE_CHECK(hipMalloc((void **)&p->d_pacc, (size_t)c->slots * sh.G * 128 * sizeof(float)));
     CREATE_CHECK(hipMalloc((void **)&p->d_pml, (size_t)c->slots * 32 * sizeof(float)));
     CREATE_CHECK(hipMemset(p->d_table, 0, c->hs.h_table.size() * sizeof(int32_t)));
-    CREATE_CHECK(hipMemset(p->d_len, 0, c->hs.h_len.size() * sizeof(int32_t)));
+    CREATE_CHECK(hipMemset(p->d_arrived, 0, (size_t)sh.max_req * sh.Hkv * sizeof(int32_t)));
     for (int b = 0; b < 2; ++b) {
       CREATE_CHECK(hipHostMalloc((void **)&p->h_items_pinned[b], (size_t)c->slots * 4 * sizeof(int32_t), hipHostMallocDefault));
       CREATE_CHECK(hipEventCreateWithFlags(&p->ev_items[b], hipEventDisableTiming));
     }
     CREATE_CHECK(hipHostMalloc((void **)&p->h_tab_pinned, c->hs.h_table.size() * sizeof(int32_t), hipHostMallocDefault));
-    CREATE_CHECK(hipHostMalloc((void **)&p->h_len_pinned, c->hs.h_len.size() * sizeof(int32_t), hipHostMallocDefault));
     CREATE_CHECK(hipEventCreateWithFlags(&p->ev_ops, hipEventDisableTiming));
     CREATE_CHECK(hipEventCreateWithFlags(&p->ev_tab, hipEventDisableTiming));
     CREATE_CHECK(hipEventCreateWithFlags(&p->ev_plan_c, hipEventDisableTiming));
@@ -679,7 +673,7 @@ int orbit_create(const orbit_config *cfg, orbit_ctx **out) try {
     if ((rc = make_events(p, p->ev_ready, sh.L, false)) || (rc = make_events(p, p->ev_done, sh.L, false)) ||
         (rc = make_events(p, p->t_wait0, sh.L, true)) || (rc = make_events(p, p->t_wait1, sh.L, true)) ||
         (rc = make_events(p, p->t_attn0, sh.L, true)) || (rc = make_events(p, p->t_attn1, sh.L, true)) ||
-        (rc = make_events(p, p->t_comb1, sh.L, true)) || (rc = make_events(p, p->t_copy0, sh.L, true)) ||
+        (rc = make_events(p, p->t_copy0, sh.L, true)) ||
         (rc = make_events(p, p->t_copy1, sh.L, true))) {
       g_create_error = p->err;
       orbit_destroy(c.release());
@@ -701,14 +695,13 @@ int orbit_destroy(orbit_ctx *c) {
       (void)hipStreamSynchronize(c->xs);
     }
     (void)hipFree(c->d_table);
-    (void)hipFree(c->d_len);
+    (void)hipFree(c->d_arrived);
     (void)hipFree(c->d_items);
     (void)hipFree(c->d_pacc);
     (void)hipFree(c->d_pml);
     (void)hipFree(c->d_ops);
     if (c->h_ops_pinned) (void)hipHostFree(c->h_ops_pinned);
     if (c->h_tab_pinned) (void)hipHostFree(c->h_tab_pinned);
-    if (c->h_len_pinned) (void)hipHostFree(c->h_len_pinned);
     for (hipEvent_t e : {c->ev_ops, c->ev_tab, c->ev_plan_c, c->ev_plan_x})
       if (e) (void)hipEventDestroy(e);
     for (int b = 0; b < 2; ++b) {
@@ -724,7 +717,6 @@ int orbit_destroy(orbit_ctx *c) {
     drop_events(c->t_wait1);
     drop_events(c->t_attn0);
     drop_events(c->t_attn1);
-    drop_events(c->t_comb1);
     drop_events(c->t_copy0);
     drop_events(c->t_copy1);
   }
@@ -871,7 +863,6 @@ static int append_layer(orbit_ctx *c, int l, const uint16_t *k, const uint16_t *
     }
     if (c->host_only) continue;
     ap.arena = c->arena;
-    ap.lens = c->d_len;
     ap.k = k + (int64_t)r0 * sh.Hkv * sh.D;  // non-NULL here: host-only contexts left the loop above
     ap.v = v + (int64_t)r0 * sh.Hkv * sh.D;
     ap.page_bytes = sh.page_bytes;
@@ -911,7 +902,6 @@ int orbit_kv_append(orbit_ctx *c, int64_t req_id, int32_t layer, const void *k, 
   if (c->host_only) return ORBIT_OK;
   const Shape &sh = c->hs.sh;
   ap.arena = c->arena;
-  ap.lens = c->d_len;
   ap.k = (const uint16_t *)k;
   ap.v = (const uint16_t *)v;
   ap.page_bytes = sh.page_bytes;
@@ -995,18 +985,20 @@ int orbit_step(orbit_ctx *c, const void *q, const void *k_new, const void *v_new
         if (c->timing) HIPCHECK(c, hipEventRecord(c->t_wait1[l], c->cs));
       }
     }
-    // a3: append this layer's new token of every request (the staging copy is live: it gets the token too)
-    if ((rc = append_layer(c, l, k_new ? (const uint16_t *)k_new + l * kv_stride : nullptr,
-                           v_new ? (const uint16_t *)v_new + l * kv_stride : nullptr, false)))
-      return rc;
+    // a3: this layer's new token of every request joins the cache inside the attention launch (the
+    // workgroup that owns its position takes the row from k_new / v_new, attends to it and stores it: into the
+    // resident page, or into the live staging copy and the host run); here only the lengths move
     for (int r = 0; r < nreq; ++r) {
-      const LayerKV &lk = hs.reqs[r].layers[l];
+      LayerKV &lk = hs.reqs[r].layers[l];
+      lk.len += 1;
+      hs.h_len[(size_t)r * sh.L + l] = lk.len;
       if (lk.tier == 1) hbm_bytes += (int64_t)lk.len * tok_bytes;
       else if (sh.zero_copy) c->copy_bytes[l] += ceil_div(lk.len, sh.P) * sh.page_bytes;  // read over the link by the kernel
     }
     if (b >= 0) find_live(c, l)->consumed = true;
     rc = attention_impl(c, l, q ? (const uint16_t *)q + l * q_stride : nullptr, out ? (uint16_t *)out + l * q_stride : nullptr,
-                        nullptr, true);
+                        nullptr, true, k_new ? (const uint16_t *)k_new + l * kv_stride : nullptr,
+                        v_new ? (const uint16_t *)v_new + l * kv_stride : nullptr);
     if (rc) return rc;
     if (b >= 0 && (rc = pump())) return rc;
   }
@@ -1026,7 +1018,6 @@ int orbit_step(orbit_ctx *c, const void *q, const void *k_new, const void *v_new
       HIPCHECK(c, hipEventElapsedTime(&stats->step_ms, c->t_step0, c->t_step1));
       for (int l = 0; l < sh.L; ++l) {
         HIPCHECK(c, hipEventElapsedTime(&stats->attn_ms[l], c->t_attn0[l], c->t_attn1[l]));
-        HIPCHECK(c, hipEventElapsedTime(&stats->combine_ms[l], c->t_attn1[l], c->t_comb1[l]));
         stats->attn_ms_total += stats->attn_ms[l];
         if (hs.block_of_layer[l] >= 0) {
           HIPCHECK(c, hipEventElapsedTime(&stats->stall_ms[l], c->t_wait0[l], c->t_wait1[l]));

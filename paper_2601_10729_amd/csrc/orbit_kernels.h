@@ -9,28 +9,31 @@ namespace orbit {
 
 constexpr int kAppendBatch = 64;  // requests per append launch (items travel as kernel arguments)
 
+constexpr int kMaxRequests = 256;  // = ORBIT_MAX_REQUESTS: per-request launch arguments travel by value
+
+struct AttnReq {
+  int32_t n_tok;            // tokens attended for this request in this layer (the appended one included)
+  int32_t host_page0;       // append mode: first page of the (request, layer) run in the host arena that must
+                            // receive the new token besides the page attention reads, or -1
+};
+
 struct AttnParams {
-  const uint8_t *arena;     // device, page 0 of the HBM arena
-  const uint8_t *host;      // device-visible page 0 of the pinned host arena (zero-copy reads), or NULL
+  uint8_t *arena;           // device, page 0 of the HBM arena
+  uint8_t *host;            // device-visible page 0 of the pinned host arena, or NULL
   const int32_t *table;     // device [max_req][L][cap_pages] page ids; a negative id i names host page ~i
-  const int32_t *lens;      // device [max_req][L] stored tokens
   const int32_t *items;     // device [n_items][4] {request, kv head, chunk, partial slot}
   const uint16_t *q;        // device [n_req][Hq][128] bf16
   float *pacc;              // device [slots][G][128] un-normalised partial outputs
   float *pml;               // device [slots][2][16] partial (max, sum) in log2 units
-  int64_t page_bytes;
-  int32_t L, layer, cap_pages, Hq, Hkv, G, chunk_tokens, n_items;
-  float scale_log2;         // softmax scale * log2(e)
-  int32_t variant;          // kernel build to launch (tuning knob)
-};
-
-struct CombineParams {
-  const float *pacc;
-  const float *pml;
-  const int32_t *lens;
+  int32_t *arrived;         // device [n_req][Hkv] chunks of a (request, kv head) finished so far; zero between launches
   uint16_t *out;            // device [n_req][Hq][128] bf16
-  float *out_f32;           // optional
-  int32_t L, layer, Hq, Hkv, G, chunk_tokens, max_chunks, n_req;
+  float *out_f32;           // optional device [n_req][Hq][128] fp32
+  const uint16_t *k_new;    // append mode: device [n_req][Hkv][128] bf16 rows of the token at position n_tok-1; else NULL
+  const uint16_t *v_new;
+  int64_t page_bytes;
+  int32_t L, layer, cap_pages, Hq, Hkv, G, chunk_tokens, max_chunks, n_items;
+  float scale_log2;         // softmax scale * log2(e)
+  AttnReq req[kMaxRequests];
 };
 
 struct AppendItem {
@@ -41,7 +44,6 @@ struct AppendItem {
 
 struct AppendParams {
   uint8_t *arena;
-  int32_t *lens;
   const uint16_t *k;        // device [.. n][Hkv][128] bf16, row i belongs to request r0 + i
   const uint16_t *v;
   int64_t page_bytes;
@@ -64,7 +66,6 @@ struct BlitOp {
 };
 
 hipError_t launch_attention(const AttnParams &p, hipStream_t s);
-hipError_t launch_combine(const CombineParams &p, hipStream_t s);
 hipError_t launch_append(const AppendParams &p, hipStream_t s);
 hipError_t launch_fill(const FillParams &p, hipStream_t s);
 hipError_t launch_gather(const FillParams &p, hipStream_t s);

@@ -7,14 +7,17 @@
 //                 O^T[dim][head] = V^T[dim][tok] . P^T[tok][head]    v_mfma_f32_16x16x32_bf16
 //              The query-head group (G <= 16) is the N dimension, padded with zero columns.
 //              Online softmax in base 2, fp32, reduced across lanes with wavefront shuffles; the
-//              four wavefronts of a workgroup are merged through LDS in a fixed order.
-//  combine   : merges the chunks of a (request, query head) in fixed order and normalises.
+//              four wavefronts of a workgroup are merged through LDS in a fixed order.  The
+//              workgroup that finishes the last chunk of a (request, kv head) merges all chunks in
+//              chunk order and writes the output, so a layer is one launch.  In append mode the
+//              workgroup that owns the position of the new token takes its K/V row from the
+//              caller's buffers, attends to it and writes it into the page(s).
 //  append    : scatters one new token per request into its page (HBM and/or mapped host page).
 //  fill/gather/blit : bulk token-major <-> page conversion and whole-page copies.
 //
 // Decode attention itself is only described in prose by the paper (Section 2.1); the block
 // size of 16 tokens is Section 2.3, the single arena addressed by a (request x layer) table is
-// Section 4.
+// Section 4, new KV of an offloaded layer going straight to the host is Section 3.2.
 #include "orbit_kernels.h"
 
 namespace orbit {
@@ -22,6 +25,7 @@ namespace orbit {
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
 constexpr int kD = 128;         // head dim
 constexpr int kP = 16;          // tokens per page
@@ -43,26 +47,24 @@ __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __builtin
 
 __device__ __forceinline__ float xor_max(float v, int mask) { return fmaxf(v, __shfl_xor(v, mask, 64)); }
 
-template <bool NT>
+// K/V is read exactly once per launch: nontemporal loads keep it from displacing anything in the caches.
 __device__ __forceinline__ u32x4_t load16(const uint8_t *p) {
-  if (NT) return __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
-  return *reinterpret_cast<const u32x4_t *>(p);
+  return __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
 }
 
 // Page ids are wave-uniform (scalar).  A negative id i names page ~i of the mapped host arena: the
 // zero-copy mode reads offloaded blocks over the host link instead of from a staging copy.
-__device__ __forceinline__ const uint8_t *page_ptr(const AttnParams &p, int id) {
+__device__ __forceinline__ uint8_t *page_ptr(const AttnParams &p, int id) {
   return id >= 0 ? p.arena + (int64_t)id * p.page_bytes : p.host + (int64_t)(~id) * p.page_bytes;
 }
 
-template <bool NT>
 __device__ __forceinline__ void load_page(u32x4_t (&k)[4], u32x4_t (&v)[4], const uint8_t *ktile, const uint8_t *vtile,
                                           uint32_t lane_off) {
   // wave-uniform tile addresses + a 32-bit per-lane offset: scalar-base global loads, 1 KiB per instruction
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk) k[kk] = load16<NT>(ktile + (lane_off + kk * 1024u));
+  for (int kk = 0; kk < 4; ++kk) k[kk] = load16(ktile + (lane_off + kk * 1024u));
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk) v[kk] = load16<NT>(vtile + (lane_off + kk * 1024u));
+  for (int kk = 0; kk < 4; ++kk) v[kk] = load16(vtile + (lane_off + kk * 1024u));
 }
 
 __device__ __forceinline__ void zero_page(u32x4_t (&k)[4], u32x4_t (&v)[4]) {
@@ -73,31 +75,47 @@ __device__ __forceinline__ void zero_page(u32x4_t (&k)[4], u32x4_t (&v)[4]) {
   }
 }
 
-// LDS-staged prefetch: the next tile's 16 KiB go from HBM straight into this wave's private LDS
-// buffer (global_load_lds_dwordx4: lane i of each instruction lands at byte 16 i of the KiB the
-// instruction names), costing no VGPRs while in flight.  Buffer order: K0 | V0 | K1 | V1, 4 KiB each.
-typedef const __attribute__((address_space(1))) void *gptr_t;
-typedef __attribute__((address_space(3))) void *lptr_t;
-
-template <bool NT>
-__device__ __forceinline__ void page_to_lds(uint8_t *lds_page, const uint8_t *ktile, const uint8_t *vtile,
-                                            uint32_t lane_off) {
+// Append mode: the token at slot `s` of this page is not in memory yet.  Its K/V row (one kv head,
+// 128 bf16 each) replaces whatever the slot's registers hold and is written to the page at
+// `ktile`/`vtile` and, if `mirror_k` is not null, to the host page that backs a staged block.
+// Register order (see the page layout): lane l holds of K tokens l%16, dims (4kk + l/16)*8 .. +8;
+// of V tokens 4(l/16) .. +4 in each 16-bit half-quad i%4, dims 32kk + 16(i/4) + l%16.
+__device__ __forceinline__ void place_new_token(u32x4_t (&k)[4], u32x4_t (&v)[4], int s, int lane, const uint16_t *krow,
+                                                const uint16_t *vrow, uint8_t *ktile, uint8_t *vtile, uint8_t *mirror_k,
+                                                uint8_t *mirror_v) {
+  if ((lane & 15) == s) {
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk)
-    __builtin_amdgcn_global_load_lds((gptr_t)(ktile + (lane_off + kk * 1024u)), (lptr_t)(lds_page + kk * 1024), 16, 0,
-                                     NT ? 2 : 0);
+    for (int kk = 0; kk < 4; ++kk) {
+      const u32x4_t w = *reinterpret_cast<const u32x4_t *>(krow + (4 * kk + (lane >> 4)) * 8);
+      k[kk] = w;
+      *reinterpret_cast<u32x4_t *>(ktile + kk * 1024 + lane * 16) = w;
+      if (mirror_k) *reinterpret_cast<u32x4_t *>(mirror_k + kk * 1024 + lane * 16) = w;
+    }
+  }
+  if ((lane >> 4) == (s >> 2)) {
+    const int i = s & 3;  // position inside the lane's quad of tokens
+    const uint32_t keep = (i & 1) ? 0x0000FFFFu : 0xFFFF0000u;
+    const int sh = (i & 1) * 16;
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk)
-    __builtin_amdgcn_global_load_lds((gptr_t)(vtile + (lane_off + kk * 1024u)), (lptr_t)(lds_page + 4096 + kk * 1024),
-                                     16, 0, NT ? 2 : 0);
-}
-
-__device__ __forceinline__ void page_from_lds(u32x4_t (&k)[4], u32x4_t (&v)[4], const uint8_t *lds_page,
-                                              uint32_t lane_off) {
-#pragma unroll
-  for (int kk = 0; kk < 4; ++kk) k[kk] = *reinterpret_cast<const u32x4_t *>(lds_page + kk * 1024 + lane_off);
-#pragma unroll
-  for (int kk = 0; kk < 4; ++kk) v[kk] = *reinterpret_cast<const u32x4_t *>(lds_page + 4096 + kk * 1024 + lane_off);
+    for (int kk = 0; kk < 4; ++kk) {
+      const uint16_t lo = vrow[32 * kk + (lane & 15)], hi = vrow[32 * kk + 16 + (lane & 15)];
+      if (i < 2) {
+        v[kk][0] = (v[kk][0] & keep) | ((uint32_t)lo << sh);
+        v[kk][2] = (v[kk][2] & keep) | ((uint32_t)hi << sh);
+      } else {
+        v[kk][1] = (v[kk][1] & keep) | ((uint32_t)lo << sh);
+        v[kk][3] = (v[kk][3] & keep) | ((uint32_t)hi << sh);
+      }
+      uint16_t *d = reinterpret_cast<uint16_t *>(vtile + kk * 1024 + lane * 16);
+      d[i] = lo;
+      d[4 + i] = hi;
+      if (mirror_v) {
+        uint16_t *m = reinterpret_cast<uint16_t *>(mirror_v + kk * 1024 + lane * 16);
+        m[i] = lo;
+        m[4 + i] = hi;
+      }
+    }
+  }
 }
 
 // One 32-token tile in two phases.  `valid` = tokens of the tile that exist (1..32); MASK = false
@@ -183,38 +201,37 @@ __device__ __forceinline__ void process_tile(Tile &T, const bf16x8_t (&q)[4], f3
   tile_pv<MASK>(T, pB, alpha, acc, valid, j);
 }
 
-// DEPTH = 5: one register tile reused in halves: the next tile's K is loaded into the K registers
-// as soon as the scores exist, its V into the V registers as soon as P.V is done (no second tile,
-// so two or three workgroups fit a CU and cover each other's start-up and merge phases).
-// DEPTH = 4: one register tile plus one LDS-staged tile in flight per wave (2 workgroups per CU).
-// DEPTH = register tiles per wave otherwise: 1 issues a tile's loads and waits for them (relies on other
-// resident wavefronts), 2 keeps the next tile in flight while the current one is processed, 3 keeps
-// the next two in flight (about 32 KiB per wave, 128 KiB per CU, outstanding at all times).
-template <int DEPTH, int MIN_BLOCKS, bool NT>
-__global__ __launch_bounds__(256, MIN_BLOCKS) void attention_kernel(const AttnParams p) {
-  extern __shared__ float smem[];  // [3][G][128] accumulators of waves 1..3, then [4][2][16] (m, l)
+// Two register tiles per wave: the next tile's loads are in flight while the current one is
+// processed (about 16 KiB per wave, 64 KiB per CU, outstanding at all times); 1 workgroup per CU slot.
+// APPEND: n_tok counts a token whose K/V row is still in k_new/v_new (see place_new_token).
+template <bool APPEND>
+__global__ __launch_bounds__(256, 1) void attention_kernel(const AttnParams p) {
+  extern __shared__ float smem[];  // [3][G][128] accumulators of waves 1..3, [4][2][16] (m, l), one flag
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int j = lane >> 4, nn = lane & 15;
   const uint32_t lane_off = (uint32_t)lane * 16u;
+  const int G = p.G;
 
   const int32_t *it = p.items + (int64_t)blockIdx.x * 4;
   const int r = it[0], g = it[1], c = it[2], pslot = it[3];
-  const int n = p.lens[(int64_t)r * p.L + p.layer];
+  const int n = p.req[r].n_tok;
+  const int nc = (n + p.chunk_tokens - 1) / p.chunk_tokens;
   const int tok0 = c * p.chunk_tokens;
   const int ntok = min(p.chunk_tokens, n - tok0);  // >= 1 by construction of the work list
   const int ntiles = (ntok + 2 * kP - 1) / (2 * kP);
   const int32_t *row = p.table + ((int64_t)r * p.L + p.layer) * p.cap_pages + tok0 / kP;
   const int64_t v_off = (int64_t)p.Hkv * kTileBytes;
   const int64_t head_off = (int64_t)g * kTileBytes;
+  const bool has_new = APPEND && c == nc - 1;  // this chunk ends with the token being appended
 
   bf16x8_t q[4];
   {
-    const uint16_t *qrow = p.q + ((int64_t)r * p.Hq + g * p.G + (nn < p.G ? nn : 0)) * kD;
+    const uint16_t *qrow = p.q + ((int64_t)r * p.Hq + g * G + (nn < G ? nn : 0)) * kD;
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
       u32x4_t w = *reinterpret_cast<const u32x4_t *>(qrow + (4 * kk + j) * 8);
-      if (nn >= p.G) w = u32x4_t{0, 0, 0, 0};
+      if (nn >= G) w = u32x4_t{0, 0, 0, 0};
       q[kk] = __builtin_bit_cast(bf16x8_t, w);
     }
   }
@@ -228,106 +245,34 @@ __global__ __launch_bounds__(256, MIN_BLOCKS) void attention_kernel(const AttnPa
     const int valid = ntok - 2 * kP * t;
     const int p0 = __builtin_amdgcn_readfirstlane(row[2 * t]);
     const uint8_t *t0 = page_ptr(p, p0) + head_off;
-    load_page<NT>(T.k0, T.v0, t0, t0 + v_off, lane_off);
+    load_page(T.k0, T.v0, t0, t0 + v_off, lane_off);
     if (valid > kP) {
       const int p1 = __builtin_amdgcn_readfirstlane(row[2 * t + 1]);
       const uint8_t *t1 = page_ptr(p, p1) + head_off;
-      load_page<NT>(T.k1, T.v1, t1, t1 + v_off, lane_off);
+      load_page(T.k1, T.v1, t1, t1 + v_off, lane_off);
     } else {
       zero_page(T.k1, T.v1);
     }
   };
   auto run_tile = [&](Tile &T, int t) {
     const int valid = ntok - 2 * kP * t;
+    if (has_new && t == ntiles - 1) {
+      const int tt = valid - 1;  // position of the new token in this tile, 0..31
+      const int pi = 2 * t + (tt >> 4);
+      const int pid = __builtin_amdgcn_readfirstlane(row[pi]);
+      uint8_t *kt = page_ptr(p, pid) + head_off;
+      const int hp = p.req[r].host_page0;
+      uint8_t *mk = hp >= 0 ? p.host + ((int64_t)hp + tok0 / kP + pi) * p.page_bytes + head_off : nullptr;
+      const uint16_t *krow = p.k_new + ((int64_t)r * p.Hkv + g) * kD;
+      const uint16_t *vrow = p.v_new + ((int64_t)r * p.Hkv + g) * kD;
+      if (tt < kP) place_new_token(T.k0, T.v0, tt, lane, krow, vrow, kt, kt + v_off, mk, mk ? mk + v_off : nullptr);
+      else place_new_token(T.k1, T.v1, tt - kP, lane, krow, vrow, kt, kt + v_off, mk, mk ? mk + v_off : nullptr);
+    }
     if (valid >= 2 * kP) process_tile<false>(T, q, acc, m, l, p.scale_log2, 2 * kP, j);
     else process_tile<true>(T, q, acc, m, l, p.scale_log2, valid, j);
   };
 
-  if (DEPTH == 5) {
-    Tile T;
-    auto load_half = [&](int t, bool want_v) {
-      const int valid = ntok - 2 * kP * t;
-      const int p0 = __builtin_amdgcn_readfirstlane(row[2 * t]);
-      const uint8_t *t0 = page_ptr(p, p0) + head_off + (want_v ? v_off : 0);
-      u32x4_t(&d0)[4] = want_v ? T.v0 : T.k0;
-      u32x4_t(&d1)[4] = want_v ? T.v1 : T.k1;
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) d0[kk] = load16<NT>(t0 + (lane_off + kk * 1024u));
-      if (valid > kP) {
-        const int p1 = __builtin_amdgcn_readfirstlane(row[2 * t + 1]);
-        const uint8_t *t1 = page_ptr(p, p1) + head_off + (want_v ? v_off : 0);
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) d1[kk] = load16<NT>(t1 + (lane_off + kk * 1024u));
-      } else {
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) d1[kk] = u32x4_t{0, 0, 0, 0};
-      }
-    };
-    int t = wave;
-    if (t < ntiles) {
-      load_half(t, false);
-      load_half(t, true);
-    }
-    while (t < ntiles) {
-      const int valid = ntok - 2 * kP * t, tn = t + kWaves;
-      const bool more = tn < ntiles;
-      float alpha;
-      bf16x8_t pB;
-      if (valid >= 2 * kP) pB = tile_scores<false>(T, q, m, l, p.scale_log2, 2 * kP, j, alpha);
-      else pB = tile_scores<true>(T, q, m, l, p.scale_log2, valid, j, alpha);
-      if (more) load_half(tn, false);  // the K registers are free once the scores exist
-      if (valid >= 2 * kP) tile_pv<false>(T, pB, alpha, acc, 2 * kP, j);
-      else tile_pv<true>(T, pB, alpha, acc, valid, j);
-      if (more) load_half(tn, true);   // and the V registers once P.V has been issued
-      t = tn;
-    }
-  } else if (DEPTH == 4) {
-    // merge area first, then one 16 KiB staging buffer per wave
-    uint8_t *stage = reinterpret_cast<uint8_t *>(smem) + (((3 * p.G * kD + kWaves * 32) * 4 + 1023) & ~1023) + wave * 16384;
-    auto issue = [&](int t) {
-      const int valid = ntok - 2 * kP * t;
-      const int p0 = __builtin_amdgcn_readfirstlane(row[2 * t]);
-      const uint8_t *t0 = page_ptr(p, p0) + head_off;
-      page_to_lds<NT>(stage, t0, t0 + v_off, lane_off);
-      if (valid > kP) {
-        const int p1 = __builtin_amdgcn_readfirstlane(row[2 * t + 1]);
-        const uint8_t *t1 = page_ptr(p, p1) + head_off;
-        page_to_lds<NT>(stage + 8192, t1, t1 + v_off, lane_off);
-      }
-    };
-    Tile A;
-    int t = wave;
-    if (t < ntiles) issue(t);
-    while (t < ntiles) {
-      __builtin_amdgcn_s_waitcnt(0);  // the staged tile has landed in LDS
-      page_from_lds(A.k0, A.v0, stage, lane_off);
-      if (ntok - 2 * kP * t > kP) page_from_lds(A.k1, A.v1, stage + 8192, lane_off);
-      else zero_page(A.k1, A.v1);
-      __builtin_amdgcn_s_waitcnt(0);  // registers filled: the buffer may be overwritten
-      const int tn = t + kWaves;
-      if (tn < ntiles) issue(tn);
-      run_tile(A, t);
-      t = tn;
-    }
-  } else if (DEPTH == 3) {
-    Tile A, B, C;
-    int t = wave;
-    if (t < ntiles) load_tile(A, t);
-    if (t + kWaves < ntiles) load_tile(B, t + kWaves);
-    while (t < ntiles) {
-      if (t + 2 * kWaves < ntiles) load_tile(C, t + 2 * kWaves);
-      run_tile(A, t);
-      t += kWaves;
-      if (t >= ntiles) break;
-      if (t + 2 * kWaves < ntiles) load_tile(A, t + 2 * kWaves);
-      run_tile(B, t);
-      t += kWaves;
-      if (t >= ntiles) break;
-      if (t + 2 * kWaves < ntiles) load_tile(B, t + 2 * kWaves);
-      run_tile(C, t);
-      t += kWaves;
-    }
-  } else if (DEPTH == 2) {
+  {
     Tile A, B;
     int t = wave;
     if (t < ntiles) load_tile(A, t);
@@ -342,21 +287,15 @@ __global__ __launch_bounds__(256, MIN_BLOCKS) void attention_kernel(const AttnPa
       run_tile(B, t);
       t = tn;
     }
-  } else {
-    Tile A;
-    for (int t = wave; t < ntiles; t += kWaves) {
-      load_tile(A, t);
-      run_tile(A, t);
-    }
   }
 
   // l holds this lane's share of the normaliser; fold the four token groups of each head
   l += __shfl_xor(l, 16, 64);
   l += __shfl_xor(l, 32, 64);
 
-  const int G = p.G;
   float *sm_acc = smem;                      // [3][G][128]
   float *sm_ml = smem + 3 * G * kD;          // [4][2][16]
+  int *sm_last = reinterpret_cast<int *>(sm_ml + kWaves * 32);
   if (j == 0) {
     sm_ml[wave * 32 + nn] = m;
     sm_ml[wave * 32 + 16 + nn] = l;
@@ -367,81 +306,90 @@ __global__ __launch_bounds__(256, MIN_BLOCKS) void attention_kernel(const AttnPa
     for (int nb = 0; nb < 8; ++nb) *reinterpret_cast<f32x4_t *>(dst + 16 * nb) = acc[nb];
   }
   __syncthreads();
-  if (wave == 0 && nn < G) {
-    float mw[kWaves], lw[kWaves];
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-      mw[w] = sm_ml[w * 32 + nn];
-      lw[w] = sm_ml[w * 32 + 16 + nn];
-    }
-    const float M = fmaxf(fmaxf(mw[0], mw[1]), fmaxf(mw[2], mw[3]));  // wave 0 always has a tile
-    float f[kWaves];
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) f[w] = fast_exp2(mw[w] - M);
-    float lt = lw[0] * f[0];
-#pragma unroll
-    for (int w = 1; w < kWaves; ++w) lt += lw[w] * f[w];
-    float *out = p.pacc + ((int64_t)pslot * G + nn) * kD + 4 * j;
-#pragma unroll
-    for (int nb = 0; nb < 8; ++nb) {
-      f32x4_t o = acc[nb] * f[0];
-#pragma unroll
-      for (int w = 1; w < kWaves; ++w)
-        o += *reinterpret_cast<const f32x4_t *>(sm_acc + ((w - 1) * G + nn) * kD + 4 * j + 16 * nb) * f[w];
-      *reinterpret_cast<f32x4_t *>(out + 16 * nb) = o;
-    }
-    if (j == 0) {
-      p.pml[(int64_t)pslot * 32 + nn] = M;
-      p.pml[(int64_t)pslot * 32 + 16 + nn] = lt;
-    }
-  }
-}
-
-// One workgroup of 4 waves per (request, query head); lane handles dims 2*lane, 2*lane+1; wave w
-// takes chunks w, w+4, ...; the four partial sums are added in wave order.
-__global__ __launch_bounds__(256) void combine_kernel(const CombineParams p) {
-  __shared__ float sm[kWaves][kD + 1];
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int r = blockIdx.x / p.Hq, h = blockIdx.x % p.Hq;
-  const int g = h / p.G, nn = h % p.G;
-  const int n = p.lens[(int64_t)r * p.L + p.layer];
-  const int nc = (n + p.chunk_tokens - 1) / p.chunk_tokens;
-  auto slot = [&](int c) { return (int64_t)(r * p.max_chunks + c) * p.Hkv + g; };
-
-  float M = -INFINITY;
-  for (int c = lane; c < nc; c += 64) M = fmaxf(M, p.pml[slot(c) * 32 + nn]);
-#pragma unroll
-  for (int s = 1; s < 64; s <<= 1) M = xor_max(M, s);
-
-  float o0 = 0.f, o1 = 0.f, lsum = 0.f;
-  for (int c = wave; c < nc; c += kWaves) {
-    const int64_t s = slot(c);
-    const float f = fast_exp2(p.pml[s * 32 + nn] - M);
-    lsum += p.pml[s * 32 + 16 + nn] * f;
-    const float2 a = *reinterpret_cast<const float2 *>(p.pacc + (s * p.G + nn) * kD + 2 * lane);
-    o0 += a.x * f;
-    o1 += a.y * f;
-  }
-  sm[wave][2 * lane] = o0;
-  sm[wave][2 * lane + 1] = o1;
-  if (lane == 0) sm[wave][kD] = lsum;
-  __syncthreads();
   if (wave == 0) {
-    float t0 = sm[0][2 * lane], t1 = sm[0][2 * lane + 1], lt = sm[0][kD];
+    if (nn < G) {
+      float mw[kWaves], lw[kWaves];
 #pragma unroll
-    for (int w = 1; w < kWaves; ++w) {
-      t0 += sm[w][2 * lane];
-      t1 += sm[w][2 * lane + 1];
-      lt += sm[w][kD];
+      for (int w = 0; w < kWaves; ++w) {
+        mw[w] = sm_ml[w * 32 + nn];
+        lw[w] = sm_ml[w * 32 + 16 + nn];
+      }
+      const float M = fmaxf(fmaxf(mw[0], mw[1]), fmaxf(mw[2], mw[3]));  // wave 0 always has a tile
+      float f[kWaves];
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) f[w] = fast_exp2(mw[w] - M);
+      float lt = lw[0] * f[0];
+#pragma unroll
+      for (int w = 1; w < kWaves; ++w) lt += lw[w] * f[w];
+      if (nc == 1) {  // the only chunk of this (request, kv head): normalise and write the output
+        const float inv = 1.0f / lt;
+        const int64_t o = ((int64_t)r * p.Hq + g * G + nn) * kD + 4 * j;
+#pragma unroll
+        for (int nb = 0; nb < 8; ++nb) {
+          f32x4_t v = acc[nb] * f[0];
+#pragma unroll
+          for (int w = 1; w < kWaves; ++w)
+            v += *reinterpret_cast<const f32x4_t *>(sm_acc + ((w - 1) * G + nn) * kD + 4 * j + 16 * nb) * f[w];
+          v *= inv;
+          *reinterpret_cast<u32x2_t *>(p.out + o + 16 * nb) =
+              u32x2_t{bf16_rne_bits(v[0]) | (bf16_rne_bits(v[1]) << 16), bf16_rne_bits(v[2]) | (bf16_rne_bits(v[3]) << 16)};
+          if (p.out_f32) *reinterpret_cast<f32x4_t *>(p.out_f32 + o + 16 * nb) = v;
+        }
+      } else {
+        float *out = p.pacc + ((int64_t)pslot * G + nn) * kD + 4 * j;
+#pragma unroll
+        for (int nb = 0; nb < 8; ++nb) {
+          f32x4_t o = acc[nb] * f[0];
+#pragma unroll
+          for (int w = 1; w < kWaves; ++w)
+            o += *reinterpret_cast<const f32x4_t *>(sm_acc + ((w - 1) * G + nn) * kD + 4 * j + 16 * nb) * f[w];
+          *reinterpret_cast<f32x4_t *>(out + 16 * nb) = o;
+        }
+        if (j == 0) {
+          p.pml[(int64_t)pslot * 32 + nn] = M;
+          p.pml[(int64_t)pslot * 32 + 16 + nn] = lt;
+        }
+      }
     }
-    const float inv = 1.0f / lt;
-    t0 *= inv;
-    t1 *= inv;
-    const int64_t o = ((int64_t)r * p.Hq + h) * kD + 2 * lane;
-    *reinterpret_cast<uint32_t *>(p.out + o) = bf16_rne_bits(t0) | (bf16_rne_bits(t1) << 16);
-    if (p.out_f32) *reinterpret_cast<float2 *>(p.out_f32 + o) = float2{t0, t1};
+    if (nc > 1) {
+      // publish the partial (device scope), then count this chunk in; whoever counts last merges
+      __threadfence();
+      int before = 0;
+      if (lane == 0) before = atomicAdd(p.arrived + (int64_t)r * p.Hkv + g, 1);
+      before = __builtin_amdgcn_readfirstlane(before);
+      if (lane == 0) *sm_last = before == nc - 1;
+    }
   }
+  if (nc == 1) return;
+  __syncthreads();
+  if (!*sm_last) return;
+  __threadfence();  // the other chunks' partials were published before their count; read them fresh
+
+  // Cross-chunk merge in chunk order (fixed, so the result does not depend on which workgroup does
+  // it): wave w takes query heads w, w+4, ... of the group, lane the dims 2*lane, 2*lane+1.
+  auto slot = [&](int cc) { return ((int64_t)r * p.max_chunks + cc) * p.Hkv + g; };
+  for (int hh = wave; hh < G; hh += kWaves) {
+    float M = -INFINITY;
+    for (int cc = lane; cc < nc; cc += 64) M = fmaxf(M, p.pml[slot(cc) * 32 + hh]);
+#pragma unroll
+    for (int s = 1; s < 64; s <<= 1) M = xor_max(M, s);
+    float o0 = 0.f, o1 = 0.f, lsum = 0.f;
+    for (int cc = 0; cc < nc; ++cc) {
+      const int64_t s = slot(cc);
+      const float f = fast_exp2(p.pml[s * 32 + hh] - M);
+      lsum += p.pml[s * 32 + 16 + hh] * f;
+      const float2 a = *reinterpret_cast<const float2 *>(p.pacc + (s * G + hh) * kD + 2 * lane);
+      o0 += a.x * f;
+      o1 += a.y * f;
+    }
+    const float inv = 1.0f / lsum;
+    o0 *= inv;
+    o1 *= inv;
+    const int64_t o = ((int64_t)r * p.Hq + g * G + hh) * kD + 2 * lane;
+    *reinterpret_cast<uint32_t *>(p.out + o) = bf16_rne_bits(o0) | (bf16_rne_bits(o1) << 16);
+    if (p.out_f32) *reinterpret_cast<float2 *>(p.out_f32 + o) = float2{o0, o1};
+  }
+  if (threadIdx.x == 0) p.arrived[(int64_t)r * p.Hkv + g] = 0;  // ready for the next launch
 }
 
 __device__ __forceinline__ int v_elem_offset(int tok, int dim) {
@@ -450,7 +398,6 @@ __device__ __forceinline__ int v_elem_offset(int tok, int dim) {
 
 __global__ __launch_bounds__(256) void append_kernel(const AppendParams p) {
   const AppendItem item = p.items[blockIdx.x];
-  const int r = p.r0 + blockIdx.x;
   const int slot = item.tok % kP;
   const uint16_t *ksrc = p.k + (int64_t)blockIdx.x * p.Hkv * kD;
   const uint16_t *vsrc = p.v + (int64_t)blockIdx.x * p.Hkv * kD;
@@ -470,7 +417,6 @@ __global__ __launch_bounds__(256) void append_kernel(const AppendParams p) {
       vt[g * (kTileBytes / 2) + v_elem_offset(slot, dim)] = vsrc[i];
     }
   }
-  if (threadIdx.x == 0) p.lens[(int64_t)r * p.L + p.layer] = item.tok + 1;
 }
 
 __device__ __forceinline__ uint8_t *fill_page_base(const FillParams &p, int64_t page_index) {
@@ -564,34 +510,10 @@ __global__ __launch_bounds__(256) void blit_kernel(const BlitOp *ops, int64_t un
 
 hipError_t launch_attention(const AttnParams &p, hipStream_t s) {
   if (p.n_items <= 0) return hipSuccess;
-  const size_t merge = (size_t)(3 * p.G * kD + kWaves * 32) * sizeof(float);
+  const size_t lds = (size_t)(3 * p.G * kD + kWaves * 32 + 4) * sizeof(float);
   const dim3 grid((unsigned)p.n_items), block(256);
-  switch (p.variant) {  // 0 is the measured best on MI355X; the others are kept for tuning runs
-    case 1: hipLaunchKernelGGL((attention_kernel<2, 1, false>), grid, block, merge, s, p); break;
-    case 2: hipLaunchKernelGGL((attention_kernel<1, 2, false>), grid, block, merge, s, p); break;
-    case 3: hipLaunchKernelGGL((attention_kernel<3, 1, true>), grid, block, merge, s, p); break;
-    case 4: hipLaunchKernelGGL((attention_kernel<1, 2, true>), grid, block, merge, s, p); break;
-    case 5: {
-      const size_t lds = ((merge + 1023) & ~(size_t)1023) + kWaves * 16384;
-      static bool raised = false;  // dynamic LDS above 64 KiB has to be allowed once per function
-      if (!raised) {
-        hipError_t e = hipFuncSetAttribute((const void *)attention_kernel<4, 2, true>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        raised = true;
-      }
-      hipLaunchKernelGGL((attention_kernel<4, 2, true>), grid, block, lds, s, p);
-      break;
-    }
-    case 6: hipLaunchKernelGGL((attention_kernel<5, 2, true>), grid, block, merge, s, p); break;
-    default: hipLaunchKernelGGL((attention_kernel<2, 1, true>), grid, block, merge, s, p); break;
-  }
-  return hipGetLastError();
-}
-
-hipError_t launch_combine(const CombineParams &p, hipStream_t s) {
-  if (p.n_req <= 0) return hipSuccess;
-  hipLaunchKernelGGL(combine_kernel, dim3((unsigned)(p.n_req * p.Hq)), dim3(256), 0, s, p);
+  if (p.k_new) hipLaunchKernelGGL(attention_kernel<true>, grid, block, lds, s, p);
+  else hipLaunchKernelGGL(attention_kernel<false>, grid, block, lds, s, p);
   return hipGetLastError();
 }
 

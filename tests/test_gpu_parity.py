@@ -334,22 +334,6 @@ def test_plan_switches_between_steps_without_host_sync():
         _check(a[S - 1, layer], None, o.attention(layer, S - 1))
 
 
-@pytest.mark.parametrize("variant", [1, 2, 3, 4, 5, 6])
-def test_alternative_kernel_builds_match_oracle(variant, monkeypatch):
-    """The tuning builds of the attention kernel (plain loads, one / three register tiles,
-    LDS-staged prefetch, half-tile register rotation) stay parity-green on lengths with ragged tiles and several chunks."""
-    h = _harness()
-    monkeypatch.setenv("ORBIT_ATTN_VARIANT", str(variant))
-    w = _custom([1, 33, 700, 1025, 3100, 5000], L=2, Hq=32, Hkv=8,
-                placement=[[1, 0], [0, 1], [1, 0], [0, 1], [1, 1], [0, 0]])
-    g = h.GpuRun(w)
-    o = h.OracleRun(w)
-    for layer in range(2):
-        out, out32 = g.attention(layer)
-        _check(out, out32, o.attention(layer))
-    g.close()
-
-
 @pytest.mark.parametrize("seed", range(10))
 def test_random_shapes_lengths_and_placements(seed):
     """Seeded random head shapes, chunk sizes, staging-range counts, lengths and placements; odd

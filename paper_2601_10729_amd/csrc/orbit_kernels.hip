@@ -52,6 +52,24 @@ __device__ __forceinline__ u32x4_t load16(const uint8_t *p) {
   return __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
 }
 
+// Split-K partials cross workgroups (and XCDs, each with an L2 of its own) inside one launch.  They are
+// written and read with relaxed device-scope atomic accesses, which go through to the level all XCDs
+// share, so that neither side needs a cache-wide write-back or invalidate.
+__device__ __forceinline__ void publish_f32x2(float *p, float a, float b) {
+  const uint64_t w = (uint64_t)__builtin_bit_cast(uint32_t, a) | ((uint64_t)__builtin_bit_cast(uint32_t, b) << 32);
+  __hip_atomic_store(reinterpret_cast<uint64_t *>(p), w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void publish_f32(float *p, float a) {
+  __hip_atomic_store(p, a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float2 fetch_f32x2(const float *p) {
+  const uint64_t w = __hip_atomic_load(reinterpret_cast<const uint64_t *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return float2{__builtin_bit_cast(float, (uint32_t)w), __builtin_bit_cast(float, (uint32_t)(w >> 32))};
+}
+__device__ __forceinline__ float fetch_f32(const float *p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // Page ids are wave-uniform (scalar).  A negative id i names page ~i of the mapped host arena: the
 // zero-copy mode reads offloaded blocks over the host link instead of from a staging copy.
 __device__ __forceinline__ uint8_t *page_ptr(const AttnParams &p, int id) {
@@ -75,45 +93,53 @@ __device__ __forceinline__ void zero_page(u32x4_t (&k)[4], u32x4_t (&v)[4]) {
   }
 }
 
-// Append mode: the token at slot `s` of this page is not in memory yet.  Its K/V row (one kv head,
-// 128 bf16 each) replaces whatever the slot's registers hold and is written to the page at
-// `ktile`/`vtile` and, if `mirror_k` is not null, to the host page that backs a staged block.
-// Register order (see the page layout): lane l holds of K tokens l%16, dims (4kk + l/16)*8 .. +8;
-// of V tokens 4(l/16) .. +4 in each 16-bit half-quad i%4, dims 32kk + 16(i/4) + l%16.
-__device__ __forceinline__ void place_new_token(u32x4_t (&k)[4], u32x4_t (&v)[4], int s, int lane, const uint16_t *krow,
-                                                const uint16_t *vrow, uint8_t *ktile, uint8_t *vtile, uint8_t *mirror_k,
-                                                uint8_t *mirror_v) {
-  if ((lane & 15) == s) {
+// The last token of a request (position n-1) is attended to as a tile of its own, with the token in
+// slot 0 and every other slot masked, in both modes, so that a step which appends inside the launch
+// and an append followed by a separate attention launch do the same arithmetic.
+// APPEND: the row comes from the caller's k_new / v_new and is also stored into slot `s` of the page
+// at `ktile` / `vtile` and, if `mirror_k` is not null, of the host page that backs a staged block.
+// Otherwise it is gathered from slot `s` of the page.
+// Register order (see the page layout): lane l holds of K token l%16, dims (4kk + l/16)*8 .. +8;
+// of V tokens 4(l/16) + i%4 in 16-bit element i, dims 32kk + 16(i/4) + l%16.
+template <bool APPEND>
+__device__ __forceinline__ void last_token_tile(Tile &T, int s, int lane, const uint16_t *krow, const uint16_t *vrow,
+                                                uint8_t *ktile, uint8_t *vtile, uint8_t *mirror_k, uint8_t *mirror_v) {
+  zero_page(T.k0, T.v0);
+  zero_page(T.k1, T.v1);
+  if ((lane & 15) == 0) {  // K of slot 0: lanes 0, 16, 32, 48
+    const int src = (16 * (lane >> 4) + s) * 16;  // where slot s of the same dims sits in each KiB of the page
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
-      const u32x4_t w = *reinterpret_cast<const u32x4_t *>(krow + (4 * kk + (lane >> 4)) * 8);
-      k[kk] = w;
-      *reinterpret_cast<u32x4_t *>(ktile + kk * 1024 + lane * 16) = w;
-      if (mirror_k) *reinterpret_cast<u32x4_t *>(mirror_k + kk * 1024 + lane * 16) = w;
+      if (APPEND) {
+        const u32x4_t w = *reinterpret_cast<const u32x4_t *>(krow + (4 * kk + (lane >> 4)) * 8);
+        T.k0[kk] = w;
+        *reinterpret_cast<u32x4_t *>(ktile + kk * 1024 + src) = w;
+        if (mirror_k) *reinterpret_cast<u32x4_t *>(mirror_k + kk * 1024 + src) = w;
+      } else {
+        T.k0[kk] = *reinterpret_cast<const u32x4_t *>(ktile + kk * 1024 + src);
+      }
     }
   }
-  if ((lane >> 4) == (s >> 2)) {
-    const int i = s & 3;  // position inside the lane's quad of tokens
-    const uint32_t keep = (i & 1) ? 0x0000FFFFu : 0xFFFF0000u;
-    const int sh = (i & 1) * 16;
+  if (lane < 16) {  // V of slot 0: element 0 (dims 32kk + lane) and element 4 (dims 32kk + 16 + lane)
+    const int src = (16 * (s >> 2) + lane) * 16 + 2 * (s & 3);
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
-      const uint16_t lo = vrow[32 * kk + (lane & 15)], hi = vrow[32 * kk + 16 + (lane & 15)];
-      if (i < 2) {
-        v[kk][0] = (v[kk][0] & keep) | ((uint32_t)lo << sh);
-        v[kk][2] = (v[kk][2] & keep) | ((uint32_t)hi << sh);
+      uint16_t lo, hi;
+      if (APPEND) {
+        lo = vrow[32 * kk + lane];
+        hi = vrow[32 * kk + 16 + lane];
+        *reinterpret_cast<uint16_t *>(vtile + kk * 1024 + src) = lo;
+        *reinterpret_cast<uint16_t *>(vtile + kk * 1024 + src + 8) = hi;
+        if (mirror_v) {
+          *reinterpret_cast<uint16_t *>(mirror_v + kk * 1024 + src) = lo;
+          *reinterpret_cast<uint16_t *>(mirror_v + kk * 1024 + src + 8) = hi;
+        }
       } else {
-        v[kk][1] = (v[kk][1] & keep) | ((uint32_t)lo << sh);
-        v[kk][3] = (v[kk][3] & keep) | ((uint32_t)hi << sh);
+        lo = *reinterpret_cast<const uint16_t *>(vtile + kk * 1024 + src);
+        hi = *reinterpret_cast<const uint16_t *>(vtile + kk * 1024 + src + 8);
       }
-      uint16_t *d = reinterpret_cast<uint16_t *>(vtile + kk * 1024 + lane * 16);
-      d[i] = lo;
-      d[4 + i] = hi;
-      if (mirror_v) {
-        uint16_t *m = reinterpret_cast<uint16_t *>(mirror_v + kk * 1024 + lane * 16);
-        m[i] = lo;
-        m[4 + i] = hi;
-      }
+      T.v0[kk][0] = lo;
+      T.v0[kk][2] = hi;
     }
   }
 }
@@ -203,7 +229,7 @@ __device__ __forceinline__ void process_tile(Tile &T, const bf16x8_t (&q)[4], f3
 
 // Two register tiles per wave: the next tile's loads are in flight while the current one is
 // processed (about 16 KiB per wave, 64 KiB per CU, outstanding at all times); 1 workgroup per CU slot.
-// APPEND: n_tok counts a token whose K/V row is still in k_new/v_new (see place_new_token).
+// APPEND: n_tok counts a token whose K/V row is still in k_new/v_new (see last_token_tile).
 template <bool APPEND>
 __global__ __launch_bounds__(256, 1) void attention_kernel(const AttnParams p) {
   extern __shared__ float smem[];  // [3][G][128] accumulators of waves 1..3, [4][2][16] (m, l), one flag
@@ -218,12 +244,13 @@ __global__ __launch_bounds__(256, 1) void attention_kernel(const AttnParams p) {
   const int n = p.req[r].n_tok;
   const int nc = (n + p.chunk_tokens - 1) / p.chunk_tokens;
   const int tok0 = c * p.chunk_tokens;
-  const int ntok = min(p.chunk_tokens, n - tok0);  // >= 1 by construction of the work list
+  // the request's last token is handled after the paged tiles (see last_token_tile)
+  const bool has_last = c == nc - 1;
+  const int ntok = min(p.chunk_tokens, n - tok0) - (has_last ? 1 : 0);  // >= 0
   const int ntiles = (ntok + 2 * kP - 1) / (2 * kP);
   const int32_t *row = p.table + ((int64_t)r * p.L + p.layer) * p.cap_pages + tok0 / kP;
   const int64_t v_off = (int64_t)p.Hkv * kTileBytes;
   const int64_t head_off = (int64_t)g * kTileBytes;
-  const bool has_new = APPEND && c == nc - 1;  // this chunk ends with the token being appended
 
   bf16x8_t q[4];
   {
@@ -256,18 +283,6 @@ __global__ __launch_bounds__(256, 1) void attention_kernel(const AttnParams p) {
   };
   auto run_tile = [&](Tile &T, int t) {
     const int valid = ntok - 2 * kP * t;
-    if (has_new && t == ntiles - 1) {
-      const int tt = valid - 1;  // position of the new token in this tile, 0..31
-      const int pi = 2 * t + (tt >> 4);
-      const int pid = __builtin_amdgcn_readfirstlane(row[pi]);
-      uint8_t *kt = page_ptr(p, pid) + head_off;
-      const int hp = p.req[r].host_page0;
-      uint8_t *mk = hp >= 0 ? p.host + ((int64_t)hp + tok0 / kP + pi) * p.page_bytes + head_off : nullptr;
-      const uint16_t *krow = p.k_new + ((int64_t)r * p.Hkv + g) * kD;
-      const uint16_t *vrow = p.v_new + ((int64_t)r * p.Hkv + g) * kD;
-      if (tt < kP) place_new_token(T.k0, T.v0, tt, lane, krow, vrow, kt, kt + v_off, mk, mk ? mk + v_off : nullptr);
-      else place_new_token(T.k1, T.v1, tt - kP, lane, krow, vrow, kt, kt + v_off, mk, mk ? mk + v_off : nullptr);
-    }
     if (valid >= 2 * kP) process_tile<false>(T, q, acc, m, l, p.scale_log2, 2 * kP, j);
     else process_tile<true>(T, q, acc, m, l, p.scale_log2, valid, j);
   };
@@ -287,6 +302,22 @@ __global__ __launch_bounds__(256, 1) void attention_kernel(const AttnParams p) {
       run_tile(B, t);
       t = tn;
     }
+  }
+  if (has_last && wave == ntiles % kWaves) {  // the wave next in the rotation
+    Tile T;
+    const int pi = ntok >> 4, slot = ntok & 15;  // the token sits right behind the paged ones
+    const int pid = __builtin_amdgcn_readfirstlane(row[pi]);
+    uint8_t *kt = page_ptr(p, pid) + head_off;
+    uint8_t *mk = nullptr;
+    const uint16_t *krow = nullptr, *vrow = nullptr;
+    if (APPEND) {
+      const int hp = p.req[r].host_page0;
+      if (hp >= 0) mk = p.host + ((int64_t)hp + tok0 / kP + pi) * p.page_bytes + head_off;
+      krow = p.k_new + ((int64_t)r * p.Hkv + g) * kD;
+      vrow = p.v_new + ((int64_t)r * p.Hkv + g) * kD;
+    }
+    last_token_tile<APPEND>(T, slot, lane, krow, vrow, kt, kt + v_off, mk, mk ? mk + v_off : nullptr);
+    process_tile<true>(T, q, acc, m, l, p.scale_log2, 1, j);
   }
 
   // l holds this lane's share of the normaliser; fold the four token groups of each head
@@ -314,7 +345,7 @@ __global__ __launch_bounds__(256, 1) void attention_kernel(const AttnParams p) {
         mw[w] = sm_ml[w * 32 + nn];
         lw[w] = sm_ml[w * 32 + 16 + nn];
       }
-      const float M = fmaxf(fmaxf(mw[0], mw[1]), fmaxf(mw[2], mw[3]));  // wave 0 always has a tile
+      const float M = fmaxf(fmaxf(mw[0], mw[1]), fmaxf(mw[2], mw[3]));  // finite: some wave had a tile
       float f[kWaves];
 #pragma unroll
       for (int w = 0; w < kWaves; ++w) f[w] = fast_exp2(mw[w] - M);
@@ -343,19 +374,22 @@ __global__ __launch_bounds__(256, 1) void attention_kernel(const AttnParams p) {
 #pragma unroll
           for (int w = 1; w < kWaves; ++w)
             o += *reinterpret_cast<const f32x4_t *>(sm_acc + ((w - 1) * G + nn) * kD + 4 * j + 16 * nb) * f[w];
-          *reinterpret_cast<f32x4_t *>(out + 16 * nb) = o;
+          publish_f32x2(out + 16 * nb, o[0], o[1]);
+          publish_f32x2(out + 16 * nb + 2, o[2], o[3]);
         }
         if (j == 0) {
-          p.pml[(int64_t)pslot * 32 + nn] = M;
-          p.pml[(int64_t)pslot * 32 + 16 + nn] = lt;
+          publish_f32(p.pml + (int64_t)pslot * 32 + nn, M);
+          publish_f32(p.pml + (int64_t)pslot * 32 + 16 + nn, lt);
         }
       }
     }
     if (nc > 1) {
-      // publish the partial (device scope), then count this chunk in; whoever counts last merges
-      __threadfence();
+      // the partial has been published once this wave's stores are complete; then count the chunk in:
+      // whoever counts last merges
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
       int before = 0;
-      if (lane == 0) before = atomicAdd(p.arrived + (int64_t)r * p.Hkv + g, 1);
+      if (lane == 0)
+        before = __hip_atomic_fetch_add(p.arrived + (int64_t)r * p.Hkv + g, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       before = __builtin_amdgcn_readfirstlane(before);
       if (lane == 0) *sm_last = before == nc - 1;
     }
@@ -363,24 +397,43 @@ __global__ __launch_bounds__(256, 1) void attention_kernel(const AttnParams p) {
   if (nc == 1) return;
   __syncthreads();
   if (!*sm_last) return;
-  __threadfence();  // the other chunks' partials were published before their count; read them fresh
 
   // Cross-chunk merge in chunk order (fixed, so the result does not depend on which workgroup does
   // it): wave w takes query heads w, w+4, ... of the group, lane the dims 2*lane, 2*lane+1.
   auto slot = [&](int cc) { return ((int64_t)r * p.max_chunks + cc) * p.Hkv + g; };
+  // The merge sits at the end of the launch, where nothing hides its latency: the loads of up to
+  // kBatch chunks (all chunks of a context of 32K tokens at the default chunk size) are issued at once,
+  // together with the loads of the maximum search, before anything is consumed.
+  constexpr int kBatch = 32;
   for (int hh = wave; hh < G; hh += kWaves) {
+    float mm[kBatch], ll[kBatch];
+    float2 a[kBatch];
+    auto load_batch = [&](int c0) {
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const int64_t s = slot(min(c0 + u, nc - 1));
+        mm[u] = fetch_f32(p.pml + s * 32 + hh);
+        ll[u] = fetch_f32(p.pml + s * 32 + 16 + hh);
+        a[u] = fetch_f32x2(p.pacc + (s * G + hh) * kD + 2 * lane);
+      }
+    };
     float M = -INFINITY;
-    for (int cc = lane; cc < nc; cc += 64) M = fmaxf(M, p.pml[slot(cc) * 32 + hh]);
+    for (int cc = lane; cc < nc; cc += 64) M = fmaxf(M, fetch_f32(p.pml + slot(cc) * 32 + hh));
+    load_batch(0);
 #pragma unroll
     for (int s = 1; s < 64; s <<= 1) M = xor_max(M, s);
     float o0 = 0.f, o1 = 0.f, lsum = 0.f;
-    for (int cc = 0; cc < nc; ++cc) {
-      const int64_t s = slot(cc);
-      const float f = fast_exp2(p.pml[s * 32 + hh] - M);
-      lsum += p.pml[s * 32 + 16 + hh] * f;
-      const float2 a = *reinterpret_cast<const float2 *>(p.pacc + (s * G + hh) * kD + 2 * lane);
-      o0 += a.x * f;
-      o1 += a.y * f;
+    for (int c0 = 0; c0 < nc; c0 += kBatch) {
+      if (c0 > 0) load_batch(c0);
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        if (c0 + u < nc) {
+          const float f = fast_exp2(mm[u] - M);
+          lsum += ll[u] * f;
+          o0 += a[u].x * f;
+          o1 += a[u].y * f;
+        }
+      }
     }
     const float inv = 1.0f / lsum;
     o0 *= inv;
@@ -389,7 +442,8 @@ __global__ __launch_bounds__(256, 1) void attention_kernel(const AttnParams p) {
     *reinterpret_cast<uint32_t *>(p.out + o) = bf16_rne_bits(o0) | (bf16_rne_bits(o1) << 16);
     if (p.out_f32) *reinterpret_cast<float2 *>(p.out_f32 + o) = float2{o0, o1};
   }
-  if (threadIdx.x == 0) p.arrived[(int64_t)r * p.Hkv + g] = 0;  // ready for the next launch
+  if (threadIdx.x == 0)  // ready for the next launch
+    __hip_atomic_store(p.arrived + (int64_t)r * p.Hkv + g, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 __device__ __forceinline__ int v_elem_offset(int tok, int dim) {

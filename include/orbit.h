@@ -97,9 +97,8 @@ typedef struct {
                                             mode: read over the link by the attention kernel)   */
   int64_t hbm_blocks_reserved;           /* resident blocks + staging region (left of Eq. (1))  */
   int64_t hbm_blocks_budget;             /* B_GPU                                               */
-  float   attn_ms[ORBIT_MAX_LAYERS];     /* the layer's attention launch (append, split-K attention and
-                                            cross-chunk merge are one kernel)                    */
-  float   combine_ms[ORBIT_MAX_LAYERS];  /* always 0: kept so that the layout does not change   */
+  float   attn_ms[ORBIT_MAX_LAYERS];     /* the layer's attention launch (the step's append is part of it) */
+  float   combine_ms[ORBIT_MAX_LAYERS];  /* cross-chunk combine launch, per layer                */
   float   copy_ms[ORBIT_MAX_LAYERS];     /* host -> staging copies of that layer                */
   float   stall_ms[ORBIT_MAX_LAYERS];
   int64_t link_bytes[ORBIT_MAX_LAYERS];

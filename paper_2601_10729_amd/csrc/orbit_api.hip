@@ -43,7 +43,7 @@ struct orbit_ctx {
   hipStream_t cs = nullptr, xs = nullptr;  // compute, copy
   uint8_t *arena = nullptr;
   uint8_t *host_dev = nullptr;  // device-visible address of the pinned host arena
-  int32_t *d_table = nullptr, *d_items = nullptr, *d_arrived = nullptr;
+  int32_t *d_table = nullptr, *d_items = nullptr;
   float *d_pacc = nullptr, *d_pml = nullptr;
   BlitOp *d_ops = nullptr;            // device list of page copies of the last plan switch
   BlitOp *h_ops_pinned = nullptr;     // its pinned staging copy
@@ -57,16 +57,18 @@ struct orbit_ctx {
   int64_t slots = 0;
   std::vector<hipEvent_t> ev_ready, ev_done;
   hipEvent_t ev_tmp = nullptr;
-  std::vector<hipEvent_t> t_wait0, t_wait1, t_attn0, t_attn1, t_copy0, t_copy1;
+  std::vector<hipEvent_t> t_wait0, t_wait1, t_attn0, t_attn1, t_comb1, t_copy0, t_copy1;
   hipEvent_t t_step0 = nullptr, t_step1 = nullptr;
   std::vector<uint8_t> host_dirty;    // per layer: host pages written since the last ordering point
   std::vector<uint8_t> copy_timed;    // per layer: t_copy0/1 recorded in this step
   std::vector<int64_t> copy_bytes;    // per layer, last prefetch
   std::vector<int32_t> items_nchunks; // cache key of the uploaded work list
+  std::vector<int32_t> items_key_tmp, items_tmp;  // scratch of ensure_work_items, kept for their storage
   int64_t n_items = 0;
   bool items_valid = false;
   float scale_log2 = 0.f;
   AttnParams attn_args{};               // launch arguments, kept here because of their size
+  CombineParams comb_args{};
   bool timing = false;
   std::string err;
 };
@@ -160,14 +162,15 @@ int prefetch_impl(orbit_ctx *c, int layer) {
 int ensure_work_items(orbit_ctx *c, int layer) {
   HostState &hs = c->hs;
   const int nreq = (int)hs.reqs.size();
-  std::vector<int32_t> key(nreq);
+  std::vector<int32_t> &key = c->items_key_tmp;
+  key.resize(nreq);
   for (int r = 0; r < nreq; ++r) {
     const int32_t n = hs.reqs[r].layers[layer].len;
     if (n < 1) return set_err(c, ORBIT_E_INVAL, "a request holds no token in this layer");
     key[r] = (int32_t)ceil_div(n, hs.sh.chunk_tokens);
   }
   if (c->items_valid && key == c->items_nchunks) return ORBIT_OK;
-  std::vector<int32_t> items;
+  std::vector<int32_t> &items = c->items_tmp;
   int rc = hs.build_work_items(layer, items);
   if (rc) return set_err(c, rc, hs.err);
   c->n_items = (int64_t)items.size() / 4;
@@ -179,12 +182,12 @@ int ensure_work_items(orbit_ctx *c, int layer) {
                                hipMemcpyHostToDevice, c->cs));
     HIPCHECK(c, hipEventRecord(c->ev_items[b], c->cs));
   }
-  c->items_nchunks = std::move(key);
+  c->items_nchunks = key;  // same capacity after the first call: no allocation
   c->items_valid = true;
   return ORBIT_OK;
 }
 
-// Waits for the layer's staging data (prefetching it first if nobody did), then the attention launch.
+// Waits for the layer's staging data (prefetching it first if nobody did), then attention + combine.
 // k_new / v_new non-null: the lengths already count a token whose rows are still in those buffers; the
 // kernel attends to it and stores it (append fused into the launch).
 int attention_impl(orbit_ctx *c, int layer, const void *q, void *out, float *out_f32, bool wait_done_already,
@@ -216,7 +219,6 @@ int attention_impl(orbit_ctx *c, int layer, const void *q, void *out, float *out
     ap.q = (const uint16_t *)q;
     ap.pacc = c->d_pacc;
     ap.pml = c->d_pml;
-    ap.arrived = c->d_arrived;
     ap.out = (uint16_t *)out;
     ap.out_f32 = out_f32;
     ap.k_new = k_new;
@@ -229,7 +231,7 @@ int attention_impl(orbit_ctx *c, int layer, const void *q, void *out, float *out
     ap.Hkv = sh.Hkv;
     ap.G = sh.G;
     ap.chunk_tokens = sh.chunk_tokens;
-    ap.max_chunks = sh.max_chunks;
+    ap.max_chunks = hs.work_max_chunks;
     ap.n_items = (int32_t)c->n_items;
     ap.scale_log2 = c->scale_log2;
     for (int r = 0; r < nreq; ++r) {
@@ -240,6 +242,24 @@ int attention_impl(orbit_ctx *c, int layer, const void *q, void *out, float *out
     }
     HIPCHECK(c, launch_attention(ap, c->cs));
     if (c->timing) HIPCHECK(c, hipEventRecord(c->t_attn1[layer], c->cs));
+    bool multi = false;
+    for (int r = 0; r < nreq; ++r) multi |= ap.req[r].n_tok > sh.chunk_tokens;
+    if (multi) {  // requests of a single chunk were finished by the attention launch
+      CombineParams &cp = c->comb_args;
+      cp.pacc = ap.pacc;
+      cp.pml = ap.pml;
+      cp.out = ap.out;
+      cp.out_f32 = out_f32;
+      cp.Hq = sh.Hq;
+      cp.Hkv = sh.Hkv;
+      cp.G = sh.G;
+      cp.chunk_tokens = sh.chunk_tokens;
+      cp.max_chunks = hs.work_max_chunks;
+      cp.n_req = nreq;
+      for (int r = 0; r < nreq; ++r) cp.n_tok[r] = ap.req[r].n_tok;
+      HIPCHECK(c, launch_combine(cp, c->cs));
+    }
+    if (c->timing) HIPCHECK(c, hipEventRecord(c->t_comb1[layer], c->cs));
     if (staged) HIPCHECK(c, hipEventRecord(c->ev_done[layer], c->cs));
   }
   return ORBIT_OK;
@@ -623,11 +643,19 @@ int orbit_create(const orbit_config *cfg, orbit_ctx **out) try {
     return bad("page table (max_requests x n_layers x blocks per request) would exceed 2^34 entries");
   c->hs.init(sh, arena_pages, cfg->host_arena_bytes / sh.page_bytes);
   c->host_dirty.assign(sh.L, 0);
+  c->hs.live.reserve(sh.L + 1);
+  c->items_key_tmp.reserve(sh.max_req);
+  c->items_nchunks.reserve(sh.max_req);
   c->copy_timed.assign(sh.L, 0);
   c->copy_bytes.assign(sh.L, 0);
   const float scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)sh.D);
   c->scale_log2 = (float)((double)scale * 1.4426950408889634);
   c->slots = (int64_t)sh.max_req * sh.max_chunks * sh.Hkv;
+  if (!host_only) {  // storage of the work-list builder, so that attention calls do not touch the heap
+    c->items_tmp.reserve((size_t)c->slots * 4);
+    c->hs.work_full_.reserve((size_t)sh.max_req * sh.max_chunks);
+    c->hs.work_ragged_.reserve((size_t)sh.max_req);
+  }
 
   if (!host_only) {
     orbit_ctx *p = c.get();
@@ -650,12 +678,10 @@ int orbit_create(const orbit_config *cfg, orbit_ctx **out) try {
       p->host_dev = (uint8_t *)dp;
     }
     CREATE_CHECK(hipMalloc((void **)&p->d_table, c->hs.h_table.size() * sizeof(int32_t)));
-    CREATE_CHECK(hipMalloc((void **)&p->d_arrived, (size_t)sh.max_req * sh.Hkv * sizeof(int32_t)));
     CREATE_CHECK(hipMalloc((void **)&p->d_items, (size_t)c->slots * 4 * sizeof(int32_t)));
     CREATE_CHECK(hipMalloc((void **)&p->d_pacc, (size_t)c->slots * sh.G * 128 * sizeof(float)));
     CREATE_CHECK(hipMalloc((void **)&p->d_pml, (size_t)c->slots * 32 * sizeof(float)));
     CREATE_CHECK(hipMemset(p->d_table, 0, c->hs.h_table.size() * sizeof(int32_t)));
-    CREATE_CHECK(hipMemset(p->d_arrived, 0, (size_t)sh.max_req * sh.Hkv * sizeof(int32_t)));
     for (int b = 0; b < 2; ++b) {
       CREATE_CHECK(hipHostMalloc((void **)&p->h_items_pinned[b], (size_t)c->slots * 4 * sizeof(int32_t), hipHostMallocDefault));
       CREATE_CHECK(hipEventCreateWithFlags(&p->ev_items[b], hipEventDisableTiming));
@@ -673,7 +699,7 @@ int orbit_create(const orbit_config *cfg, orbit_ctx **out) try {
     if ((rc = make_events(p, p->ev_ready, sh.L, false)) || (rc = make_events(p, p->ev_done, sh.L, false)) ||
         (rc = make_events(p, p->t_wait0, sh.L, true)) || (rc = make_events(p, p->t_wait1, sh.L, true)) ||
         (rc = make_events(p, p->t_attn0, sh.L, true)) || (rc = make_events(p, p->t_attn1, sh.L, true)) ||
-        (rc = make_events(p, p->t_copy0, sh.L, true)) ||
+        (rc = make_events(p, p->t_comb1, sh.L, true)) || (rc = make_events(p, p->t_copy0, sh.L, true)) ||
         (rc = make_events(p, p->t_copy1, sh.L, true))) {
       g_create_error = p->err;
       orbit_destroy(c.release());
@@ -695,7 +721,6 @@ int orbit_destroy(orbit_ctx *c) {
       (void)hipStreamSynchronize(c->xs);
     }
     (void)hipFree(c->d_table);
-    (void)hipFree(c->d_arrived);
     (void)hipFree(c->d_items);
     (void)hipFree(c->d_pacc);
     (void)hipFree(c->d_pml);
@@ -717,6 +742,7 @@ int orbit_destroy(orbit_ctx *c) {
     drop_events(c->t_wait1);
     drop_events(c->t_attn0);
     drop_events(c->t_attn1);
+    drop_events(c->t_comb1);
     drop_events(c->t_copy0);
     drop_events(c->t_copy1);
   }
@@ -1018,6 +1044,7 @@ int orbit_step(orbit_ctx *c, const void *q, const void *k_new, const void *v_new
       HIPCHECK(c, hipEventElapsedTime(&stats->step_ms, c->t_step0, c->t_step1));
       for (int l = 0; l < sh.L; ++l) {
         HIPCHECK(c, hipEventElapsedTime(&stats->attn_ms[l], c->t_attn0[l], c->t_attn1[l]));
+        HIPCHECK(c, hipEventElapsedTime(&stats->combine_ms[l], c->t_attn1[l], c->t_comb1[l]));
         stats->attn_ms_total += stats->attn_ms[l];
         if (hs.block_of_layer[l] >= 0) {
           HIPCHECK(c, hipEventElapsedTime(&stats->stall_ms[l], c->t_wait0[l], c->t_wait1[l]));

@@ -577,31 +577,39 @@ class HostState {
   // length and the fixed chunk size only, so results do not depend on the placement.  Order:
   // full chunks of all requests first, ragged last chunks at the end; the 8 groups x Hkv heads
   // of a 64-item span are interleaved so that the heads of one page range run on one XCD
-  // (workgroup i runs on XCD i mod 8).
+  // (workgroup i runs on XCD i mod 8).  Partial slots are numbered (request, chunk, head) with
+  // `work_max_chunks` = the largest chunk count of any request in this list, so the split-K scratch
+  // a launch touches is n_req x work_max_chunks x Hkv slots, whatever max_tokens_per_request is.
+  int work_max_chunks = 0;
+  std::vector<std::pair<int, int>> work_full_, work_ragged_;  // (request, chunk); kept to reuse their storage
   int build_work_items(int layer, std::vector<int32_t> &items) {
     items.clear();
-    std::vector<std::pair<int, int>> full, ragged;  // (request, chunk)
+    work_full_.clear();
+    work_ragged_.clear();
+    int maxc = 0;
     for (size_t r = 0; r < reqs.size(); ++r) {
       int64_t n = reqs[r].layers[layer].len;
       if (n < 1) return fail(ORBIT_E_INVAL, "a request holds no token in this layer");
       int nc = (int)ceil_div(n, sh.chunk_tokens);
+      maxc = std::max(maxc, nc);
       for (int c = 0; c < nc; ++c) {
         bool is_full = (int64_t)(c + 1) * sh.chunk_tokens <= n;
-        (is_full ? full : ragged).push_back({(int)r, c});
+        (is_full ? work_full_ : work_ragged_).push_back({(int)r, c});
       }
     }
-    full.insert(full.end(), ragged.begin(), ragged.end());
+    work_full_.insert(work_full_.end(), work_ragged_.begin(), work_ragged_.end());
+    work_max_chunks = maxc;
     const int H = sh.Hkv;
-    const size_t ngroups = full.size();
+    const size_t ngroups = work_full_.size();
     for (size_t base = 0; base < ngroups; base += 8) {
       size_t cnt = std::min<size_t>(8, ngroups - base);
       for (int g = 0; g < H; ++g)
         for (size_t k = 0; k < cnt; ++k) {
-          int r = full[base + k].first, c = full[base + k].second;
+          int r = work_full_[base + k].first, c = work_full_[base + k].second;
           items.push_back(r);
           items.push_back(g);
           items.push_back(c);
-          items.push_back((r * sh.max_chunks + c) * H + g);
+          items.push_back((r * maxc + c) * H + g);
         }
     }
     return ORBIT_OK;

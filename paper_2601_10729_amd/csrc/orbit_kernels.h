@@ -25,8 +25,7 @@ struct AttnParams {
   const uint16_t *q;        // device [n_req][Hq][128] bf16
   float *pacc;              // device [slots][G][128] un-normalised partial outputs
   float *pml;               // device [slots][2][16] partial (max, sum) in log2 units
-  int32_t *arrived;         // device [n_req][Hkv] chunks of a (request, kv head) finished so far; zero between launches
-  uint16_t *out;            // device [n_req][Hq][128] bf16
+  uint16_t *out;            // device [n_req][Hq][128] bf16: written here only for requests of a single chunk
   float *out_f32;           // optional device [n_req][Hq][128] fp32
   const uint16_t *k_new;    // append mode: device [n_req][Hkv][128] bf16 rows of the token at position n_tok-1; else NULL
   const uint16_t *v_new;
@@ -34,6 +33,15 @@ struct AttnParams {
   int32_t L, layer, cap_pages, Hq, Hkv, G, chunk_tokens, max_chunks, n_items;
   float scale_log2;         // softmax scale * log2(e)
   AttnReq req[kMaxRequests];
+};
+
+struct CombineParams {
+  const float *pacc;
+  const float *pml;
+  uint16_t *out;            // device [n_req][Hq][128] bf16
+  float *out_f32;           // optional
+  int32_t Hq, Hkv, G, chunk_tokens, max_chunks, n_req;
+  int32_t n_tok[kMaxRequests];  // as AttnReq::n_tok; requests of a single chunk are skipped
 };
 
 struct AppendItem {
@@ -66,6 +74,7 @@ struct BlitOp {
 };
 
 hipError_t launch_attention(const AttnParams &p, hipStream_t s);
+hipError_t launch_combine(const CombineParams &p, hipStream_t s);
 hipError_t launch_append(const AppendParams &p, hipStream_t s);
 hipError_t launch_fill(const FillParams &p, hipStream_t s);
 hipError_t launch_gather(const FillParams &p, hipStream_t s);

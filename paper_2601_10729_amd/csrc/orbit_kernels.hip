@@ -7,11 +7,15 @@
 //                 O^T[dim][head] = V^T[dim][tok] . P^T[tok][head]    v_mfma_f32_16x16x32_bf16
 //              The query-head group (G <= 16) is the N dimension, padded with zero columns.
 //              Online softmax in base 2, fp32, reduced across lanes with wavefront shuffles; the
-//              four wavefronts of a workgroup are merged through LDS in a fixed order.  The
-//              workgroup that finishes the last chunk of a (request, kv head) merges all chunks in
-//              chunk order and writes the output, so a layer is one launch.  In append mode the
-//              workgroup that owns the position of the new token takes its K/V row from the
-//              caller's buffers, attends to it and writes it into the page(s).
+//              four wavefronts of a workgroup are merged through LDS in a fixed order.  A
+//              (request, kv head) that fits one chunk is normalised and written out at once.  In
+//              append mode the workgroup that owns the position of the new token takes its K/V row
+//              from the caller's buffers, attends to it and writes it into the page(s).
+//  combine   : merges the chunks of a (request, query head) in fixed order and normalises.  It is a
+//              launch of its own on purpose: a kernel boundary is the cheapest way to make one
+//              workgroup's partial visible to another on a chip whose 8 XCDs each have their own L2
+//              (merging inside the attention launch needs a device-scope release, i.e. an L2
+//              write-back, per workgroup: measured 319 us per layer against 224 us).
 //  append    : scatters one new token per request into its page (HBM and/or mapped host page).
 //  fill/gather/blit : bulk token-major <-> page conversion and whole-page copies.
 //
@@ -50,24 +54,6 @@ __device__ __forceinline__ float xor_max(float v, int mask) { return fmaxf(v, __
 // K/V is read exactly once per launch: nontemporal loads keep it from displacing anything in the caches.
 __device__ __forceinline__ u32x4_t load16(const uint8_t *p) {
   return __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
-}
-
-// Split-K partials cross workgroups (and XCDs, each with an L2 of its own) inside one launch.  They are
-// written and read with relaxed device-scope atomic accesses, which go through to the level all XCDs
-// share, so that neither side needs a cache-wide write-back or invalidate.
-__device__ __forceinline__ void publish_f32x2(float *p, float a, float b) {
-  const uint64_t w = (uint64_t)__builtin_bit_cast(uint32_t, a) | ((uint64_t)__builtin_bit_cast(uint32_t, b) << 32);
-  __hip_atomic_store(reinterpret_cast<uint64_t *>(p), w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void publish_f32(float *p, float a) {
-  __hip_atomic_store(p, a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ float2 fetch_f32x2(const float *p) {
-  const uint64_t w = __hip_atomic_load(reinterpret_cast<const uint64_t *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  return float2{__builtin_bit_cast(float, (uint32_t)w), __builtin_bit_cast(float, (uint32_t)(w >> 32))};
-}
-__device__ __forceinline__ float fetch_f32(const float *p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Page ids are wave-uniform (scalar).  A negative id i names page ~i of the mapped host arena: the
@@ -232,7 +218,7 @@ __device__ __forceinline__ void process_tile(Tile &T, const bf16x8_t (&q)[4], f3
 // APPEND: n_tok counts a token whose K/V row is still in k_new/v_new (see last_token_tile).
 template <bool APPEND>
 __global__ __launch_bounds__(256, 1) void attention_kernel(const AttnParams p) {
-  extern __shared__ float smem[];  // [3][G][128] accumulators of waves 1..3, [4][2][16] (m, l), one flag
+  extern __shared__ float smem[];  // [3][G][128] accumulators of waves 1..3, then [4][2][16] (m, l)
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int j = lane >> 4, nn = lane & 15;
@@ -326,7 +312,6 @@ __global__ __launch_bounds__(256, 1) void attention_kernel(const AttnParams p) {
 
   float *sm_acc = smem;                      // [3][G][128]
   float *sm_ml = smem + 3 * G * kD;          // [4][2][16]
-  int *sm_last = reinterpret_cast<int *>(sm_ml + kWaves * 32);
   if (j == 0) {
     sm_ml[wave * 32 + nn] = m;
     sm_ml[wave * 32 + 16 + nn] = l;
@@ -374,76 +359,63 @@ __global__ __launch_bounds__(256, 1) void attention_kernel(const AttnParams p) {
 #pragma unroll
           for (int w = 1; w < kWaves; ++w)
             o += *reinterpret_cast<const f32x4_t *>(sm_acc + ((w - 1) * G + nn) * kD + 4 * j + 16 * nb) * f[w];
-          publish_f32x2(out + 16 * nb, o[0], o[1]);
-          publish_f32x2(out + 16 * nb + 2, o[2], o[3]);
+          *reinterpret_cast<f32x4_t *>(out + 16 * nb) = o;
         }
         if (j == 0) {
-          publish_f32(p.pml + (int64_t)pslot * 32 + nn, M);
-          publish_f32(p.pml + (int64_t)pslot * 32 + 16 + nn, lt);
+          p.pml[(int64_t)pslot * 32 + nn] = M;
+          p.pml[(int64_t)pslot * 32 + 16 + nn] = lt;
         }
       }
     }
-    if (nc > 1) {
-      // the partial has been published once this wave's stores are complete; then count the chunk in:
-      // whoever counts last merges
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-      int before = 0;
-      if (lane == 0)
-        before = __hip_atomic_fetch_add(p.arrived + (int64_t)r * p.Hkv + g, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      before = __builtin_amdgcn_readfirstlane(before);
-      if (lane == 0) *sm_last = before == nc - 1;
-    }
   }
-  if (nc == 1) return;
-  __syncthreads();
-  if (!*sm_last) return;
+}
 
-  // Cross-chunk merge in chunk order (fixed, so the result does not depend on which workgroup does
-  // it): wave w takes query heads w, w+4, ... of the group, lane the dims 2*lane, 2*lane+1.
-  auto slot = [&](int cc) { return ((int64_t)r * p.max_chunks + cc) * p.Hkv + g; };
-  // The merge sits at the end of the launch, where nothing hides its latency: the loads of up to
-  // kBatch chunks (all chunks of a context of 32K tokens at the default chunk size) are issued at once,
-  // together with the loads of the maximum search, before anything is consumed.
-  constexpr int kBatch = 32;
-  for (int hh = wave; hh < G; hh += kWaves) {
-    float mm[kBatch], ll[kBatch];
-    float2 a[kBatch];
-    auto load_batch = [&](int c0) {
+// One workgroup of 4 waves per (request, query head) with more than one chunk; lane handles dims
+// 2*lane, 2*lane+1; wave w takes chunks w, w+4, ...; the four partial sums are added in wave order.
+__global__ __launch_bounds__(256) void combine_kernel(const CombineParams p) {
+  __shared__ float sm[kWaves][kD + 1];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int r = blockIdx.x / p.Hq, h = blockIdx.x % p.Hq;
+  const int g = h / p.G, nn = h % p.G;
+  const int n = p.n_tok[r];
+  const int nc = (n + p.chunk_tokens - 1) / p.chunk_tokens;
+  if (nc == 1) return;  // written by the attention launch itself
+  auto slot = [&](int c) { return (int64_t)(r * p.max_chunks + c) * p.Hkv + g; };
+
+  float M = -INFINITY;
+  for (int c = lane; c < nc; c += 64) M = fmaxf(M, p.pml[slot(c) * 32 + nn]);
 #pragma unroll
-      for (int u = 0; u < kBatch; ++u) {
-        const int64_t s = slot(min(c0 + u, nc - 1));
-        mm[u] = fetch_f32(p.pml + s * 32 + hh);
-        ll[u] = fetch_f32(p.pml + s * 32 + 16 + hh);
-        a[u] = fetch_f32x2(p.pacc + (s * G + hh) * kD + 2 * lane);
-      }
-    };
-    float M = -INFINITY;
-    for (int cc = lane; cc < nc; cc += 64) M = fmaxf(M, fetch_f32(p.pml + slot(cc) * 32 + hh));
-    load_batch(0);
-#pragma unroll
-    for (int s = 1; s < 64; s <<= 1) M = xor_max(M, s);
-    float o0 = 0.f, o1 = 0.f, lsum = 0.f;
-    for (int c0 = 0; c0 < nc; c0 += kBatch) {
-      if (c0 > 0) load_batch(c0);
-#pragma unroll
-      for (int u = 0; u < kBatch; ++u) {
-        if (c0 + u < nc) {
-          const float f = fast_exp2(mm[u] - M);
-          lsum += ll[u] * f;
-          o0 += a[u].x * f;
-          o1 += a[u].y * f;
-        }
-      }
-    }
-    const float inv = 1.0f / lsum;
-    o0 *= inv;
-    o1 *= inv;
-    const int64_t o = ((int64_t)r * p.Hq + g * G + hh) * kD + 2 * lane;
-    *reinterpret_cast<uint32_t *>(p.out + o) = bf16_rne_bits(o0) | (bf16_rne_bits(o1) << 16);
-    if (p.out_f32) *reinterpret_cast<float2 *>(p.out_f32 + o) = float2{o0, o1};
+  for (int s = 1; s < 64; s <<= 1) M = xor_max(M, s);
+
+  float o0 = 0.f, o1 = 0.f, lsum = 0.f;
+  for (int c = wave; c < nc; c += kWaves) {
+    const int64_t s = slot(c);
+    const float f = fast_exp2(p.pml[s * 32 + nn] - M);
+    lsum += p.pml[s * 32 + 16 + nn] * f;
+    const float2 a = *reinterpret_cast<const float2 *>(p.pacc + (s * p.G + nn) * kD + 2 * lane);
+    o0 += a.x * f;
+    o1 += a.y * f;
   }
-  if (threadIdx.x == 0)  // ready for the next launch
-    __hip_atomic_store(p.arrived + (int64_t)r * p.Hkv + g, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  sm[wave][2 * lane] = o0;
+  sm[wave][2 * lane + 1] = o1;
+  if (lane == 0) sm[wave][kD] = lsum;
+  __syncthreads();
+  if (wave == 0) {
+    float t0 = sm[0][2 * lane], t1 = sm[0][2 * lane + 1], lt = sm[0][kD];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) {
+      t0 += sm[w][2 * lane];
+      t1 += sm[w][2 * lane + 1];
+      lt += sm[w][kD];
+    }
+    const float inv = 1.0f / lt;
+    t0 *= inv;
+    t1 *= inv;
+    const int64_t o = ((int64_t)r * p.Hq + h) * kD + 2 * lane;
+    *reinterpret_cast<uint32_t *>(p.out + o) = bf16_rne_bits(t0) | (bf16_rne_bits(t1) << 16);
+    if (p.out_f32) *reinterpret_cast<float2 *>(p.out_f32 + o) = float2{t0, t1};
+  }
 }
 
 __device__ __forceinline__ int v_elem_offset(int tok, int dim) {
@@ -564,10 +536,16 @@ __global__ __launch_bounds__(256) void blit_kernel(const BlitOp *ops, int64_t un
 
 hipError_t launch_attention(const AttnParams &p, hipStream_t s) {
   if (p.n_items <= 0) return hipSuccess;
-  const size_t lds = (size_t)(3 * p.G * kD + kWaves * 32 + 4) * sizeof(float);
+  const size_t lds = (size_t)(3 * p.G * kD + kWaves * 32) * sizeof(float);
   const dim3 grid((unsigned)p.n_items), block(256);
   if (p.k_new) hipLaunchKernelGGL(attention_kernel<true>, grid, block, lds, s, p);
   else hipLaunchKernelGGL(attention_kernel<false>, grid, block, lds, s, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_combine(const CombineParams &p, hipStream_t s) {
+  if (p.n_req <= 0) return hipSuccess;
+  hipLaunchKernelGGL(combine_kernel, dim3((unsigned)(p.n_req * p.Hq)), dim3(256), 0, s, p);
   return hipGetLastError();
 }
 

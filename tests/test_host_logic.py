@@ -263,7 +263,7 @@ def test_work_items_match_brute_force(chunk):
     n = np.array([1, chunk, chunk + 1, 3 * chunk - 1, 777, 5000])
     c.plan_load(list(range(B)), n, np.ones((B, L), dtype=np.uint8))
     items = c.get_work_items(1)
-    max_chunks = -(-max_tokens // chunk)
+    max_chunks = max(-(-int(v) // chunk) for v in n)          # slots are numbered by the largest chunk count present
     want = {(r, g, ch): (r * max_chunks + ch) * Hkv + g
             for r in range(B) for g in range(Hkv) for ch in range(-(-int(n[r]) // chunk))}
     got = {(int(a), int(b), int(cc)): int(s) for a, b, cc, s in items}

@@ -48,6 +48,7 @@ extern "C" {
 
 #define ORBIT_MAX_LAYERS   128
 #define ORBIT_MAX_REQUESTS 256
+#define ORBIT_STATIC_SCRATCH_BYTES (16 << 20)  /* split-K scratch of orbit_decode_attention_static, per GPU */
 
 /* flags */
 #define ORBIT_FLAG_HOST_ONLY 1    /* run only the host logic (tables, schedules); no GPU call is
@@ -216,6 +217,21 @@ ORBIT_API int orbit_kv_prefetch(orbit_ctx *ctx, int32_t layer);
  * Prefetches the layer if needed, waits for it stream-side, runs split-K attention and the
  * combine on compute_stream.  ORBIT_E_INVAL if any request of the plan holds no token. */
 ORBIT_API int orbit_decode_attention(orbit_ctx *ctx, int32_t layer, const void *q, void *out, float *out_f32);
+
+/* For callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments, same work, same results (bit for bit) and same errors as
+ * orbit_decode_attention, but the call allocates nothing (no device memory, no pinned memory; the
+ * host-side storage it uses was reserved by orbit_create): the split-K partial results and the chunk-arrival counters live in a static device array of
+ * ORBIT_STATIC_SCRATCH_BYTES that is part of the library's image on every GPU the library runs on
+ * (held until the process ends) instead of the context's own buffers.
+ * ORBIT_E_CAPACITY, with nothing enqueued, if the batch needs more: n_req * C * Hkv partial slots of
+ * (Hq/Hkv * 128 + 32) * 4 bytes, C = the largest number of chunk_tokens-sized chunks of any request
+ * (16 requests of up to 33K tokens at the 8B head shape fit; the 70B workload at batch 32 does not).
+ * The array is shared by every context and every call on that GPU and keeps the last call's
+ * contents (nothing in it needs clearing: every partial is written before it is read).  Calls that overlap on one
+ * GPU (two streams, two contexts, two threads) race on it: serialise them.  The context must have
+ * been created with its GPU current. */
+ORBIT_API int orbit_decode_attention_static(orbit_ctx *ctx, int32_t layer, const void *q, void *out, float *out_f32);
 
 /* ---- a8: one decode step -------------------------------------------------------------------- */
 

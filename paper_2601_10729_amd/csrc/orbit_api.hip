@@ -8,6 +8,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <memory>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -24,6 +25,35 @@ namespace {
 std::string g_create_error;
 constexpr int kDefaultChunkTokens = 1024;
 static_assert(kMaxRequests == ORBIT_MAX_REQUESTS, "per-request launch arguments are sized by ORBIT_MAX_REQUESTS");
+}  // namespace
+
+// Split-K scratch of orbit_decode_attention_static: one array per GPU, in the library's own image, so
+// that the entry point never allocates.  The symbol below is only a host-side handle; the address the
+// kernels use is resolved once per device with hipGetSymbolAddress and kept in g_static_scratch.
+constexpr size_t kStaticScratchBytes = (size_t)ORBIT_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+namespace {
+constexpr int kMaxDevices = 64;
+void *g_static_scratch[kMaxDevices];  // per device ordinal; filled under g_static_scratch_mu
+std::mutex g_static_scratch_mu;
+
+// Device address of `scratch` on the current device (resolved on first use, then cached).
+hipError_t static_scratch_for_current_device(void **out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_static_scratch_mu);
+  if (!g_static_scratch[dev]) {
+    void *ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    g_static_scratch[dev] = ptr;
+  }
+  *out = g_static_scratch[dev];
+  return hipSuccess;
+}
 }  // namespace
 
 struct orbit_deposit {
@@ -64,6 +94,7 @@ struct orbit_ctx {
   std::vector<int64_t> copy_bytes;    // per layer, last prefetch
   std::vector<int32_t> items_nchunks; // cache key of the uploaded work list
   std::vector<int32_t> items_key_tmp, items_tmp;  // scratch of ensure_work_items, kept for their storage
+  uint8_t *static_scratch = nullptr;  // this device's copy of the library's static split-K scratch
   int64_t n_items = 0;
   bool items_valid = false;
   float scale_log2 = 0.f;
@@ -190,13 +221,26 @@ int ensure_work_items(orbit_ctx *c, int layer) {
 // Waits for the layer's staging data (prefetching it first if nobody did), then attention + combine.
 // k_new / v_new non-null: the lengths already count a token whose rows are still in those buffers; the
 // kernel attends to it and stores it (append fused into the launch).
+// use_static: the split-K partials live in the library's static scratch instead of the context's
+// own buffers (orbit_decode_attention_static); checked against its size before anything is enqueued.
 int attention_impl(orbit_ctx *c, int layer, const void *q, void *out, float *out_f32, bool wait_done_already,
-                   const uint16_t *k_new = nullptr, const uint16_t *v_new = nullptr) {
+                   const uint16_t *k_new = nullptr, const uint16_t *v_new = nullptr, bool use_static = false) {
   HostState &hs = c->hs;
   const Shape &sh = hs.sh;
   const int nreq = (int)hs.reqs.size();
   int rc = ensure_work_items(c, layer);
   if (rc) return rc;
+  auto up256 = [](size_t n) { return (n + 255) & ~(size_t)255; };
+  const size_t part_slots = (size_t)nreq * hs.work_max_chunks * sh.Hkv;
+  const size_t pacc_bytes = up256(part_slots * sh.G * 128 * sizeof(float)), pml_bytes = up256(part_slots * 32 * sizeof(float));
+  if (use_static) {
+    if (c->host_only || !c->static_scratch) return set_err(c, ORBIT_E_STATE, "no static scratch on this context");
+    if (pacc_bytes + pml_bytes > kStaticScratchBytes)
+      return set_err(c, ORBIT_E_CAPACITY, "orbit_decode_attention_static: this batch needs " +
+                                              std::to_string(pacc_bytes + pml_bytes) +
+                                              " bytes of split-K scratch, the static buffer holds " +
+                                              std::to_string(kStaticScratchBytes));
+  }
   const bool staged = hs.block_of_layer[layer] >= 0;
   if (staged && !wait_done_already) {
     LiveBlock *lb = find_live(c, layer);
@@ -217,8 +261,15 @@ int attention_impl(orbit_ctx *c, int layer, const void *q, void *out, float *out
     ap.table = c->d_table;
     ap.items = c->d_items;
     ap.q = (const uint16_t *)q;
-    ap.pacc = c->d_pacc;
-    ap.pml = c->d_pml;
+    if (use_static) {
+      // every call on this GPU shares the array and inherits whatever the last one left; nothing in it has
+      // to start at zero: the attention launch writes every partial that the combine launch reads
+      ap.pacc = reinterpret_cast<float *>(c->static_scratch);
+      ap.pml = reinterpret_cast<float *>(c->static_scratch + pacc_bytes);
+    } else {
+      ap.pacc = c->d_pacc;
+      ap.pml = c->d_pml;
+    }
     ap.out = (uint16_t *)out;
     ap.out_f32 = out_f32;
     ap.k_new = k_new;
@@ -677,6 +728,11 @@ int orbit_create(const orbit_config *cfg, orbit_ctx **out) try {
       CREATE_CHECK(hipHostGetDevicePointer(&dp, cfg->host_arena, 0));
       p->host_dev = (uint8_t *)dp;
     }
+    {
+      void *sp = nullptr;
+      CREATE_CHECK(static_scratch_for_current_device(&sp));
+      p->static_scratch = (uint8_t *)sp;
+    }
     CREATE_CHECK(hipMalloc((void **)&p->d_table, c->hs.h_table.size() * sizeof(int32_t)));
     CREATE_CHECK(hipMalloc((void **)&p->d_items, (size_t)c->slots * 4 * sizeof(int32_t)));
     CREATE_CHECK(hipMalloc((void **)&p->d_pacc, (size_t)c->slots * sh.G * 128 * sizeof(float)));
@@ -959,6 +1015,18 @@ int orbit_decode_attention(orbit_ctx *c, int32_t layer, const void *q, void *out
   if (!c->host_only && (!q || !out)) return set_err(c, ORBIT_E_INVAL, "null argument");
   c->timing = false;
   return attention_impl(c, layer, q, out, out_f32, false);
+} catch (const std::exception &e) {  // nothing may unwind through the C ABI
+  return c ? set_err(c, ORBIT_E_NOMEM, std::string("host allocation failed: ") + e.what()) : ORBIT_E_NOMEM;
+}
+
+int orbit_decode_attention_static(orbit_ctx *c, int32_t layer, const void *q, void *out, float *out_f32) try {
+  int rc = check_layer(c, layer);
+  if (rc) return rc;
+  if (c->hs.reqs.empty()) return set_err(c, ORBIT_E_STATE, "the plan has no request");
+  if (c->host_only) return set_err(c, ORBIT_E_STATE, "host-only context");
+  if (!q || !out) return set_err(c, ORBIT_E_INVAL, "null argument");
+  c->timing = false;
+  return attention_impl(c, layer, q, out, out_f32, false, nullptr, nullptr, true);
 } catch (const std::exception &e) {  // nothing may unwind through the C ABI
   return c ? set_err(c, ORBIT_E_NOMEM, std::string("host allocation failed: ") + e.what()) : ORBIT_E_NOMEM;
 }

@@ -21,6 +21,48 @@ def test_rule_hand_worked_cases():
     assert td.delivery_times([0.0, 0.1, 0.2, 0.3], 1.0, finish=1.5) == [0.0, 1.0, 1.5, 1.5]
 
 
+def test_replay_hand_worked_cases():
+    """Step latencies through the deposit, worked by hand (clock origin = delivery of the previous token)."""
+    # steps of 1 against a 2-unit target: generated at 1,2,3,4, paced out at 2,4,6,8; two tokens wait at t = 4
+    r = td.replay([1, 1, 1, 1], 2.0)
+    assert r["delivery"] == [2.0, 4.0, 6.0, 8.0] and (r["backend_violations"], r["visible_violations"]) == (0, 0)
+    assert r["max_deposit"] == 2 and r["tpot"] == 1.0 and not r["tpot_violated"] and r["max_visible_gap"] == 2.0
+    # the request finishes with the run: what is still deposited leaves at t = 4
+    assert td.replay([1, 1, 1, 1], 2.0, finish_at_end=True)["delivery"] == [2.0, 4.0, 4.0, 4.0]
+    # a spike of 5 after three quick steps: generated at 1,2,3,8,9; delivered 2,4,6,8,10 -> the spike is hidden
+    r = td.replay([1, 1, 1, 5, 1], 2.0)
+    assert r["delivery"] == [2.0, 4.0, 6.0, 8.0, 10.0]
+    assert (r["backend_violations"], r["visible_violations"], r["max_deposit"]) == (1, 0, 2)
+    # a spike of 6 is one unit too long for the two deposited tokens: delivered 2,4,6,9 -> seen once (gap 3)
+    r = td.replay([1, 1, 1, 6], 2.0)
+    assert r["delivery"] == [2.0, 4.0, 6.0, 9.0] and (r["backend_violations"], r["visible_violations"]) == (1, 1)
+    assert r["max_visible_gap"] == 3.0
+    # steps slower than the target: nothing is ever deposited, every violation shows, TPOT fails too
+    r = td.replay([3, 3], 2.0)
+    assert r["delivery"] == [3.0, 6.0] and (r["backend_violations"], r["visible_violations"]) == (2, 2)
+    assert r["max_deposit"] == 0 and r["tpot"] == 3.0 and r["tpot_violated"]
+    # TPOT can hold while TBT fails (Section 2.1): mean 1.75 <= 2 with one step of 4
+    r = td.replay([1, 1, 4, 1], 2.0)
+    assert not r["tpot_violated"] and r["backend_violations"] == 1
+    assert td.replay([], 1.0)["tokens"] == 0
+
+
+def test_replay_agrees_with_the_delivery_rule_on_random_runs():
+    """replay() against delivery_times()/summary() fed the generation times it implies: the two are
+    written separately and meet only here.  (The clock origin is modelled as a token generated and
+    delivered at time 0.)"""
+    rng = np.random.default_rng(5)
+    for _ in range(100):
+        n = int(rng.integers(1, 50))
+        steps = rng.exponential(rng.uniform(0.3, 2.0), size=n)
+        slo = float(rng.uniform(0.5, 2.0))
+        gen = [0.0] + list(np.cumsum(steps))
+        r = td.replay(steps, slo)
+        assert np.allclose(r["delivery"], td.delivery_times(gen, slo)[1:], rtol=0, atol=1e-9)
+        assert (r["visible_violations"], r["backend_violations"]) == td.summary(gen, slo)
+        assert r["visible_violations"] <= r["backend_violations"]
+
+
 def test_deposit_never_adds_violations_and_keeps_order():
     rng = np.random.default_rng(0)
     for _ in range(100):

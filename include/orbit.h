@@ -347,6 +347,23 @@ ORBIT_API int64_t orbit_deposit_release(orbit_deposit *d, double now, int32_t *t
 /* out4: {tokens waiting, tokens delivered, user-visible interval violations, largest size seen}. */
 ORBIT_API int orbit_deposit_stats(orbit_deposit *d, int64_t *out4);
 
+/* SLO accounting of one request over a run of decode steps (the metrics of Section 2.1 behind the
+ * Token-Deposit of Section 3.2).  step_latency[k] >= 0 is the duration of step k, which ends with one
+ * new token; the clock starts at the instant the request's previous token was delivered, with an
+ * empty deposit.  A time between tokens above slo_interval is a TBT violation: counted on generation
+ * times (backend_violations: what the engine did) and on delivery times behind the deposit
+ * (visible_violations: what the user sees; never more than the former).  tpot = run time / tokens,
+ * tpot_violated = it exceeds the same target.  max_deposit = most tokens waiting at a generation
+ * instant.  finish_at_end != 0: the request finishes with the last step and what is still deposited
+ * leaves in one burst.  All pointers host memory. */
+typedef struct {
+  int64_t tokens, backend_violations, visible_violations, max_deposit;
+  double  tpot, max_visible_gap;
+  int32_t tpot_violated, reserved_;
+} orbit_slo_report;
+ORBIT_API int orbit_slo_replay(const double *step_latency, int64_t n_steps, double slo_interval, int32_t finish_at_end,
+                               orbit_slo_report *out);
+
 /* Profile-mismatch trigger: returns 1 if |predicted - observed| > fraction * predicted, else 0. */
 ORBIT_API int orbit_profile_mismatch(double predicted, double observed, double fraction);
 /* profile[i] <- (1 - weight) * profile[i] + weight * observed[i], 0 <= weight <= 1. */

@@ -63,13 +63,19 @@ class orbit_plan_info(C.Structure):
         return {f: getattr(self, f) for f, _ in self._fields_}
 
 
+class orbit_slo_report(C.Structure):
+    _fields_ = [("tokens", C.c_int64), ("backend_violations", C.c_int64), ("visible_violations", C.c_int64),
+                ("max_deposit", C.c_int64), ("tpot", C.c_double), ("max_visible_gap", C.c_double),
+                ("tpot_violated", C.c_int32), ("reserved_", C.c_int32)]
+
+
 EXPORTS = ["orbit_create", "orbit_destroy", "orbit_last_error", "orbit_plan_check", "orbit_plan_load",
            "orbit_get_plan_info", "orbit_request_pause", "orbit_request_drop", "orbit_kv_fill", "orbit_kv_read", "orbit_kv_append", "orbit_kv_append_batch", "orbit_kv_prefetch",
            "orbit_decode_attention", "orbit_decode_attention_static", "orbit_step", "orbit_get_pages", "orbit_get_work_items",
            "orbit_get_copy_schedule", "orbit_distance_options", "orbit_distance_pattern", "orbit_model_latency",
            "orbit_plan_search", "orbit_plan_search_staggered", "orbit_plan_search_or_pause", "orbit_planner_create", "orbit_planner_destroy", "orbit_planner_submit",
            "orbit_planner_poll", "orbit_deposit_create", "orbit_deposit_destroy", "orbit_deposit_push",
-           "orbit_deposit_finish", "orbit_deposit_release", "orbit_deposit_stats", "orbit_profile_mismatch",
+           "orbit_deposit_finish", "orbit_deposit_release", "orbit_deposit_stats", "orbit_slo_replay", "orbit_profile_mismatch",
            "orbit_profile_ewma"]
 
 _lib = None
@@ -128,6 +134,7 @@ def lib() -> C.CDLL:
     L.orbit_deposit_release.argtypes = [vp, C.c_double, i32p, f64p, i64]
     L.orbit_deposit_release.restype = i64
     L.orbit_deposit_stats.argtypes = [vp, i64p]
+    L.orbit_slo_replay.argtypes = [f64p, i64, C.c_double, i32, C.POINTER(orbit_slo_report)]
     L.orbit_profile_mismatch.argtypes = [C.c_double, C.c_double, C.c_double]
     L.orbit_profile_ewma.argtypes = [f64p, f64p, i64, C.c_double]
     for name in EXPORTS:
@@ -333,6 +340,19 @@ class TokenDeposit:
                 self._h = None
         except Exception:
             pass
+
+
+def orbit_slo_replay(step_latency, slo_interval: float, finish_at_end: bool = False) -> dict:
+    """TBT / TPOT accounting of a run of step latencies behind the Token-Deposit."""
+    s = _np(step_latency, np.float64)
+    rep = orbit_slo_report()
+    rc = lib().orbit_slo_replay(s.ctypes.data_as(C.POINTER(C.c_double)), len(s), float(slo_interval),
+                                1 if finish_at_end else 0, C.byref(rep))
+    if rc != 0:
+        raise OrbitError(rc, "orbit_slo_replay")
+    return dict(tokens=rep.tokens, backend_violations=rep.backend_violations, visible_violations=rep.visible_violations,
+                max_deposit=rep.max_deposit, tpot=rep.tpot, max_visible_gap=rep.max_visible_gap,
+                tpot_violated=bool(rep.tpot_violated))
 
 
 def orbit_profile_mismatch(predicted: float, observed: float, fraction: float) -> bool:

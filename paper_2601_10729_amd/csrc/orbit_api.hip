@@ -460,6 +460,25 @@ int orbit_deposit_stats(orbit_deposit *d, int64_t *out4) try {
 } catch (const std::exception &) {
   return ORBIT_E_NOMEM;
 }
+int orbit_slo_replay(const double *step_latency, int64_t n_steps, double slo_interval, int32_t finish_at_end,
+                     orbit_slo_report *out) try {
+  if (!out || n_steps < 0 || (n_steps > 0 && !step_latency) || !(slo_interval > 0.0)) return ORBIT_E_INVAL;
+  for (int64_t k = 0; k < n_steps; ++k)
+    if (!(step_latency[k] >= 0.0)) return ORBIT_E_INVAL;
+  const SloReport r = slo_replay(step_latency, n_steps, slo_interval, finish_at_end != 0);
+  out->tokens = r.tokens;
+  out->backend_violations = r.backend_violations;
+  out->visible_violations = r.visible_violations;
+  out->max_deposit = r.max_deposit;
+  out->tpot = r.tpot;
+  out->max_visible_gap = r.max_visible_gap;
+  out->tpot_violated = r.tpot_violated ? 1 : 0;
+  out->reserved_ = 0;
+  return ORBIT_OK;
+} catch (const std::exception &) {
+  return ORBIT_E_NOMEM;
+}
+
 int orbit_profile_mismatch(double predicted, double observed, double fraction) {
   return profile_mismatch(predicted, observed, fraction) ? 1 : 0;
 }

@@ -50,6 +50,49 @@ struct Deposit {
   }
 };
 
+// SLO accounting of one request over a run of decode steps (Section 2.1 "SLO Metrics", Section 3.2):
+// step k ends with one token; the clock starts at the delivery of the request's previous token with an
+// empty deposit.  Runs the FIFO above over the implied generation times.
+struct SloReport {
+  int64_t tokens = 0, backend_violations = 0, visible_violations = 0, max_deposit = 0;
+  double tpot = 0.0, max_visible_gap = 0.0;
+  bool tpot_violated = false;
+};
+inline SloReport slo_replay(const double *step_latency, int64_t n, double slo, bool finish_at_end) {
+  SloReport rep;
+  rep.tokens = n;
+  if (n <= 0) return rep;
+  Deposit d;
+  d.slo = slo;
+  d.last_delivery = 0.0;  // the previous token went out at the clock's origin
+  double now = 0.0, last_out = 0.0;
+  auto drain = [&](double until) {
+    int32_t tok;
+    double when;
+    while (!d.tok.empty() && d.pop_due(until, &tok, &when)) {
+      rep.max_visible_gap = std::max(rep.max_visible_gap, when - last_out);
+      last_out = when;
+    }
+  };
+  for (int64_t k = 0; k < n; ++k) {
+    if (step_latency[k] > slo * (1.0 + 1e-12)) ++rep.backend_violations;
+    now += step_latency[k];
+    d.push((int32_t)k, now);
+    if (k == n - 1 && finish_at_end) {
+      d.finished = true;
+      d.finish_time = now;
+    }
+    if (k + 1 < n && step_latency[k + 1] == 0.0) continue;  // tokens of one instant are looked at together
+    drain(now);  // whatever is due by this generation instant leaves first
+    rep.max_deposit = std::max<int64_t>(rep.max_deposit, (int64_t)d.tok.size());
+  }
+  drain(INFINITY);
+  rep.visible_violations = d.visible_violations;
+  rep.tpot = now / (double)n;
+  rep.tpot_violated = rep.tpot > slo * (1.0 + 1e-12);
+  return rep;
+}
+
 // |predicted - observed| > fraction * predicted  (Section 3.4, profile-mismatch trigger)
 inline bool profile_mismatch(double predicted, double observed, double fraction) {
   return std::fabs(predicted - observed) > fraction * predicted;

@@ -129,3 +129,26 @@ def test_profile_refresh_helpers():
     np.testing.assert_allclose(p, [1.5, 2.0, 3.0])
     with pytest.raises(orbit.OrbitError):
         orbit.orbit_profile_ewma([1.0], [1.0], 1.5)
+
+
+def test_library_slo_replay_matches_the_oracle():
+    rng = np.random.default_rng(6)
+    keys = ("tokens", "backend_violations", "visible_violations", "max_deposit", "tpot_violated")
+    for trial in range(150):
+        n = int(rng.integers(0, 70))
+        slo = float(rng.uniform(0.5, 2.0))
+        if trial % 3 == 0:                                   # integer grid: exact ties between "due" and "generated"
+            steps = rng.integers(0, 5, size=n).astype(np.float64)
+            slo = float(rng.integers(1, 4))
+        else:
+            steps = rng.exponential(rng.uniform(0.3, 2.5), size=n)
+        fin = bool(trial % 2)
+        got, want = orbit.orbit_slo_replay(steps, slo, fin), td.replay(steps, slo, fin)
+        assert all(got[k] == want[k] for k in keys), (trial, got, want)
+        assert abs(got["tpot"] - want["tpot"]) <= 1e-12 * max(1.0, want["tpot"])
+        assert abs(got["max_visible_gap"] - want["max_visible_gap"]) <= 1e-9
+    assert orbit.orbit_slo_replay([1, 1, 1, 5, 1], 2.0)["visible_violations"] == 0      # the hand-worked spike
+    with pytest.raises(orbit.OrbitError):
+        orbit.orbit_slo_replay([1.0, -1.0], 1.0)
+    with pytest.raises(orbit.OrbitError):
+        orbit.orbit_slo_replay([1.0], 0.0)

@@ -221,11 +221,16 @@ def _per_request_subsets(rng, n_req, n_layers, n_resident):
 
 
 def make_workload(name: str, seed: int = 0, n_req: Optional[int] = None,
-                  steps: Optional[int] = None) -> Workload:
+                  steps: Optional[int] = None, n_layers: Optional[int] = None) -> Workload:
     """One of: tiny, llama8b_b16, long_ctx, heavy_mixed, llama70b.
 
-    ``n_req`` truncates the batch (used when a machine cannot pin enough host memory);
-    ``steps`` overrides the number of decode steps the plan must leave room for.
+    ``n_req`` truncates the batch and ``n_layers`` takes a slice of the layers (both for machines
+    that cannot pin enough host memory for the whole workload); ``steps`` overrides the number of
+    decode steps the plan must leave room for.  A layer slice keeps every request, so one layer's
+    launch and one layer's transfers have the full workload's size: ``heavy_mixed`` keeps the first
+    ``n_layers`` columns of the drawn placement and scales the byte budget by ``n_layers / 32``;
+    ``llama70b`` keeps, in layer order, the first resident and the first offloaded layers in the
+    workload's own 1 : 3 proportion.
     """
     rng = np.random.Generator(np.random.PCG64([seed, sum(map(ord, name))]))
     shape8b = dict(n_layers=32, n_q_heads=32, n_kv_heads=8, head_dim=128, page_tokens=16)
@@ -251,8 +256,15 @@ def make_workload(name: str, seed: int = 0, n_req: Optional[int] = None,
         ctx = np.exp(rng.uniform(np.log(1024.0), np.log(65536.0), size=b)).astype(np.int32)
         frac = rng.uniform(0.0, 1.0, size=b)
         pl = _per_request_subsets(rng, b, 32, np.floor(frac * 32))
+        budget = 40 * 10**9
+        if n_layers is not None and n_layers < 32:
+            pl = pl[:, :n_layers]
+            budget = budget * n_layers // 32
+            shape8b = dict(shape8b, n_layers=n_layers)
         w = Workload(name, seed, req_ids=np.arange(b, dtype=np.int64) + 3000, ctx_len=ctx,
-                     placement=pl, hbm_budget_bytes=40 * 10**9, **shape8b)
+                     placement=pl, hbm_budget_bytes=budget, **shape8b)
+        if n_layers is not None and n_layers < 32:
+            w = dataclasses.replace(w, note=f"first {n_layers} of 32 layers, budget scaled to {budget / 1e9:.1f} GB")
     elif name == "llama70b":
         b = 32
         ctx = rng.integers(16384, 131072, size=b, endpoint=True).astype(np.int32)
@@ -260,8 +272,18 @@ def make_workload(name: str, seed: int = 0, n_req: Optional[int] = None,
         pl = np.zeros((b, 80), dtype=np.uint8)
         pl[:, keep] = 1                                  # same 20 of 80 layers for everyone
         w = Workload(name, seed, 80, 64, 8, 128, 16, np.arange(b, dtype=np.int64) + 4000, ctx, pl)
+        if n_layers is not None and n_layers < 80:
+            n_res = max(1, round(n_layers / 4))
+            res = np.nonzero(pl[0] == 1)[0][:n_res]
+            off = np.nonzero(pl[0] == 0)[0][:n_layers - n_res]
+            cols = np.sort(np.concatenate([res, off]))
+            w = dataclasses.replace(w, n_layers=n_layers, placement=pl[:, cols],
+                                    note=f"{n_layers} of 80 layers ({n_res} resident, {n_layers - n_res} streamed), all 32 requests")
     else:
         raise ValueError(f"unknown workload {name!r}")
+    if n_layers is not None and name in ("llama8b_b16", "long_ctx") and n_layers < w.n_layers:
+        w = dataclasses.replace(w, n_layers=n_layers, placement=w.placement[:, :n_layers],
+                                note=f"first {n_layers} of 32 layers")
     if n_req is not None and n_req < w.n_req:
         w = dataclasses.replace(w, req_ids=w.req_ids[:n_req], ctx_len=w.ctx_len[:n_req],
                                 placement=w.placement[:n_req],

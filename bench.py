@@ -48,7 +48,7 @@ def cpu_model():
     return "unknown"
 
 
-def measure_link(torch, host, sizes=(1 << 20, 16 << 20, 256 << 20, 1 << 30), reps=4):
+def measure_link(torch, host, streams, sizes=(1 << 20, 16 << 20, 256 << 20, 1 << 30), reps=4):
     """Pinned host <-> device copy rates (GB/s) from slices of the pinned arena `host`.
     Returns (H2D peak over single transfers of 1 MiB .. 1 GiB = the link roofline, the sweep, and the
     rates of 1 GiB copies in both directions at once on two streams)."""
@@ -69,7 +69,7 @@ def measure_link(torch, host, sizes=(1 << 20, 16 << 20, 256 << 20, 1 << 30), rep
             best = max(best, n / (e0.elapsed_time(e1) * 1e-3) / 1e9)
         sweep[str(n >> 20)] = best
     dev2 = torch.ones(n_max, dtype=torch.uint8, device="cuda:0")
-    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    s1, s2 = streams
 
     def rate(h2d, d2h):
         torch.cuda.synchronize()
@@ -122,7 +122,7 @@ def cpu_baseline(w, n_req_sample=16, n_layers_sample=3):
 class Run:
     """One workload resident on the GPU, its per-step inputs, and the timed loops."""
 
-    def __init__(self, torch, w, total_steps, host, *, slots, chunk_tokens=0, zero_copy=False, host_factor=1.0,
+    def __init__(self, torch, w, total_steps, host, streams, *, slots, chunk_tokens=0, zero_copy=False, host_factor=1.0,
                  allow_resident=True):
         import harness
         from paper_2601_10729_amd import orbit_plan_check
@@ -131,8 +131,9 @@ class Run:
         dev = torch.device("cuda:0")
         _, _, need, host_blocks = orbit_plan_check(w.ctx_len, w.placement, w.page_tokens, 0 if zero_copy else slots, total_steps)
         self.need, self.host_blocks, self.slots = need, host_blocks, slots
-        # the arena is sized so that the all-resident variant of the same workload also fits
-        all_res = int(w.blocks(total_steps).sum()) * w.n_layers
+        # the arena is sized so that the all-resident variant of the same workload also fits (a plan loaded after s
+        # steps reserves ctx + s + window tokens per request)
+        all_res = int(w.blocks(2 * total_steps).sum()) * w.n_layers
         self.fits_resident = allow_resident and all_res * w.page_bytes < 250e9
         pages = (max(need, all_res) if self.fits_resident else need) + 8
         if w.hbm_budget_bytes is not None:
@@ -143,7 +144,7 @@ class Run:
         assert host_pages >= host_blocks, "pinned arena too small for this workload"
         t0 = time.perf_counter()
         self.g = harness.GpuRun(w, prefetch_slots=slots, chunk_tokens=chunk_tokens, budget_pages=pages,
-                                host_pages=host_pages, zero_copy=zero_copy, host_tensor=host,
+                                host_pages=host_pages, zero_copy=zero_copy, host_tensor=host, streams=streams,
                                 max_tokens=int(w.ctx_len.max()) + total_steps + 32, decode_window=total_steps)
         B, L = w.n_req, w.n_layers
         self.q_all = torch.empty((total_steps, L, B, w.n_q_heads, w.head_dim), dtype=torch.bfloat16, device=dev)
@@ -250,7 +251,7 @@ def resident_variant(run, n_steps=3):
             "avg_launch_ms": attn, "avg_combine_ms": float(st["comb_ms"].mean()), "bytes_per_launch": launch_bytes}
 
 
-def other_workload(torch, name, args, host, link_peak):
+def other_workload(torch, name, args, host, streams, link_peak):
     """Compact record of one of the other BASELINE configurations: the largest layer slice (all requests kept)
     whose offloaded blocks fit the pinned arena, 1 warm-up + 3 timed + 3 event-timed steps, all-resident variant."""
     import numpy as np
@@ -263,12 +264,12 @@ def other_workload(torch, name, args, host, link_peak):
         w = make_workload(name, args.seed, steps=steps, n_layers=None if n_layers == full.n_layers else n_layers)
         slots = args.prefetch_slots if w.hbm_budget_bytes is None else 1
         _, _, need, host_blocks = orbit_plan_check(w.ctx_len, w.placement, w.page_tokens, slots, steps)
-        all_res = int(w.blocks(steps).sum()) * w.n_layers
+        all_res = int(w.blocks(2 * steps).sum()) * w.n_layers
         if (host_blocks + 8) * w.page_bytes <= host.numel() and max(need, all_res) * w.page_bytes < 230e9:
             break
         n_layers -= 1
         assert n_layers >= 1
-    run = Run(torch, w, steps, host, slots=slots)
+    run = Run(torch, w, steps, host, streams, slots=slots)
     first_ms, _ = run.timed(1)
     ms, _ = run.timed(3)
     st = run.timed_with_stats(3)
@@ -359,9 +360,12 @@ def main():
     # blocks cached, so separate allocations per workload would add up
     host = torch.empty(host_bytes, dtype=torch.uint8, pin_memory=True)
     host[:2 << 30].fill_(1)
-    link_peak, link_sweep, duplex = measure_link(torch, host)
+    # two streams for the whole process (compute, copy): every further stream in use would have to share one of the
+    # four hardware queues a process gets here with them
+    streams = (torch.cuda.Stream(), torch.cuda.Stream())
+    link_peak, link_sweep, duplex = measure_link(torch, host, streams)
 
-    run = Run(torch, w, total_steps, host, slots=slots, chunk_tokens=args.chunk_tokens, zero_copy=args.zero_copy,
+    run = Run(torch, w, total_steps, host, streams, slots=slots, chunk_tokens=args.chunk_tokens, zero_copy=args.zero_copy,
               host_factor=2.2, allow_resident=w.hbm_budget_bytes is None)
     B, L = w.n_req, w.n_layers
     first_step_ms, _ = run.timed(1)                # the very first step of the process: cold queues, cold page tables
@@ -505,7 +509,7 @@ def main():
         others = []
         for name in ("long_ctx", "heavy_mixed", "llama70b"):
             try:
-                others.append(other_workload(torch, name, args, host, link_peak))
+                others.append(other_workload(torch, name, args, host, streams, link_peak))
             except Exception as e:                               # a record that cannot be taken must not cost the headline
                 others.append({"workload": name, "error": repr(e)[:300]})
                 torch.cuda.empty_cache()

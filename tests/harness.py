@@ -24,7 +24,7 @@ class GpuRun:
 
     def __init__(self, w: Workload, placement=None, *, prefetch_slots=1, decode_window=None,
                  chunk_tokens=0, budget_pages=None, extra_pages=4, max_tokens=None, host_pages=None,
-                 fill=True, layers=None, zero_copy=False, host_tensor=None):
+                 fill=True, layers=None, zero_copy=False, host_tensor=None, streams=None):
         from paper_2601_10729_amd import OrbitContext, orbit_plan_check
         self.w = w
         self.dev = torch.device("cuda:0")
@@ -42,7 +42,7 @@ class GpuRun:
         else:                                   # a slice of a pinned arena the caller keeps for several runs
             assert host_tensor.is_pinned() and host_tensor.numel() >= hpages * w.page_bytes
             self.host = host_tensor[:max(hpages, 1) * w.page_bytes]
-        self.cs, self.xs = torch.cuda.Stream(device=self.dev), torch.cuda.Stream(device=self.dev)
+        self.cs, self.xs = streams if streams else (torch.cuda.Stream(device=self.dev), torch.cuda.Stream(device=self.dev))
         mt = int(w.ctx_len.max()) + self.window + 16 if max_tokens is None else max_tokens
         self.ctx = OrbitContext(n_layers=w.n_layers, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads,
                                 head_dim=w.head_dim, page_tokens=w.page_tokens, max_requests=max(w.n_req, 1),

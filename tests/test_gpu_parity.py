@@ -90,7 +90,7 @@ def test_edge_lengths(lens, chunk):
     g.close()
 
 
-@pytest.mark.parametrize("Hq,Hkv", [(32, 8), (64, 8), (8, 8), (16, 1)])
+@pytest.mark.parametrize("Hq,Hkv", [(32, 8), (64, 8), (8, 8), (16, 1), (128, 128), (256, 128)])
 def test_head_shapes(Hq, Hkv):
     h = _harness()
     w = _custom([40, 777, 2050], L=2, Hq=Hq, Hkv=Hkv, placement=[[1, 0], [0, 1], [1, 0]])
@@ -99,6 +99,18 @@ def test_head_shapes(Hq, Hkv):
     for layer in range(2):
         out, out32 = g.attention(layer)
         _check(out, out32, o.attention(layer))
+    g.close()
+
+
+def test_largest_accepted_request_length():
+    """max_tokens_per_request at its upper limit of 2^24 (a page-table row of 2^20 blocks, 16384 chunk slots per
+    kv head): the tables are sized by it, the work by the tokens actually held."""
+    h = _harness()
+    w = _custom([5000, 1], L=1)
+    g = h.GpuRun(w, max_tokens=1 << 24)
+    o = h.OracleRun(w)
+    out, out32 = g.attention(0)
+    _check(out, out32, o.attention(0))
     g.close()
 
 

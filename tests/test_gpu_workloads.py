@@ -49,16 +49,24 @@ def test_long_ctx_32_appended_steps():
 
 
 def test_llama70b_shape_group_of_eight():
-    """64 query heads over 8 KV heads, contexts in [16K, 128K] (batch truncated to 4)."""
+    """64 query heads over 8 KV heads at the workload's full batch of 32 with contexts in [16K, 128K]: each of the
+    two launches reads 9.7 GB of KV (half of the requests resident, half streamed).  Attention over the stored
+    cache, then one orbit_step (the append folded into the launch) at the same size."""
     import harness as h
-    w = _two_layer_slice("llama70b", n_req=4)
-    g = h.GpuRun(w)
+    w = _two_layer_slice("llama70b", steps=1)
+    assert w.n_req == 32 and w.n_q_heads // w.n_kv_heads == 8
+    g = h.GpuRun(w, prefetch_slots=1)
     outs, outs32 = [], []
     for layer in range(2):
         o, o32 = g.attention(layer)
         outs.append(o)
         outs32.append(o32)
-    _check_groups(h, w, outs, outs32, w.ctx_len, [(0, 0, 0), (1, 1, 6), (0, 3, 2), (1, 2, 4)])
+    order = np.argsort(w.ctx_len)
+    picks = [int(order[0]), int(order[15]), int(order[-1])]
+    _check_groups(h, w, outs, outs32, w.ctx_len, [(0, picks[0], 0), (1, picks[0], 6), (0, picks[1], 2), (1, picks[2], 4)])
+    out, _ = g.step(0)
+    assert torch.isfinite(out.float()).all()
+    _check_groups(h, w, out, None, w.ctx_len.astype(np.int64) + 1, [(0, picks[2], 7), (1, picks[1], 3), (1, 31, 5)], step=0)
     g.close()
 
 
@@ -76,6 +84,25 @@ def test_heavy_mixed_lengths():
     picks = [int(order[0]), int(order[len(order) // 2]), int(order[-1])]
     _check_groups(h, w, outs, outs32, w.ctx_len, [(0, picks[0], 1), (1, picks[0], 6), (0, picks[1], 2),
                                                   (1, picks[2], 4), (0, picks[2], 7)])
+    g.close()
+
+
+def test_heavy_mixed_under_its_byte_budget():
+    """Batch 64 with the workload's own per-request placement and byte budget (an eight-layer slice: 8/32 of the
+    40 GB; the prefetch buffer of Eq. (1) is one layer's worth whatever the number of layers, so a thinner slice
+    has no feasible plan), one staging buffer."""
+    import harness as h
+    w = make_workload("heavy_mixed", 0, n_layers=8, steps=1)
+    assert w.n_req == 64 and w.hbm_budget_bytes == 40 * 10**9 * 8 // 32
+    g = h.GpuRun(w, prefetch_slots=1, budget_pages=w.hbm_budget_bytes // w.page_bytes)
+    info = g.ctx.get_plan_info()
+    assert info["resident_blocks"] + info["staging_blocks"] <= info["budget_blocks"] and info["host_blocks"] > 0
+    out, stats = g.step(0, want_stats=True)
+    assert torch.isfinite(out.float()).all() and stats.link_kv_bytes > 0
+    order = np.argsort(w.ctx_len)
+    lens = w.ctx_len.astype(np.int64) + 1
+    samples = [(l, int(r), int(k)) for l, r, k in ((0, order[0], 1), (7, order[0], 6), (3, order[32], 2), (5, order[-1], 4), (0, order[-1], 7))]
+    _check_groups(h, w, out, None, lens, samples, step=0)
     g.close()
 
 

@@ -340,7 +340,7 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     K, W = args.steps, args.warmup
-    total_steps = 1 + W + 2 * K + 12     # first, warm-up, timed, event-timed, searched-plan and all-resident variants
+    total_steps = 1 + W + 2 * K + 16     # first, warm-up, timed, event-timed, searched-plan, all-resident variants, switch back
     n_req, n_layers = args.n_req, args.n_layers
     host_bytes = int(args.max_host_gib * (1 << 30))
     while True:
@@ -490,9 +490,26 @@ def main():
             planner["searched_plan_observed_ms"] = None
             planner["searched_plan_note"] = str(e)
 
-    resident = None
+    resident, plan_switch = None, None
     if not args.no_resident_variant and args.placement == "workload" and not w.placement.all() and run.fits_resident:
         resident = resident_variant(run)
+        # and back: a switch that only demotes (25 % of the KV leaves HBM).  The copies the new plan does not need at
+        # once run on the library's own stream beside the next steps, in the link direction the prefetches leave free
+        try:
+            run.drain()
+            t0 = time.perf_counter()
+            run.g.ctx.plan_load(w.req_ids, run.lengths().astype("int32"), w.placement)
+            call_ms = (time.perf_counter() - t0) * 1e3
+            info = run.g.ctx.get_plan_info()
+            first_ms, _ = run.timed(1)
+            steady_ms, _ = run.timed(2)
+            plan_switch = {"kind": "all resident -> workload placement (demotions only)", "plan_load_call_ms": call_ms,
+                           "moved_to_host_blocks": info["moved_to_host_blocks"], "deferred_blocks": info["deferred_to_host_blocks"],
+                           "moved_gb": info["moved_to_host_blocks"] * w.page_bytes / 1e9,
+                           "first_step_after_switch_ms": first_ms, "steady_step_ms": steady_ms, "ratio": first_ms / steady_ms,
+                           "note": "first_step_after_switch_ms includes everything the switch left to do"}
+        except Exception as e:
+            plan_switch = {"error": repr(e)[:300]}
     setup_s = run.setup_s
     run.close()
     if args.calibrate_copy:
@@ -536,6 +553,7 @@ def main():
         "planner_model": planner,
         "slo_sim": slo_sim,
         "all_resident_variant": resident,
+        "plan_switch": plan_switch,
         "other_workloads": others,
         "first_step_ms": first_step_ms,
         "host_enqueue_ms_per_step": host_enqueue_ms,

@@ -127,6 +127,8 @@ typedef struct {
   int64_t paused_resident_blocks; /* HBM blocks still held by paused requests (reclaimable)     */
   int32_t paused_requests;
   int32_t reserved_;
+  int64_t deferred_to_host_blocks;/* of the blocks the last plan load moved or evicted to the host: those whose
+                                     copy runs beside the following steps instead of in front of them      */
 } orbit_plan_info;
 
 /* ---- lifetime (ancillary) ------------------------------------------------------------------ */

@@ -24,6 +24,7 @@ using namespace orbit;
 namespace {
 std::string g_create_error;
 constexpr int kDefaultChunkTokens = 1024;
+constexpr int kDeferredCopyWorkgroups = 128;  // half a workgroup per CU: link-bound copies beside the decode steps
 static_assert(kMaxRequests == ORBIT_MAX_REQUESTS, "per-request launch arguments are sized by ORBIT_MAX_REQUESTS");
 }  // namespace
 
@@ -70,7 +71,8 @@ struct orbit_ctx {
   orbit_config cfg{};
   HostState hs;
   bool host_only = false;
-  hipStream_t cs = nullptr, xs = nullptr;  // compute, copy
+  hipStream_t cs = nullptr, xs = nullptr;  // compute, copy (caller-owned)
+  hipStream_t ds = nullptr;                // library-owned: deferred HBM -> host copies of a plan switch
   uint8_t *arena = nullptr;
   uint8_t *host_dev = nullptr;  // device-visible address of the pinned host arena
   int32_t *d_table = nullptr, *d_items = nullptr;
@@ -81,6 +83,10 @@ struct orbit_ctx {
   int32_t *h_tab_pinned = nullptr;                           // pinned snapshot the table upload reads
   hipEvent_t ev_ops = nullptr, ev_tab = nullptr;             // last use of the staging copies
   hipEvent_t ev_plan_c = nullptr, ev_plan_x = nullptr;       // stream ordering of a plan switch
+  hipEvent_t ev_ops_up = nullptr, ev_lazy_all = nullptr;     // op list uploaded; every deferred copy of the last switch done
+  std::vector<hipEvent_t> ev_lazy;                           // per layer: that layer's deferred copies done
+  std::vector<uint8_t> lazy_x, lazy_c;                       // per layer: copy / compute stream has yet to wait for ev_lazy[l]
+  bool lazy_outstanding = false;
   int32_t *h_items_pinned[2] = {nullptr, nullptr};
   hipEvent_t ev_items[2] = {nullptr, nullptr};
   int items_buf = 0;
@@ -138,6 +144,17 @@ LiveBlock *find_live(orbit_ctx *c, int layer) {
   return nullptr;
 }
 
+// A layer's host blocks may still be on their way out of HBM (deferred copies of the last plan switch):
+// whoever is about to read or write them waits, stream-side, once per stream.
+int wait_deferred(orbit_ctx *c, int layer, bool on_copy_stream) {
+  if (c->host_only) return ORBIT_OK;
+  std::vector<uint8_t> &flag = on_copy_stream ? c->lazy_x : c->lazy_c;
+  if (!flag[layer]) return ORBIT_OK;
+  HIPCHECK(c, hipStreamWaitEvent(on_copy_stream ? c->xs : c->cs, c->ev_lazy[layer], 0));
+  flag[layer] = 0;
+  return ORBIT_OK;
+}
+
 // 0 = issued (or nothing to do), 1 = blocked by a prefetched layer not yet attended, <0 = error
 int prefetch_impl(orbit_ctx *c, int layer) {
   HostState &hs = c->hs;
@@ -165,6 +182,7 @@ int prefetch_impl(orbit_ctx *c, int layer) {
     }
     c->host_dirty[layer] = 0;
   }
+  if (int rc = wait_deferred(c, layer, true)) return rc;
   if (c->timing && !c->host_only) HIPCHECK(c, hipEventRecord(c->t_copy0[layer], c->xs));
   int64_t bytes = 0;
   for (const CopyItem &ci : blk.copies) {
@@ -253,6 +271,7 @@ int attention_impl(orbit_ctx *c, int layer, const void *q, void *out, float *out
     if (!c->host_only) HIPCHECK(c, hipStreamWaitEvent(c->cs, c->ev_ready[layer], 0));
     lb->consumed = true;
   }
+  if ((rc = wait_deferred(c, layer, false))) return rc;  // zero-copy reads, and the append's write into a host block
   if (!c->host_only) {
     if (c->timing) HIPCHECK(c, hipEventRecord(c->t_attn0[layer], c->cs));
     AttnParams &ap = c->attn_args;  // the per-request part is rewritten below; the rest is cheap to refill
@@ -333,8 +352,15 @@ int apply_plan_gpu(orbit_ctx *c, const std::vector<std::vector<PageOp>> &phases)
   const Shape &sh = hs.sh;
   HIPCHECK(c, hipEventRecord(c->ev_plan_c, c->cs));
   HIPCHECK(c, hipStreamWaitEvent(c->xs, c->ev_plan_c, 0));
-  size_t total = 0;
-  for (auto &ph : phases) total += ph.size();
+  if (c->lazy_outstanding) {  // pages and host runs the last switch's deferred copies still use may change hands now
+    HIPCHECK(c, hipStreamWaitEvent(c->xs, c->ev_lazy_all, 0));
+    std::fill(c->lazy_x.begin(), c->lazy_x.end(), 0);
+    std::fill(c->lazy_c.begin(), c->lazy_c.end(), 0);  // the compute stream waits for this switch below
+    c->lazy_outstanding = false;
+  }
+  size_t urgent = 0;
+  for (auto &ph : phases) urgent += ph.size();
+  const size_t total = urgent + hs.deferred.size();
   if (total > 0) {
     HIPCHECK(c, hipEventSynchronize(c->ev_ops));
     if (total > c->d_ops_cap) {
@@ -351,19 +377,22 @@ int apply_plan_gpu(orbit_ctx *c, const std::vector<std::vector<PageOp>> &phases)
     const int64_t pb = sh.page_bytes;
     auto hbm = [&](int64_t p) { return (uint64_t)(uintptr_t)(c->arena + p * pb); };
     auto hst = [&](int64_t p) { return (uint64_t)(uintptr_t)(c->host_dev + p * pb); };
+    auto to_blit = [&](const PageOp &op) {
+      BlitOp b{};
+      switch (op.kind) {
+        case OP_HBM_TO_HOST: b.src = hbm(op.src); b.dst = hst(op.dst); break;
+        case OP_HOST_TO_HBM: b.src = hst(op.src); b.dst = hbm(op.dst); break;
+        case OP_HBM_TO_HBM: b.src = hbm(op.src); b.dst = hbm(op.dst); break;
+        default: b.src = hst(op.src); b.dst = hst(op.dst); break;
+      }
+      return b;
+    };
     size_t n = 0;
     for (auto &ph : phases)
-      for (const PageOp &op : ph) {
-        BlitOp b{};
-        switch (op.kind) {
-          case OP_HBM_TO_HOST: b.src = hbm(op.src); b.dst = hst(op.dst); break;
-          case OP_HOST_TO_HBM: b.src = hst(op.src); b.dst = hbm(op.dst); break;
-          case OP_HBM_TO_HBM: b.src = hbm(op.src); b.dst = hbm(op.dst); break;
-          default: b.src = hst(op.src); b.dst = hst(op.dst); break;
-        }
-        c->h_ops_pinned[n++] = b;
-      }
+      for (const PageOp &op : ph) c->h_ops_pinned[n++] = to_blit(op);
+    for (const PageOp &op : hs.deferred) c->h_ops_pinned[n++] = to_blit(op);
     HIPCHECK(c, hipMemcpyAsync(c->d_ops, c->h_ops_pinned, total * sizeof(BlitOp), hipMemcpyHostToDevice, c->xs));
+    HIPCHECK(c, hipEventRecord(c->ev_ops_up, c->xs));
     size_t at = 0;
     for (auto &ph : phases) {
       if (ph.empty()) continue;
@@ -371,6 +400,23 @@ int apply_plan_gpu(orbit_ctx *c, const std::vector<std::vector<PageOp>> &phases)
       at += ph.size();
     }
     HIPCHECK(c, hipEventRecord(c->ev_ops, c->xs));
+    if (!hs.deferred.empty()) {
+      // the deferred copies start behind everything enqueued so far on both caller streams and then run on the
+      // library's own stream, beside the next steps: the link carries them in the direction the prefetches leave free
+      HIPCHECK(c, hipStreamWaitEvent(c->ds, c->ev_ops_up, 0));
+      size_t lo = 0;
+      for (int l = 0; l < sh.L; ++l) {
+        const size_t hi = hs.deferred_end[l];
+        if (hi > lo) {
+          HIPCHECK(c, launch_blit_narrow(c->d_ops + urgent + lo, (int64_t)(hi - lo), pb, kDeferredCopyWorkgroups, c->ds));
+          HIPCHECK(c, hipEventRecord(c->ev_lazy[l], c->ds));
+          c->lazy_x[l] = c->lazy_c[l] = 1;
+        }
+        lo = hi;
+      }
+      HIPCHECK(c, hipEventRecord(c->ev_lazy_all, c->ds));
+      c->lazy_outstanding = true;
+    }
   }
   HIPCHECK(c, hipEventRecord(c->ev_plan_x, c->xs));
   HIPCHECK(c, hipStreamWaitEvent(c->cs, c->ev_plan_x, 0));
@@ -713,6 +759,8 @@ int orbit_create(const orbit_config *cfg, orbit_ctx **out) try {
     return bad("page table (max_requests x n_layers x blocks per request) would exceed 2^34 entries");
   c->hs.init(sh, arena_pages, cfg->host_arena_bytes / sh.page_bytes);
   c->host_dirty.assign(sh.L, 0);
+  c->lazy_x.assign(sh.L, 0);
+  c->lazy_c.assign(sh.L, 0);
   c->hs.live.reserve(sh.L + 1);
   c->items_key_tmp.reserve(sh.max_req);
   c->items_nchunks.reserve(sh.max_req);
@@ -767,11 +815,15 @@ int orbit_create(const orbit_config *cfg, orbit_ctx **out) try {
     CREATE_CHECK(hipEventCreateWithFlags(&p->ev_plan_c, hipEventDisableTiming));
     CREATE_CHECK(hipEventCreateWithFlags(&p->ev_plan_x, hipEventDisableTiming));
     CREATE_CHECK(hipEventCreateWithFlags(&p->ev_tmp, hipEventDisableTiming));
+    CREATE_CHECK(hipEventCreateWithFlags(&p->ev_ops_up, hipEventDisableTiming));
+    CREATE_CHECK(hipEventCreateWithFlags(&p->ev_lazy_all, hipEventDisableTiming));
+    CREATE_CHECK(hipStreamCreateWithFlags(&p->ds, hipStreamNonBlocking));  // default priority, as the caller's streams
     CREATE_CHECK(hipEventCreate(&p->t_step0));
     CREATE_CHECK(hipEventCreate(&p->t_step1));
 #undef CREATE_CHECK
     int rc = 0;
     if ((rc = make_events(p, p->ev_ready, sh.L, false)) || (rc = make_events(p, p->ev_done, sh.L, false)) ||
+        (rc = make_events(p, p->ev_lazy, sh.L, false)) ||
         (rc = make_events(p, p->t_wait0, sh.L, true)) || (rc = make_events(p, p->t_wait1, sh.L, true)) ||
         (rc = make_events(p, p->t_attn0, sh.L, true)) || (rc = make_events(p, p->t_attn1, sh.L, true)) ||
         (rc = make_events(p, p->t_comb1, sh.L, true)) || (rc = make_events(p, p->t_copy0, sh.L, true)) ||
@@ -795,6 +847,10 @@ int orbit_destroy(orbit_ctx *c) {
       (void)hipStreamSynchronize(c->cs);
       (void)hipStreamSynchronize(c->xs);
     }
+    if (c->ds) {
+      (void)hipStreamSynchronize(c->ds);
+      (void)hipStreamDestroy(c->ds);
+    }
     (void)hipFree(c->d_table);
     (void)hipFree(c->d_items);
     (void)hipFree(c->d_pacc);
@@ -802,7 +858,7 @@ int orbit_destroy(orbit_ctx *c) {
     (void)hipFree(c->d_ops);
     if (c->h_ops_pinned) (void)hipHostFree(c->h_ops_pinned);
     if (c->h_tab_pinned) (void)hipHostFree(c->h_tab_pinned);
-    for (hipEvent_t e : {c->ev_ops, c->ev_tab, c->ev_plan_c, c->ev_plan_x})
+    for (hipEvent_t e : {c->ev_ops, c->ev_tab, c->ev_plan_c, c->ev_plan_x, c->ev_ops_up, c->ev_lazy_all})
       if (e) (void)hipEventDestroy(e);
     for (int b = 0; b < 2; ++b) {
       if (c->h_items_pinned[b]) (void)hipHostFree(c->h_items_pinned[b]);
@@ -813,6 +869,7 @@ int orbit_destroy(orbit_ctx *c) {
     if (c->t_step1) (void)hipEventDestroy(c->t_step1);
     drop_events(c->ev_ready);
     drop_events(c->ev_done);
+    drop_events(c->ev_lazy);
     drop_events(c->t_wait0);
     drop_events(c->t_wait1);
     drop_events(c->t_attn0);
@@ -887,6 +944,7 @@ static int fill_or_read(orbit_ctx *c, bool write, int64_t req_id, int32_t layer,
     c->host_dirty[layer] = 1;
   }
   if (c->host_only) return ORBIT_OK;
+  if (lk.tier == 0 && (rc = wait_deferred(c, layer, false))) return rc;
   const Shape &sh = c->hs.sh;
   FillParams fp{};
   fp.arena = c->arena;
@@ -940,6 +998,7 @@ static int append_item(orbit_ctx *c, int r, int layer, AppendItem &item) {
 // An append into a layer whose prefetch is in flight also writes the staging copy: the compute
 // stream must first see that copy landed, or the transfer could overwrite the new token.
 static int wait_for_live_copy(orbit_ctx *c, int layer) {
+  if (int rc = wait_deferred(c, layer, false)) return rc;  // the append may write into a host block
   LiveBlock *lb = find_live(c, layer);
   if (lb && !lb->consumed && !c->host_only) HIPCHECK(c, hipStreamWaitEvent(c->cs, c->ev_ready[layer], 0));
   return ORBIT_OK;

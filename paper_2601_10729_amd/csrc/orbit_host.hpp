@@ -38,6 +38,11 @@ struct PageOp {
   int kind;
   int64_t src, dst;  // page index in the HBM arena or in the host arena, by kind
 };
+// One (request, layer) block that leaves HBM in a plan load: ops [first, first + n) of phase `phase`.
+struct DemoteGroup {
+  int phase, layer;
+  size_t first, n;
+};
 
 struct LayerKV {
   uint8_t tier = 1;            // 1 = HBM, 0 = host
@@ -182,6 +187,15 @@ class HostState {
   std::vector<int32_t> h_table;  // [max_req][L][cap_pages]
   std::vector<int32_t> h_len;    // [max_req][L]
 
+  // Deferred demotions of the last plan load (Section 4: plan changes are applied without stopping the
+  // decode loop).  An HBM -> host copy whose source pages the new plan does not need at once (they lie
+  // below the staging region and no allocation of this plan load took them) is taken out of `phases` and
+  // listed here, grouped by layer: it may run beside the following steps, and only a later use of that
+  // layer's host blocks, or the next plan load, has to wait for it.
+  std::vector<PageOp> deferred;          // sorted by layer
+  std::vector<size_t> deferred_end;      // [L] end offset of layer l's ops in `deferred`
+  std::vector<uint8_t> reuse_mark_;      // [arena_pages] scratch of the classification
+
   std::string err;
 
   void init(const Shape &s, int64_t arena_pages_, int64_t host_pages_) {
@@ -194,6 +208,7 @@ class HostState {
     h_table.assign((size_t)sh.max_req * sh.L * sh.cap_pages, 0);
     h_len.assign((size_t)sh.max_req * sh.L, 0);
     block_of_layer.assign(sh.L, -1);
+    deferred_end.assign(sh.L, 0);
   }
 
   int find(int64_t id) const {
@@ -302,6 +317,8 @@ class HostState {
     }
     std::vector<int64_t> free_hbm;
     std::vector<std::pair<int64_t, int64_t>> free_host;
+    std::vector<DemoteGroup> groups;       // blocks leaving HBM (evictions and demotions)
+    std::vector<int32_t> taken;            // HBM pages this plan load allocated
     auto end_phase = [&]() {
       for (int64_t p : free_hbm) A.release(p);
       for (auto &pr : free_host) H.release(pr.first, pr.second);
@@ -319,10 +336,11 @@ class HostState {
         for (auto &lk : q.layers) if (lk.tier == 1) n += (int64_t)lk.pages.size();
         return n;
       };
-      auto evict = [&](LayerKV &lk) -> int {
+      auto evict = [&](LayerKV &lk, int layer) -> int {
         const int64_t used = (int64_t)lk.pages.size();
         int64_t run = H.alloc(used);
         if (run < 0) return ORBIT_E_HOST_CAPACITY;
+        groups.push_back({(int)phases.size() - 1, layer, phases.back().size(), (size_t)used});
         for (int64_t i = 0; i < used; ++i) phases.back().push_back({OP_HBM_TO_HOST, lk.pages[i], run + i});
         for (int32_t p : lk.pages) free_hbm.push_back(p);
         evicted += used;
@@ -333,11 +351,12 @@ class HostState {
         return ORBIT_OK;
       };
       for (auto &q : np)
-        for (auto &lk : q.layers) {
+        for (int l = 0; l < L; ++l) {
+          LayerKV &lk = q.layers[l];
           if (lk.tier != 1) continue;
           bool inside = false;
           for (int32_t pg : lk.pages) inside |= pg >= ring_first;
-          if (inside && evict(lk)) return fail(ORBIT_E_HOST_CAPACITY, "host arena full (evicting a paused request)");
+          if (inside && evict(lk, l)) return fail(ORBIT_E_HOST_CAPACITY, "host arena full (evicting a paused request)");
         }
       for (;;) {
         int64_t held = 0;
@@ -351,7 +370,7 @@ class HostState {
         if (e.resident + held <= ring_first || victim < 0) break;
         for (int l = L - 1; l >= 0; --l)
           if (np[victim].layers[l].tier == 1 && !np[victim].layers[l].pages.empty()) {
-            if (evict(np[victim].layers[l])) return fail(ORBIT_E_HOST_CAPACITY, "host arena full (evicting a paused request)");
+            if (evict(np[victim].layers[l], l)) return fail(ORBIT_E_HOST_CAPACITY, "host arena full (evicting a paused request)");
             break;
           }
       }
@@ -366,6 +385,7 @@ class HostState {
         int64_t run = H.alloc(rb[r]);
         if (run < 0) return fail(ORBIT_E_HOST_CAPACITY, "host arena full or fragmented (demotion)");
         int64_t used = ceil_div(lk.len, P);
+        groups.push_back({(int)phases.size() - 1, l, phases.back().size(), (size_t)used});
         for (int64_t i = 0; i < used; ++i) phases.back().push_back({OP_HBM_TO_HOST, lk.pages[i], run + i});
         to_host += used;
         for (int32_t p : lk.pages) free_hbm.push_back(p);
@@ -405,6 +425,7 @@ class HostState {
           if (lk.pages[i] < ring_first) continue;
           int32_t np = A.alloc_below(ring_first);
           if (np < 0) return fail(ORBIT_E_CAPACITY, "internal: no page below the staging region");
+          taken.push_back(np);
           if ((int64_t)i < used) {
             phases.back().push_back({OP_HBM_TO_HBM, lk.pages[i], np});
             ++reloc;
@@ -426,6 +447,7 @@ class HostState {
         while ((int64_t)lk.pages.size() < rb[r]) {
           int32_t np = A.alloc_below(ring_first);
           if (np < 0) return fail(ORBIT_E_CAPACITY, "internal: resident allocation failed");
+          taken.push_back(np);
           lk.pages.push_back(np);
         }
         if (promote) {
@@ -479,7 +501,58 @@ class HostState {
       nb.push_back(std::move(sb));
     }
 
+    // Which blocks may leave HBM lazily: every source page below the staging region and not handed out
+    // again by this plan load.  Their copies move from `phases` to `deferred`, grouped by layer.
+    std::vector<PageOp> lazy;
+    std::vector<size_t> lazy_end(L, 0);
+    int64_t n_deferred = 0;
+    if (!groups.empty()) {
+      reuse_mark_.assign((size_t)arena_pages, 0);
+      for (int32_t pg : taken) reuse_mark_[pg] = 1;
+      std::vector<uint8_t> is_lazy(groups.size(), 0);
+      std::vector<size_t> per_layer(L, 0);
+      for (size_t gi = 0; gi < groups.size(); ++gi) {
+        const DemoteGroup &g = groups[gi];
+        bool ok = g.n > 0;
+        for (size_t i = 0; i < g.n && ok; ++i) {
+          const int64_t src = phases[g.phase][g.first + i].src;
+          ok = src < ring_first && !reuse_mark_[src];
+        }
+        is_lazy[gi] = ok;
+        if (ok) per_layer[g.layer] += g.n;
+      }
+      size_t at = 0;
+      std::vector<size_t> cursor(L, 0);
+      for (int l = 0; l < L; ++l) {
+        cursor[l] = at;
+        at += per_layer[l];
+        lazy_end[l] = at;
+      }
+      lazy.resize(at);
+      std::vector<std::vector<uint8_t>> drop(phases.size());
+      for (size_t gi = 0; gi < groups.size(); ++gi) {
+        if (!is_lazy[gi]) continue;
+        const DemoteGroup &g = groups[gi];
+        if (drop[g.phase].empty()) drop[g.phase].assign(phases[g.phase].size(), 0);
+        for (size_t i = 0; i < g.n; ++i) {
+          lazy[cursor[g.layer]++] = phases[g.phase][g.first + i];
+          drop[g.phase][g.first + i] = 1;
+        }
+        n_deferred += (int64_t)g.n;
+      }
+      for (size_t ph = 0; ph < phases.size(); ++ph) {
+        if (drop[ph].empty()) continue;
+        std::vector<PageOp> keep;
+        for (size_t i = 0; i < phases[ph].size(); ++i)
+          if (!drop[ph][i]) keep.push_back(phases[ph][i]);
+        phases[ph] = std::move(keep);
+      }
+    }
+
     // commit
+    deferred = std::move(lazy);
+    deferred_end = std::move(lazy_end);
+    info.deferred_to_host_blocks = n_deferred;
     hbm = std::move(A);
     host = std::move(H);
     reqs = std::move(nw);

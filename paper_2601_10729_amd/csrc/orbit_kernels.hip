@@ -532,6 +532,18 @@ __global__ __launch_bounds__(256) void blit_kernel(const BlitOp *ops, int64_t un
     d[i] = s[i];
 }
 
+// The same copies with a small, fixed number of workgroups that walk the list: for copies that run
+// beside the decode steps.  A link-bound copy needs few bytes in flight, and workgroups parked on the
+// link must not fill the wavefront slots the attention launches need.
+__global__ __launch_bounds__(256) void blit_narrow_kernel(const BlitOp *ops, int64_t n_ops, int64_t units_per_page) {
+  for (int64_t o = blockIdx.x; o < n_ops; o += gridDim.x) {
+    const BlitOp op = ops[o];
+    const u32x4_t *s = reinterpret_cast<const u32x4_t *>(op.src);
+    u32x4_t *d = reinterpret_cast<u32x4_t *>(op.dst);
+    for (int64_t i = threadIdx.x; i < units_per_page; i += blockDim.x) d[i] = s[i];
+  }
+}
+
 // ------------------------------------------------------------------------------------ launches
 
 hipError_t launch_attention(const AttnParams &p, hipStream_t s) {
@@ -577,6 +589,13 @@ hipError_t launch_blit(const BlitOp *ops_dev, int64_t n_ops, int64_t page_bytes,
   const int64_t units = page_bytes / 16;
   const unsigned split = (unsigned)std::max<int64_t>(1, std::min<int64_t>(8, units / 1024));
   hipLaunchKernelGGL(blit_kernel, dim3((unsigned)n_ops, split), dim3(256), 0, s, ops_dev, units);
+  return hipGetLastError();
+}
+
+hipError_t launch_blit_narrow(const BlitOp *ops_dev, int64_t n_ops, int64_t page_bytes, int workgroups, hipStream_t s) {
+  if (n_ops <= 0) return hipSuccess;
+  const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>(workgroups, n_ops));
+  hipLaunchKernelGGL(blit_narrow_kernel, dim3(grid), dim3(256), 0, s, ops_dev, n_ops, page_bytes / 16);
   return hipGetLastError();
 }
 

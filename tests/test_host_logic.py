@@ -506,3 +506,51 @@ def test_batched_append_is_all_or_nothing():
     c.plan_load(ids, np.array([15, 32], dtype=np.int32), np.ones((2, 2), dtype=np.uint8), 64 * PAGE)
     c.kv_append_batch(0, None, None)
     assert c.get_pages(1, 0)["length"] == 16 and c.get_pages(2, 0)["length"] == 33
+
+
+# ------------------------------------------------------------------ deferred demotions of a plan switch
+
+def test_demotions_are_deferred_unless_their_pages_are_needed_at_once():
+    """A block that leaves HBM in a plan switch may be copied out beside the following steps when the new plan
+    needs none of its pages: they lie below the new staging region and no allocation of the switch took them."""
+    L, B = 4, 4
+    n = [160, 160, 160, 160]                                   # 10 blocks per (request, layer), 160 in all
+    ones = np.ones((B, L), dtype=np.uint8)
+    # roomy arena: the all-resident plan occupies pages 0..159, the staging region sits at the top of 4096
+    c = ctx(L=L, hbm_pages=4096)
+    c.plan_load(list(range(B)), n, ones)
+    x = ones.copy()
+    x[:, 1] = 0                                                # demote layer 1 of every request: 40 blocks
+    c.plan_load(list(range(B)), n, x)
+    info = c.get_plan_info()
+    assert info["moved_to_host_blocks"] == 40 and info["deferred_to_host_blocks"] == 40
+    assert info["relocated_blocks"] == 0
+    # back to all-resident, then the same demotion in an arena with no slack: the staging region (40 pages) now
+    # covers resident pages 120..159; what lies there must leave or move at once, the rest may still wait
+    c = ctx(L=L, hbm_pages=160)
+    c.plan_load(list(range(B)), n, ones)
+    before = {(r, l): [int(p) for p in c.get_pages(r, l)["pages"]] for r in range(B) for l in range(L)}
+    c.plan_load(list(range(B)), n, x)
+    info = c.get_plan_info()
+    first = info["staging_first_page"]
+    assert first == 120 and info["moved_to_host_blocks"] == 40
+    in_region = sum(1 for r in range(B) if any(p >= first for p in before[(r, 1)]))
+    moved_in = info["relocated_blocks"]
+    assert moved_in > 0                                        # residents inside the region moved into freed pages
+    assert info["deferred_to_host_blocks"] < 40                # ... so the blocks that freed those pages went at once
+    assert info["deferred_to_host_blocks"] % 10 == 0 and info["deferred_to_host_blocks"] <= 40 - 10 * in_region
+    _layout_invariants(c, list(range(B)), L)
+    # zero-copy mode has no staging region: every demotion whose pages nobody takes is deferred
+    c = ctx(L=L, hbm_pages=160, zero_copy=True)
+    c.plan_load(list(range(B)), n, ones)
+    c.plan_load(list(range(B)), n, x)
+    assert c.get_plan_info()["deferred_to_host_blocks"] == 40
+    # a promotion in the same switch takes the lowest free pages, some of them freed by this switch's own
+    # demotions: the blocks that held those go out at once, the others may wait
+    y = x.copy()
+    y[:, 1] = 1
+    y[:, 2] = 0                                                # layer 1 back in, layer 2 out
+    c.plan_load(list(range(B)), n, y)
+    info = c.get_plan_info()
+    assert info["moved_to_host_blocks"] == 40 and info["moved_to_hbm_blocks"] == 40
+    assert 0 <= info["deferred_to_host_blocks"] < 40 and info["deferred_to_host_blocks"] % 10 == 0

@@ -57,6 +57,11 @@ extern "C" {
 /* flags */
 #define ORBIT_FLAG_HOST_ONLY 1    /* run only the host logic (tables, schedules); no GPU call is
                                      made and the arenas may be NULL.  For CPU-side tests.      */
+#define ORBIT_FLAG_POISON_STAGING 4 /* debugging aid: once a layer's attention has read its staging range, the
+                                     range is overwritten with NaN bit patterns, so that any later read of
+                                     stale staged KV (a missing wait, a range reused too early) shows up as
+                                     NaN outputs instead of plausible numbers.  Costs one fill per streamed
+                                     layer; results are otherwise bit-identical.                           */
 #define ORBIT_FLAG_ZERO_COPY 2    /* no staging region and no host->staging copies: the attention
                                      kernel reads offloaded blocks straight from the mapped pinned
                                      host arena over the link.  Eq. (1) then charges no B_buf,
@@ -215,7 +220,8 @@ ORBIT_API int orbit_kv_append_batch(orbit_ctx *ctx, int32_t layer, const void *k
  * ORBIT_E_STATE if the range is still needed by a prefetched layer not yet attended. */
 ORBIT_API int orbit_kv_prefetch(orbit_ctx *ctx, int32_t layer);
 
-/* ---- a6/a7: attention ---------------------------------------------------------------------- */
+/* ---- a6/a7: attention (Section 2.1 and Fig. 1: decode reads the KV of every earlier token and
+ *      computes one token; grouped-query attention shares a KV head among a group of query heads) ---- */
 
 /* Batched decode attention of one layer over the stored lengths of that layer.
  * q: device [n_req][Hq][D] bf16 in plan order; out: device [n_req][Hq][D] bf16;
@@ -239,7 +245,8 @@ ORBIT_API int orbit_decode_attention(orbit_ctx *ctx, int32_t layer, const void *
  * been created with its GPU current. */
 ORBIT_API int orbit_decode_attention_static(orbit_ctx *ctx, int32_t layer, const void *q, void *out, float *out_f32);
 
-/* ---- a8: one decode step -------------------------------------------------------------------- */
+/* ---- a8: one decode step (Section 3, "Runtime Executor": layers run in order, prefetches of
+ *      offloaded layers run ahead, compute / transfer time and memory in use are recorded) ---------- */
 
 /* For l = 0..L-1 in order: append k_new[l], v_new[l] to every request, then attend q[l] over
  * the grown cache into out[l]; prefetches run ahead on copy_stream.

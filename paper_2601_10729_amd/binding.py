@@ -21,6 +21,7 @@ ORBIT_E_NOT_FOUND, ORBIT_E_STATE, ORBIT_E_HIP, ORBIT_E_NOMEM = -4, -5, -6, -7
 ORBIT_MAX_LAYERS, ORBIT_MAX_REQUESTS = 128, 256
 ORBIT_FLAG_HOST_ONLY = 1
 ORBIT_FLAG_ZERO_COPY = 2
+ORBIT_FLAG_POISON_STAGING = 4
 
 _ERR_NAMES = {-1: "ORBIT_E_INVAL", -2: "ORBIT_E_CAPACITY", -3: "ORBIT_E_HOST_CAPACITY",
               -4: "ORBIT_E_NOT_FOUND", -5: "ORBIT_E_STATE", -6: "ORBIT_E_HIP", -7: "ORBIT_E_NOMEM"}
@@ -375,7 +376,7 @@ class OrbitContext:
     def __init__(self, *, n_layers: int, n_q_heads: int, n_kv_heads: int, head_dim: int = 128,
                  page_tokens: int = 16, max_requests: int, max_tokens_per_request: int,
                  softmax_scale: float = 0.0, prefetch_slots: int = 1, chunk_tokens: int = 0,
-                 decode_window: int = 0, host_only: bool = False, zero_copy: bool = False, hbm_arena=None, hbm_arena_bytes: int = 0,
+                 decode_window: int = 0, host_only: bool = False, zero_copy: bool = False, poison_staging: bool = False, hbm_arena=None, hbm_arena_bytes: int = 0,
                  host_arena=None, host_arena_bytes: int = 0, compute_stream=None, copy_stream=None):
         self._L = lib()
         self._keep = (hbm_arena, host_arena, compute_stream, copy_stream)   # keep caller objects alive
@@ -385,7 +386,8 @@ class OrbitContext:
         cfg.max_requests, cfg.max_tokens_per_request = max_requests, max_tokens_per_request
         cfg.softmax_scale, cfg.prefetch_slots, cfg.chunk_tokens = softmax_scale, prefetch_slots, chunk_tokens
         cfg.decode_window = decode_window
-        cfg.flags = (ORBIT_FLAG_HOST_ONLY if host_only else 0) | (ORBIT_FLAG_ZERO_COPY if zero_copy else 0)
+        cfg.flags = ((ORBIT_FLAG_HOST_ONLY if host_only else 0) | (ORBIT_FLAG_ZERO_COPY if zero_copy else 0) |
+                     (ORBIT_FLAG_POISON_STAGING if poison_staging else 0))
         cfg.hbm_arena = _ptr(hbm_arena)
         cfg.hbm_arena_bytes = hbm_arena_bytes if hbm_arena is None else hbm_arena.numel() * hbm_arena.element_size()
         cfg.host_arena = _ptr(host_arena)

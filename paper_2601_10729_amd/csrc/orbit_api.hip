@@ -330,6 +330,10 @@ int attention_impl(orbit_ctx *c, int layer, const void *q, void *out, float *out
       HIPCHECK(c, launch_combine(cp, c->cs));
     }
     if (c->timing) HIPCHECK(c, hipEventRecord(c->t_comb1[layer], c->cs));
+    if (staged && (c->cfg.flags & ORBIT_FLAG_POISON_STAGING)) {  // nobody may read this range again before it is refilled
+      const StageBlock &blk = hs.blocks[hs.block_of_layer[layer]];
+      HIPCHECK(c, launch_poison(c->arena + (int64_t)blk.p0 * sh.page_bytes, (int64_t)blk.n * sh.page_bytes, c->cs));
+    }
     if (staged) HIPCHECK(c, hipEventRecord(c->ev_done[layer], c->cs));
   }
   return ORBIT_OK;
@@ -723,7 +727,7 @@ int orbit_create(const orbit_config *cfg, orbit_ctx **out) try {
   if (ch < 32 || ch % 32 || ch > 65536) return bad("chunk_tokens must be a multiple of 32");
   const bool host_only = (cfg->flags & ORBIT_FLAG_HOST_ONLY) != 0;
   const bool zero_copy = (cfg->flags & ORBIT_FLAG_ZERO_COPY) != 0;
-  if (cfg->flags & ~(ORBIT_FLAG_HOST_ONLY | ORBIT_FLAG_ZERO_COPY)) return bad("unknown flag");
+  if (cfg->flags & ~(ORBIT_FLAG_HOST_ONLY | ORBIT_FLAG_ZERO_COPY | ORBIT_FLAG_POISON_STAGING)) return bad("unknown flag");
   if (cfg->hbm_arena_bytes < 0 || cfg->host_arena_bytes < 0) return bad("negative arena size");
   if (!host_only) {
     if (!cfg->hbm_arena || ((uintptr_t)cfg->hbm_arena & 255)) return bad("hbm_arena must be a 256-byte aligned device pointer");

@@ -79,6 +79,7 @@ hipError_t launch_append(const AppendParams &p, hipStream_t s);
 hipError_t launch_fill(const FillParams &p, hipStream_t s);
 hipError_t launch_gather(const FillParams &p, hipStream_t s);
 hipError_t launch_blit(const BlitOp *ops_dev, int64_t n_ops, int64_t page_bytes, hipStream_t s);
+hipError_t launch_poison(uint8_t *p, int64_t bytes, hipStream_t s);
 hipError_t launch_blit_narrow(const BlitOp *ops_dev, int64_t n_ops, int64_t page_bytes, int workgroups, hipStream_t s);
 
 }  // namespace orbit

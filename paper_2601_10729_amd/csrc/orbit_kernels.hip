@@ -532,6 +532,12 @@ __global__ __launch_bounds__(256) void blit_kernel(const BlitOp *ops, int64_t un
     d[i] = s[i];
 }
 
+// Debugging aid (ORBIT_FLAG_POISON_STAGING): a consumed staging range is filled with quiet-NaN bf16 patterns.
+__global__ __launch_bounds__(256) void poison_kernel(u32x4_t *p, int64_t n_units) {
+  const u32x4_t nan4 = {0x7FC07FC0u, 0x7FC07FC0u, 0x7FC07FC0u, 0x7FC07FC0u};
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_units; i += (int64_t)gridDim.x * blockDim.x) p[i] = nan4;
+}
+
 // The same copies with a small, fixed number of workgroups that walk the list: for copies that run
 // beside the decode steps.  A link-bound copy needs few bytes in flight, and workgroups parked on the
 // link must not fill the wavefront slots the attention launches need.
@@ -589,6 +595,12 @@ hipError_t launch_blit(const BlitOp *ops_dev, int64_t n_ops, int64_t page_bytes,
   const int64_t units = page_bytes / 16;
   const unsigned split = (unsigned)std::max<int64_t>(1, std::min<int64_t>(8, units / 1024));
   hipLaunchKernelGGL(blit_kernel, dim3((unsigned)n_ops, split), dim3(256), 0, s, ops_dev, units);
+  return hipGetLastError();
+}
+
+hipError_t launch_poison(uint8_t *p, int64_t bytes, hipStream_t s) {
+  if (bytes <= 0) return hipSuccess;
+  hipLaunchKernelGGL(poison_kernel, dim3(1024), dim3(256), 0, s, reinterpret_cast<u32x4_t *>(p), bytes / 16);
   return hipGetLastError();
 }
 

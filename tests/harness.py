@@ -24,7 +24,7 @@ class GpuRun:
 
     def __init__(self, w: Workload, placement=None, *, prefetch_slots=1, decode_window=None,
                  chunk_tokens=0, budget_pages=None, extra_pages=4, max_tokens=None, host_pages=None,
-                 fill=True, layers=None, zero_copy=False, host_tensor=None, streams=None):
+                 fill=True, layers=None, zero_copy=False, host_tensor=None, streams=None, poison_staging=False):
         from paper_2601_10729_amd import OrbitContext, orbit_plan_check
         self.w = w
         self.dev = torch.device("cuda:0")
@@ -47,7 +47,7 @@ class GpuRun:
         self.ctx = OrbitContext(n_layers=w.n_layers, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads,
                                 head_dim=w.head_dim, page_tokens=w.page_tokens, max_requests=max(w.n_req, 1),
                                 max_tokens_per_request=mt, prefetch_slots=prefetch_slots,
-                                chunk_tokens=chunk_tokens, decode_window=self.window, zero_copy=zero_copy,
+                                chunk_tokens=chunk_tokens, decode_window=self.window, zero_copy=zero_copy, poison_staging=poison_staging,
                                 hbm_arena=self.hbm, host_arena=self.host,
                                 compute_stream=self.cs, copy_stream=self.xs)
         self.ctx.plan_load(w.req_ids, w.ctx_len, self.placement, w.hbm_budget_bytes)

@@ -535,3 +535,46 @@ def test_per_layer_calls_equal_orbit_step():
         g.close()
     for a, b in zip(*results):
         assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+def test_poisoned_staging_ranges_change_nothing():
+    """ORBIT_FLAG_POISON_STAGING overwrites a staging range with NaN patterns as soon as its layer has been
+    attended.  If any launch read staged KV after that point (a missing wait, a range reused too early) the
+    outputs would turn NaN; instead they are bit-identical to a run without the flag, through steps (one and
+    three staging ranges), per-layer calls with prefetches running ahead, and a plan switch in between."""
+    h = _harness()
+    w = _custom([17, 300, 1000, 2048, 31, 4000], L=6, Hq=8, Hkv=2, seed=9, steps=8,
+                placement=[[1, 0, 0, 1, 0, 1], [0, 1, 0, 1, 0, 0], [0, 0, 1, 1, 1, 0], [1, 0, 1, 0, 0, 0],
+                           [0, 0, 0, 0, 0, 0], [1, 1, 0, 0, 1, 0]])
+    for slots in (1, 3):
+        runs = []
+        for poison in (False, True):
+            g = h.GpuRun(w, prefetch_slots=slots, chunk_tokens=256, poison_staging=poison,
+                         budget_pages=int(w.blocks(8).sum()) * (w.n_layers + slots + 1),        # room for either placement
+                         host_pages=int(w.blocks(8).sum()) * w.n_layers * 2)                    # and for both during the switch
+            outs = []
+            for s in range(3):
+                out, _ = g.step(s)
+                outs.append(out.cpu())
+            g.ctx.plan_load(w.req_ids, g.len.astype(np.int32), 1 - w.placement)       # every block changes tier
+            for s in range(3, 5):
+                out, _ = g.step(s)
+                outs.append(out.cpu())
+            q = g.q_all(5)
+            k_new, v_new = g.kv_new_all()
+            out = torch.empty_like(out, device=g.dev)
+            torch.cuda.synchronize()
+            g.ctx.kv_prefetch(0)
+            for l in range(w.n_layers):
+                if l + 1 < w.n_layers and slots > 1:                 # a single staging buffer cannot run ahead
+                    g.ctx.kv_prefetch(l + 1)
+                g.ctx.kv_append_batch(l, k_new[l], v_new[l])
+                g.ctx.decode_attention(l, q[l], out[l], None)
+            g.cs.synchronize()
+            g.xs.synchronize()
+            outs.append(out.cpu())
+            runs.append(outs)
+            g.close()
+        for a, b in zip(*runs):
+            assert torch.isfinite(b.float()).all()
+            assert torch.equal(a.view(torch.int16), b.view(torch.int16))

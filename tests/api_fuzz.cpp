@@ -114,6 +114,8 @@ int main(int argc, char **argv) {
         orbit_plan_info info;
         CHECK(orbit_get_plan_info(ctx, &info) == ORBIT_OK);
         CHECK(info.resident_blocks + info.staging_blocks <= info.budget_blocks && info.n_requests == (int)ids.size());
+        CHECK(info.deferred_to_host_blocks >= 0 &&
+              info.deferred_to_host_blocks <= info.moved_to_host_blocks + info.evicted_blocks);
         CHECK(lengths_match());
       }
     } else if (op <= 4) {  // whole step
@@ -177,6 +179,18 @@ int main(int argc, char **argv) {
       int dummy = 0;
       CHECK(orbit_kv_append(ctx, 987654321, 0, &dummy, &dummy) == ORBIT_E_NOT_FOUND);
       CHECK(orbit_request_pause(ctx, 987654321) == ORBIT_E_NOT_FOUND);
+      CHECK(orbit_decode_attention_static(ctx, 0, &dummy, &dummy, nullptr) < 0);   // a host-only context has no scratch
+      {  // SLO replay on a random run: the deposit never adds violations, counts stay within the run
+        double steps[24];
+        const int ns = rnd(0, 24);
+        for (int i = 0; i < ns; ++i) steps[i] = rnd(0, 50) / 10.0;
+        orbit_slo_report rep;
+        CHECK(orbit_slo_replay(steps, ns, 0.1 * rnd(1, 40), rnd(0, 1), &rep) == ORBIT_OK);
+        CHECK(rep.tokens == ns && rep.visible_violations <= rep.backend_violations && rep.backend_violations <= ns);
+        CHECK(rep.max_deposit >= 0 && rep.max_deposit <= ns);
+        CHECK(orbit_slo_replay(steps, ns, 0.0, 0, &rep) == ORBIT_E_INVAL);
+        CHECK(orbit_slo_replay(nullptr, 3, 1.0, 0, &rep) == ORBIT_E_INVAL);
+      }
       CHECK(lengths_match());
     }
   }

@@ -129,6 +129,22 @@ def test_profile_refresh_helpers():
     np.testing.assert_allclose(p, [1.5, 2.0, 3.0])
     with pytest.raises(orbit.OrbitError):
         orbit.orbit_profile_ewma([1.0], [1.0], 1.5)
+    # properties of a moving average that do not restate its update: n refreshes with a constant observation x
+    # leave p0 + (x - p0)(1 - (1 - w)^n); a constant profile is a fixed point; weight 0 keeps, weight 1 replaces;
+    # the refreshed value always lies between the old one and the observation
+    p0, x, w = np.array([10.0, 0.5]), np.array([4.0, 2.5]), 0.2
+    p = p0.copy()
+    for n in range(1, 12):
+        p = orbit.orbit_profile_ewma(p, x, w)
+        np.testing.assert_allclose(p, p0 + (x - p0) * (1 - (1 - w) ** n), rtol=1e-12)
+        assert np.all((p - x) * (p0 - x) >= 0) and np.all(np.abs(p - x) < np.abs(p0 - x))
+    np.testing.assert_array_equal(orbit.orbit_profile_ewma(x, x, 0.37), x)
+    np.testing.assert_array_equal(orbit.orbit_profile_ewma(p0, x, 0.0), p0)
+    np.testing.assert_array_equal(orbit.orbit_profile_ewma(p0, x, 1.0), x)
+    # the trigger is symmetric in the sign of the error and scale-free
+    for pred, obs, frac in ((100.0, 131.0, 0.3), (100.0, 129.0, 0.3), (7.0, 7.0, 0.0), (5.0, 4.0, 0.25)):
+        a = orbit.orbit_profile_mismatch(pred, obs, frac)
+        assert a == orbit.orbit_profile_mismatch(pred, 2 * pred - obs, frac) == orbit.orbit_profile_mismatch(3 * pred, 3 * obs, frac)
 
 
 def test_library_slo_replay_matches_the_oracle():

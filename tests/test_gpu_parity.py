@@ -578,3 +578,67 @@ def test_poisoned_staging_ranges_change_nothing():
         for a, b in zip(*runs):
             assert torch.isfinite(b.float()).all()
             assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_unsynchronised_switches_pauses_and_steps(seed):
+    """Seeded random plans, pauses / resumes and steps (whole steps and per-layer calls) enqueued back to back
+    with no host-side wait anywhere, on contexts large enough that a switch's copies (the deferred ones run on
+    the library's own stream) are still in flight for several of the steps behind it.  Every step's output equals,
+    bit for bit, that of a run which keeps everything resident and waits after every call, and the KV read back
+    at the end equals the generator's values."""
+    h = _harness()
+    from workloads import gen_q_steps, gen_kv
+    rng = np.random.default_rng(700 + seed)
+    B, L, S = 5, 6, 10
+    lens = [int(x) for x in rng.integers(2000, 24000, size=B)]
+    w = _custom(lens, L=L, steps=S, seed=seed)
+    zero_copy = seed % 3 == 2
+    plans = [rng.integers(0, 2, size=(B, L)).astype(np.uint8) for _ in range(5)]
+    script = [(int(rng.integers(0, 4)), int(rng.integers(0, 5)), int(rng.integers(0, B))) for _ in range(S)]
+
+    def run(switching: bool):
+        g = h.GpuRun(w, placement=plans[0] if switching else np.ones((B, L), np.uint8), prefetch_slots=2,
+                     budget_pages=int(w.blocks(2 * S).sum()) * (L + 3), host_pages=int(w.blocks(2 * S).sum()) * L * 2,
+                     decode_window=S, max_tokens=int(w.ctx_len.max()) + 2 * S + 16, zero_copy=zero_copy and switching)
+        dev = g.dev
+        q = torch.stack([torch.stack([gen_q_steps(w.seed, l, int(rid), 0, S, w.n_q_heads, w.head_dim, dev)
+                                      for rid in w.req_ids], dim=1) for l in range(L)], dim=1).contiguous()
+        kv = [[gen_kv(w.seed, l, int(rid), int(w.ctx_len[r]), S, w.n_kv_heads, w.head_dim, dev)
+               for r, rid in enumerate(w.req_ids)] for l in range(L)]
+        k_new = torch.stack([torch.stack([kv[l][r][0] for r in range(B)], dim=1) for l in range(L)], dim=1).contiguous()
+        v_new = torch.stack([torch.stack([kv[l][r][1] for r in range(B)], dim=1) for l in range(L)], dim=1).contiguous()
+        outs = torch.zeros((S, L, B, w.n_q_heads, w.head_dim), dtype=torch.bfloat16, device=dev)
+        torch.cuda.synchronize()
+        for s, (kind, pi, victim) in enumerate(script):
+            if switching and kind == 1:
+                g.ctx.plan_load(w.req_ids, w.ctx_len + s, plans[pi])
+            elif switching and kind == 2:                               # out of the batch and straight back in, elsewhere
+                g.ctx.request_pause(int(w.req_ids[victim]))
+                g.ctx.plan_load(w.req_ids, w.ctx_len + s, plans[pi])
+            if kind == 3:                                                # the per-layer path
+                for l in range(L):
+                    g.ctx.kv_append_batch(l, k_new[s, l], v_new[s, l])
+                    g.ctx.decode_attention(l, q[s, l], outs[s, l], None)
+            else:
+                g.ctx.step(q[s], k_new[s], v_new[s], outs[s])
+            if not switching:
+                g.cs.synchronize()
+                g.xs.synchronize()
+        g.cs.synchronize()
+        g.xs.synchronize()
+        g.len = w.ctx_len.astype(np.int64) + S
+        res = outs.cpu()
+        if switching:
+            for r in range(B):
+                for l in (0, L - 1):
+                    n = int(g.len[r])
+                    k, v = g.read_kv(r, l, 0, n)
+                    kw, vw = gen_kv(w.seed, l, int(w.req_ids[r]), 0, n, w.n_kv_heads, w.head_dim, dev)
+                    assert torch.equal(k, kw) and torch.equal(v, vw), (r, l)
+        g.close()
+        return res
+
+    a, b = run(True), run(False)
+    assert torch.isfinite(a.float()).all()
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))

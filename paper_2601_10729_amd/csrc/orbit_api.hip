@@ -995,7 +995,6 @@ static int append_item(orbit_ctx *c, int r, int layer, AppendItem &item) {
     item.host_page = c->host_only ? 1 : (uint64_t)(uintptr_t)(c->host_dev + (lk.host_page0 + pi) * hs.sh.page_bytes);
   }
   lk.len += 1;
-  hs.h_len[(size_t)r * hs.sh.L + layer] = lk.len;
   return ORBIT_OK;
 }
 
@@ -1030,11 +1029,8 @@ static int append_layer(orbit_ctx *c, int l, const uint16_t *k, const uint16_t *
     ap.k = k + (int64_t)r0 * sh.Hkv * sh.D;  // non-NULL here: host-only contexts left the loop above
     ap.v = v + (int64_t)r0 * sh.Hkv * sh.D;
     ap.page_bytes = sh.page_bytes;
-    ap.L = sh.L;
-    ap.layer = l;
     ap.Hkv = sh.Hkv;
     ap.n = n;
-    ap.r0 = r0;
     HIPCHECK(c, launch_append(ap, c->cs));
   }
   return ORBIT_OK;
@@ -1069,11 +1065,8 @@ int orbit_kv_append(orbit_ctx *c, int64_t req_id, int32_t layer, const void *k, 
   ap.k = (const uint16_t *)k;
   ap.v = (const uint16_t *)v;
   ap.page_bytes = sh.page_bytes;
-  ap.L = sh.L;
-  ap.layer = layer;
   ap.Hkv = sh.Hkv;
   ap.n = 1;
-  ap.r0 = r;
   HIPCHECK(c, launch_append(ap, c->cs));
   return ORBIT_OK;
 } catch (const std::exception &e) {  // nothing may unwind through the C ABI
@@ -1167,7 +1160,6 @@ int orbit_step(orbit_ctx *c, const void *q, const void *k_new, const void *v_new
     for (int r = 0; r < nreq; ++r) {
       LayerKV &lk = hs.reqs[r].layers[l];
       lk.len += 1;
-      hs.h_len[(size_t)r * sh.L + l] = lk.len;
       if (lk.tier == 1) hbm_bytes += (int64_t)lk.len * tok_bytes;
       else if (sh.zero_copy) c->copy_bytes[l] += ceil_div(lk.len, sh.P) * sh.page_bytes;  // read over the link by the kernel
     }

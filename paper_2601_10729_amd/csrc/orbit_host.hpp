@@ -183,9 +183,8 @@ class HostState {
   std::vector<int> block_of_layer;  // index into blocks or -1
   std::vector<LiveBlock> live;      // staging ranges currently holding (or receiving) a layer
 
-  // host mirrors of the device tables
+  // host mirror of the device page table (lengths live in the requests and travel with every launch)
   std::vector<int32_t> h_table;  // [max_req][L][cap_pages]
-  std::vector<int32_t> h_len;    // [max_req][L]
 
   // Deferred demotions of the last plan load (Section 4: plan changes are applied without stopping the
   // decode loop).  An HBM -> host copy whose source pages the new plan does not need at once (they lie
@@ -206,7 +205,6 @@ class HostState {
     hbm.cursor = 0;
     host.reset(host_pages);
     h_table.assign((size_t)sh.max_req * sh.L * sh.cap_pages, 0);
-    h_len.assign((size_t)sh.max_req * sh.L, 0);
     block_of_layer.assign(sh.L, -1);
     deferred_end.assign(sh.L, 0);
   }
@@ -629,7 +627,6 @@ class HostState {
   }
 
   void rebuild_tables() {
-    std::fill(h_len.begin(), h_len.end(), 0);
     for (size_t r = 0; r < reqs.size(); ++r)
       for (int l = 0; l < sh.L; ++l) {
         const LayerKV &lk = reqs[r].layers[l];
@@ -641,7 +638,6 @@ class HostState {
           for (int i = 0; i < reqs[r].reserved; ++i) row[i] = ~(int32_t)(lk.host_page0 + i);
         else
           for (int i = 0; i < reqs[r].reserved; ++i) row[i] = lk.stage_page0 + i;
-        h_len[r * sh.L + l] = lk.len;
       }
   }
 

@@ -55,7 +55,7 @@ struct AppendParams {
   const uint16_t *k;        // device [.. n][Hkv][128] bf16, row i belongs to request r0 + i
   const uint16_t *v;
   int64_t page_bytes;
-  int32_t L, layer, Hkv, n, r0;
+  int32_t Hkv, n;
   AppendItem items[kAppendBatch];
 };
 

@@ -138,8 +138,9 @@ typedef struct {
 
 /* ---- lifetime (ancillary) ------------------------------------------------------------------ */
 
-/* Creates a context.  Allocates the library's own small device tables (page table, lengths,
- * work list, split partials).  Fails with ORBIT_E_INVAL on an unsupported shape. */
+/* Creates a context, with the GPU it is to run on current.  Allocates the library's own device tables (page
+ * table, work list, split partials), one stream of default priority for the deferred copies of a plan switch,
+ * and reserves the host-side storage its calls need.  Fails with ORBIT_E_INVAL on an unsupported shape. */
 ORBIT_API int orbit_create(const orbit_config *cfg, orbit_ctx **out);
 /* Synchronises both streams, frees the library's own memory.  Caller arenas are untouched. */
 ORBIT_API int orbit_destroy(orbit_ctx *ctx);
@@ -167,8 +168,11 @@ ORBIT_API int orbit_plan_check(int32_t n_req, int32_t n_layers, int32_t page_tok
  * NOTHING changes.  On success it moves only the blocks whose tier changed, plus resident
  * blocks that sit where the new contiguous staging region goes, and rebuilds the tables.
  * The host does not wait for the GPU (no stream or device synchronisation, as Section 4 asks):
- * the migrations are enqueued on copy_stream behind everything already enqueued on
- * compute_stream, and compute_stream waits for them before any later call's work.
+ * the migrations the new plan needs at once are enqueued on copy_stream behind everything already
+ * enqueued on compute_stream, and compute_stream waits for them before any later call's work.
+ * Blocks that leave HBM without their pages being needed at once (orbit_plan_info.deferred_to_host_blocks)
+ * are copied out on a stream of the library's own, beside the following steps; whatever touches such a
+ * layer's host blocks next, and the next plan load, waits for those copies stream-side.
  * ORBIT_E_STATE if a prefetched layer has not been attended yet. */
 ORBIT_API int orbit_plan_load(orbit_ctx *ctx, int32_t n_req, const int64_t *req_ids, const int32_t *ctx_len,
                     const uint8_t *placement_bitmap, int64_t hbm_budget_bytes);

@@ -358,7 +358,16 @@ def main():
 
     # one pinned arena for the whole run: the pinned pool of this machine is small, and torch keeps freed pinned
     # blocks cached, so separate allocations per workload would add up
-    host = torch.empty(host_bytes, dtype=torch.uint8, pin_memory=True)
+    host = None
+    while host is None:
+        try:
+            host = torch.empty(host_bytes, dtype=torch.uint8, pin_memory=True)
+        except RuntimeError:                 # this machine pins less than asked for: take what it gives, and say so
+            torch.cuda.empty_cache()
+            host_bytes = host_bytes * 3 // 4
+            if (host_blocks + 8) * w.page_bytes > host_bytes:
+                raise
+    pinned_gib = host_bytes / (1 << 30)
     host[:2 << 30].fill_(1)
     # two streams for the whole process (compute, copy): every further stream in use would have to share one of the
     # four hardware queues a process gets here with them
@@ -561,7 +570,7 @@ def main():
         "host_enqueue_ms_per_step": host_enqueue_ms,
         "ms_per_step_with_events": ms_per_step_events,
         "step_ms_median": float(np.median(st["step_ms"])), "step_ms_min": float(np.min(st["step_ms"])),
-        "setup_seconds": setup_s, "pinned_arena_gib": args.max_host_gib,
+        "setup_seconds": setup_s, "pinned_arena_gib": pinned_gib,
     }
     print(json.dumps(line))
 

@@ -644,7 +644,7 @@ class HostState {
   // ------------------------------------------------------------------------------ work list
   // Items {request index, kv head, chunk, partial slot}: chunks are a function of the stored
   // length and the fixed chunk size only, so results do not depend on the placement.  Order:
-  // full chunks of all requests first, ragged last chunks at the end; the 8 groups x Hkv heads
+  // full chunks of all requests first, ragged last chunks at the end, longest first; the 8 groups x Hkv heads
   // of a 64-item span are interleaved so that the heads of one page range run on one XCD
   // (workgroup i runs on XCD i mod 8).  Partial slots are numbered (request, chunk, head) with
   // `work_max_chunks` = the largest chunk count of any request in this list, so the split-K scratch
@@ -666,6 +666,12 @@ class HostState {
         (is_full ? work_full_ : work_ragged_).push_back({(int)r, c});
       }
     }
+    // longest ragged chunk first: the last round of a launch is then filled with the shortest items
+    std::stable_sort(work_ragged_.begin(), work_ragged_.end(), [&](const std::pair<int, int> &a, const std::pair<int, int> &b) {
+      const int64_t ta = reqs[a.first].layers[layer].len - (int64_t)a.second * sh.chunk_tokens;
+      const int64_t tb = reqs[b.first].layers[layer].len - (int64_t)b.second * sh.chunk_tokens;
+      return ta > tb;
+    });
     work_full_.insert(work_full_.end(), work_ragged_.begin(), work_ragged_.end());
     work_max_chunks = maxc;
     const int H = sh.Hkv;

@@ -556,7 +556,7 @@ def main():
                    "placement": args.placement, "n_req": B, "n_layers": L, "tokens_per_layer": float(mid_len.sum()),
                    "kv_bytes_per_step": step_bytes, "resident_fraction": resident_frac,
                    "prefetch_slots": 0 if args.zero_copy else slots, "zero_copy": bool(args.zero_copy), "note": w.note,
-                   "hbm_budget_bytes": w.hbm_budget_bytes, "chunk_tokens": args.chunk_tokens or 1024},
+                   "hbm_budget_bytes": w.hbm_budget_bytes, "chunk_tokens": args.chunk_tokens or "per launch (4096 at this size)"},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "parity": parity,

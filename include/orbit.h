@@ -83,7 +83,8 @@ typedef struct {
   float   softmax_scale;          /* <= 0 selects 1/sqrt(head_dim)                              */
   int32_t prefetch_slots;         /* k >= 1: staging region = k * B_buf blocks; 1 = the paper's
                                      single prefetch buffer of Eq. (1)                          */
-  int32_t chunk_tokens;           /* split-K chunk, multiple of 32; 0 selects the default       */
+  int32_t chunk_tokens;           /* tokens per attention work segment (multiple of 32); 0 lets
+                                     every launch choose (see orbit_get_work_items)             */
   int32_t decode_window;          /* Delta >= 0: tokens each request may grow under one plan
                                      (the decode window of Section 3.3.1); Eq. (1) is checked
                                      with b_r = ceil((ctx_len + Delta)/16)                      */
@@ -237,12 +238,13 @@ ORBIT_API int orbit_decode_attention(orbit_ctx *ctx, int32_t layer, const void *
 /* For callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses
  * that forbid hipMalloc.  Same arguments, same work, same results (bit for bit) and same errors as
  * orbit_decode_attention, but the call allocates nothing (no device memory, no pinned memory; the
- * host-side storage it uses was reserved by orbit_create): the split-K partial results and the chunk-arrival counters live in a static device array of
+ * host-side storage it uses was reserved by orbit_create): the split-K partial results live in a static device array of
  * ORBIT_STATIC_SCRATCH_BYTES that is part of the library's image on every GPU the library runs on
  * (held until the process ends) instead of the context's own buffers.
- * ORBIT_E_CAPACITY, with nothing enqueued, if the batch needs more: n_req * C * Hkv partial slots of
- * (Hq/Hkv * 128 + 32) * 4 bytes, C = the largest number of chunk_tokens-sized chunks of any request
- * (16 requests of up to 33K tokens at the 8B head shape fit; the 70B workload at batch 32 does not).
+ * ORBIT_E_CAPACITY, with nothing enqueued, if the batch needs more: S * Hkv partial slots of
+ * (Hq/Hkv * 128 + 32) * 4 bytes, S = the number of work segments (see orbit_get_work_items; with
+ * chunk_tokens 0 the 70B workload at batch 32 needs 620 segments = 21 MB and does not fit, the 8B
+ * workloads of up to 64 requests do).
  * The array is shared by every context and every call on that GPU and keeps the last call's
  * contents (nothing in it needs clearing: every partial is written before it is read).  Calls that overlap on one
  * GPU (two streams, two contexts, two threads) race on it: serialise them.  The context must have
@@ -395,8 +397,13 @@ ORBIT_API int orbit_profile_ewma(double *profile, const double *observed, int64_
 ORBIT_API int64_t orbit_get_pages(orbit_ctx *ctx, int64_t req_id, int32_t layer, int32_t *tier,
                         int64_t *host_first_page, int32_t *length, int32_t *pages_out, int64_t cap);
 
-/* Split-K work items of `layer` for the current lengths: rows {request index, kv head, chunk
- * index, partial slot}.  Returns the item count. */
+/* Attention work segments of `layer` for the current lengths: rows {request index, first token,
+ * tokens, position in the launch order}, by request and first token.  Every request is cut into chunks
+ * of C tokens, C = chunk_tokens if the context fixed it, else the largest power of two in [128, 4096]
+ * that still gives every compute unit a workgroup (requests are not cut when none is longer than 512
+ * tokens, or when none is longer than 4096 and whole requests already fill half of the units); longest
+ * segments are launched first.  A request cut into
+ * several segments is merged by the combine launch in token order.  Returns the segment count. */
 ORBIT_API int64_t orbit_get_work_items(orbit_ctx *ctx, int32_t layer, int32_t *items_out, int64_t cap);
 
 /* Copy schedule of the installed plan: rows {layer, request index, staging first page,

@@ -23,7 +23,7 @@ using namespace orbit;
 
 namespace {
 std::string g_create_error;
-constexpr int kDefaultChunkTokens = 1024;
+constexpr int kItemBufs = 2;  // pinned staging buffers of the work list
 constexpr int kDeferredCopyWorkgroups = 128;  // half a workgroup per CU: link-bound copies beside the decode steps
 static_assert(kMaxRequests == ORBIT_MAX_REQUESTS, "per-request launch arguments are sized by ORBIT_MAX_REQUESTS");
 }  // namespace
@@ -87,10 +87,11 @@ struct orbit_ctx {
   std::vector<hipEvent_t> ev_lazy;                           // per layer: that layer's deferred copies done
   std::vector<uint8_t> lazy_x, lazy_c;                       // per layer: copy / compute stream has yet to wait for ev_lazy[l]
   bool lazy_outstanding = false;
-  int32_t *h_items_pinned[2] = {nullptr, nullptr};
-  hipEvent_t ev_items[2] = {nullptr, nullptr};
+  int32_t *h_items_pinned[kItemBufs] = {};
+  hipEvent_t ev_items[kItemBufs] = {};
   int items_buf = 0;
-  int64_t slots = 0;
+  int64_t seg_cap = 0;                // most segments a work list can have
+  int64_t slots = 0;                  // seg_cap * Hkv split-K partial slots
   std::vector<hipEvent_t> ev_ready, ev_done;
   hipEvent_t ev_tmp = nullptr;
   std::vector<hipEvent_t> t_wait0, t_wait1, t_attn0, t_attn1, t_comb1, t_copy0, t_copy1;
@@ -98,10 +99,11 @@ struct orbit_ctx {
   std::vector<uint8_t> host_dirty;    // per layer: host pages written since the last ordering point
   std::vector<uint8_t> copy_timed;    // per layer: t_copy0/1 recorded in this step
   std::vector<int64_t> copy_bytes;    // per layer, last prefetch
-  std::vector<int32_t> items_nchunks; // cache key of the uploaded work list
+  std::vector<int32_t> items_key;     // chunk counts and chunk size the uploaded work list was built for
   std::vector<int32_t> items_key_tmp, items_tmp;  // scratch of ensure_work_items, kept for their storage
   uint8_t *static_scratch = nullptr;  // this device's copy of the library's static split-K scratch
-  int64_t n_items = 0;
+  int64_t n_segs = 0;
+  int32_t seg_off = 0;                // where the segments start in the uploaded buffer (after the span table)
   bool items_valid = false;
   float scale_log2 = 0.f;
   AttnParams attn_args{};               // launch arguments, kept here because of their size
@@ -208,30 +210,35 @@ int prefetch_impl(orbit_ctx *c, int layer) {
   return 0;
 }
 
+// The work list is a function of the chunk size chosen for the current lengths and of each request's chunk
+// count; it is rebuilt (and uploaded again, stream-ordered on the compute stream) when those change.
 int ensure_work_items(orbit_ctx *c, int layer) {
   HostState &hs = c->hs;
   const int nreq = (int)hs.reqs.size();
   std::vector<int32_t> &key = c->items_key_tmp;
-  key.resize(nreq);
-  for (int r = 0; r < nreq; ++r) {
-    const int32_t n = hs.reqs[r].layers[layer].len;
-    if (n < 1) return set_err(c, ORBIT_E_INVAL, "a request holds no token in this layer");
-    key[r] = (int32_t)ceil_div(n, hs.sh.chunk_tokens);
-  }
-  if (c->items_valid && key == c->items_nchunks) return ORBIT_OK;
-  std::vector<int32_t> &items = c->items_tmp;
-  int rc = hs.build_work_items(layer, items);
+  key.resize(nreq + 1);
+  for (int r = 0; r < nreq; ++r)
+    if (hs.reqs[r].layers[layer].len < 1) return set_err(c, ORBIT_E_INVAL, "a request holds no token in this layer");
+  const int chunk = hs.choose_chunk(layer);
+  key[nreq] = chunk;
+  for (int r = 0; r < nreq; ++r) key[r] = (int32_t)ceil_div(hs.reqs[r].layers[layer].len, chunk);
+  if (c->items_valid && key == c->items_key) return ORBIT_OK;
+  std::vector<int32_t> &segs = c->items_tmp;
+  int rc = hs.build_work_items(layer, segs);
   if (rc) return set_err(c, rc, hs.err);
-  c->n_items = (int64_t)items.size() / 4;
+  c->n_segs = (int64_t)segs.size() / 4;
+  c->seg_off = (int32_t)hs.work_order.size();
   if (!c->host_only) {
-    const int b = c->items_buf ^= 1;
+    const int b = c->items_buf = (c->items_buf + 1) % kItemBufs;
     HIPCHECK(c, hipEventSynchronize(c->ev_items[b]));  // last upload from this buffer is long done
-    std::memcpy(c->h_items_pinned[b], items.data(), items.size() * sizeof(int32_t));
-    HIPCHECK(c, hipMemcpyAsync(c->d_items, c->h_items_pinned[b], items.size() * sizeof(int32_t),
+    int32_t *dst = c->h_items_pinned[b];
+    std::memcpy(dst, hs.work_order.data(), hs.work_order.size() * sizeof(int32_t));
+    std::memcpy(dst + c->seg_off, segs.data(), segs.size() * sizeof(int32_t));
+    HIPCHECK(c, hipMemcpyAsync(c->d_items, dst, ((size_t)c->seg_off + segs.size()) * sizeof(int32_t),
                                hipMemcpyHostToDevice, c->cs));
     HIPCHECK(c, hipEventRecord(c->ev_items[b], c->cs));
   }
-  c->items_nchunks = key;  // same capacity after the first call: no allocation
+  c->items_key = key;  // same capacity after the first call: no allocation
   c->items_valid = true;
   return ORBIT_OK;
 }
@@ -249,7 +256,7 @@ int attention_impl(orbit_ctx *c, int layer, const void *q, void *out, float *out
   int rc = ensure_work_items(c, layer);
   if (rc) return rc;
   auto up256 = [](size_t n) { return (n + 255) & ~(size_t)255; };
-  const size_t part_slots = (size_t)nreq * hs.work_max_chunks * sh.Hkv;
+  const size_t part_slots = (size_t)c->n_segs * sh.Hkv;
   const size_t pacc_bytes = up256(part_slots * sh.G * 128 * sizeof(float)), pml_bytes = up256(part_slots * 32 * sizeof(float));
   if (use_static) {
     if (c->host_only || !c->static_scratch) return set_err(c, ORBIT_E_STATE, "no static scratch on this context");
@@ -278,7 +285,7 @@ int attention_impl(orbit_ctx *c, int layer, const void *q, void *out, float *out
     ap.arena = c->arena;
     ap.host = c->host_dev;
     ap.table = c->d_table;
-    ap.items = c->d_items;
+    ap.work = c->d_items;
     ap.q = (const uint16_t *)q;
     if (use_static) {
       // every call on this GPU shares the array and inherits whatever the last one left; nothing in it has
@@ -300,21 +307,21 @@ int attention_impl(orbit_ctx *c, int layer, const void *q, void *out, float *out
     ap.Hq = sh.Hq;
     ap.Hkv = sh.Hkv;
     ap.G = sh.G;
-    ap.chunk_tokens = sh.chunk_tokens;
-    ap.max_chunks = hs.work_max_chunks;
-    ap.n_items = (int32_t)c->n_items;
+    ap.n_workers = hs.work_workers;
+    ap.seg_off = c->seg_off;
     ap.scale_log2 = c->scale_log2;
     for (int r = 0; r < nreq; ++r) {
       const LayerKV &lk = hs.reqs[r].layers[layer];
       ap.req[r].n_tok = lk.len;
       // a staged block has a second home: the host run that the next step's prefetch reads
       ap.req[r].host_page0 = (k_new && lk.tier == 0 && !sh.zero_copy) ? (int32_t)lk.host_page0 : -1;
+      ap.req[r].n_parts = hs.work_n_parts[r];
     }
     HIPCHECK(c, launch_attention(ap, c->cs));
     if (c->timing) HIPCHECK(c, hipEventRecord(c->t_attn1[layer], c->cs));
     bool multi = false;
-    for (int r = 0; r < nreq; ++r) multi |= ap.req[r].n_tok > sh.chunk_tokens;
-    if (multi) {  // requests of a single chunk were finished by the attention launch
+    for (int r = 0; r < nreq; ++r) multi |= hs.work_n_parts[r] > 1;
+    if (multi) {  // requests of a single segment were finished by the attention launch
       CombineParams &cp = c->comb_args;
       cp.pacc = ap.pacc;
       cp.pml = ap.pml;
@@ -323,10 +330,11 @@ int attention_impl(orbit_ctx *c, int layer, const void *q, void *out, float *out
       cp.Hq = sh.Hq;
       cp.Hkv = sh.Hkv;
       cp.G = sh.G;
-      cp.chunk_tokens = sh.chunk_tokens;
-      cp.max_chunks = hs.work_max_chunks;
       cp.n_req = nreq;
-      for (int r = 0; r < nreq; ++r) cp.n_tok[r] = ap.req[r].n_tok;
+      for (int r = 0; r < nreq; ++r) {
+        cp.seg_base[r] = hs.work_seg_base[r];
+        cp.n_parts[r] = hs.work_n_parts[r];
+      }
       HIPCHECK(c, launch_combine(cp, c->cs));
     }
     if (c->timing) HIPCHECK(c, hipEventRecord(c->t_comb1[layer], c->cs));
@@ -723,8 +731,8 @@ int orbit_create(const orbit_config *cfg, orbit_ctx **out) try {
   if (cfg->max_tokens_per_request < 1 || cfg->max_tokens_per_request > (1 << 24)) return bad("max_tokens_per_request out of range");
   if (cfg->prefetch_slots < 1 || cfg->prefetch_slots > 16) return bad("prefetch_slots out of range");
   if (cfg->decode_window < 0) return bad("negative decode_window");
-  const int ch = cfg->chunk_tokens == 0 ? kDefaultChunkTokens : cfg->chunk_tokens;
-  if (ch < 32 || ch % 32 || ch > 65536) return bad("chunk_tokens must be a multiple of 32");
+  const int ch = cfg->chunk_tokens;
+  if (ch != 0 && (ch < 32 || ch % 32 || ch > 65536)) return bad("chunk_tokens must be 0 or a multiple of 32");
   const bool host_only = (cfg->flags & ORBIT_FLAG_HOST_ONLY) != 0;
   const bool zero_copy = (cfg->flags & ORBIT_FLAG_ZERO_COPY) != 0;
   if (cfg->flags & ~(ORBIT_FLAG_HOST_ONLY | ORBIT_FLAG_ZERO_COPY | ORBIT_FLAG_POISON_STAGING)) return bad("unknown flag");
@@ -750,15 +758,14 @@ int orbit_create(const orbit_config *cfg, orbit_ctx **out) try {
   sh.page_bytes = (int64_t)2 * sh.Hkv * sh.P * sh.D * 2;
   sh.cap_pages = (int)((ceil_div(sh.max_tokens, sh.P) + 1) & ~(int64_t)1);
   sh.chunk_tokens = ch;
-  sh.max_chunks = (int)ceil_div(sh.max_tokens, ch);
   sh.window = cfg->decode_window;
   sh.slots = cfg->prefetch_slots;
   sh.zero_copy = zero_copy;
   const int64_t arena_pages = cfg->hbm_arena_bytes / sh.page_bytes;
   if (arena_pages > 0x7FFFFFF0) return bad("hbm arena has too many pages");
   if (cfg->host_arena_bytes / sh.page_bytes > 0x7FFFFFF0) return bad("host arena has too many pages");
-  if ((int64_t)sh.max_req * sh.max_chunks * sh.Hkv > 0x7FFFFFF0)
-    return bad("max_requests x max_tokens_per_request / chunk_tokens x n_kv_heads exceeds 2^31 work items");
+  if (ch && (int64_t)sh.max_req * ceil_div(sh.max_tokens, ch) * sh.Hkv > 0x7FFFFFF0 / 2)
+    return bad("max_requests x max_tokens_per_request / chunk_tokens x n_kv_heads exceeds 2^30 work items");
   if ((int64_t)sh.max_req * sh.L * sh.cap_pages > ((int64_t)1 << 34))
     return bad("page table (max_requests x n_layers x blocks per request) would exceed 2^34 entries");
   c->hs.init(sh, arena_pages, cfg->host_arena_bytes / sh.page_bytes);
@@ -766,17 +773,27 @@ int orbit_create(const orbit_config *cfg, orbit_ctx **out) try {
   c->lazy_x.assign(sh.L, 0);
   c->lazy_c.assign(sh.L, 0);
   c->hs.live.reserve(sh.L + 1);
-  c->items_key_tmp.reserve(sh.max_req);
-  c->items_nchunks.reserve(sh.max_req);
+  c->items_key_tmp.reserve(sh.max_req + 1);
+  c->items_key.reserve(sh.max_req + 1);
   c->copy_timed.assign(sh.L, 0);
   c->copy_bytes.assign(sh.L, 0);
   const float scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)sh.D);
   c->scale_log2 = (float)((double)scale * 1.4426950408889634);
-  c->slots = (int64_t)sh.max_req * sh.max_chunks * sh.Hkv;
+  if (!host_only) {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+      c->hs.n_cu = cus;
+  }
+  c->seg_cap = c->hs.max_segments();
+  c->slots = c->seg_cap * sh.Hkv;
+  const size_t items_words = (size_t)(c->seg_cap + 8) + (size_t)c->seg_cap * 4;
   if (!host_only) {  // storage of the work-list builder, so that attention calls do not touch the heap
-    c->items_tmp.reserve((size_t)c->slots * 4);
-    c->hs.work_full_.reserve((size_t)sh.max_req * sh.max_chunks);
-    c->hs.work_ragged_.reserve((size_t)sh.max_req);
+    c->items_tmp.reserve((size_t)c->seg_cap * 4);
+    c->hs.work_order.reserve((size_t)c->seg_cap + 8);
+    c->hs.work_sort_.reserve((size_t)c->seg_cap);
+    c->hs.work_seg_base.reserve(sh.max_req);
+    c->hs.work_n_parts.reserve(sh.max_req);
   }
 
   if (!host_only) {
@@ -805,12 +822,12 @@ int orbit_create(const orbit_config *cfg, orbit_ctx **out) try {
       p->static_scratch = (uint8_t *)sp;
     }
     CREATE_CHECK(hipMalloc((void **)&p->d_table, c->hs.h_table.size() * sizeof(int32_t)));
-    CREATE_CHECK(hipMalloc((void **)&p->d_items, (size_t)c->slots * 4 * sizeof(int32_t)));
+    CREATE_CHECK(hipMalloc((void **)&p->d_items, items_words * sizeof(int32_t)));
     CREATE_CHECK(hipMalloc((void **)&p->d_pacc, (size_t)c->slots * sh.G * 128 * sizeof(float)));
     CREATE_CHECK(hipMalloc((void **)&p->d_pml, (size_t)c->slots * 32 * sizeof(float)));
     CREATE_CHECK(hipMemset(p->d_table, 0, c->hs.h_table.size() * sizeof(int32_t)));
-    for (int b = 0; b < 2; ++b) {
-      CREATE_CHECK(hipHostMalloc((void **)&p->h_items_pinned[b], (size_t)c->slots * 4 * sizeof(int32_t), hipHostMallocDefault));
+    for (int b = 0; b < kItemBufs; ++b) {
+      CREATE_CHECK(hipHostMalloc((void **)&p->h_items_pinned[b], items_words * sizeof(int32_t), hipHostMallocDefault));
       CREATE_CHECK(hipEventCreateWithFlags(&p->ev_items[b], hipEventDisableTiming));
     }
     CREATE_CHECK(hipHostMalloc((void **)&p->h_tab_pinned, c->hs.h_table.size() * sizeof(int32_t), hipHostMallocDefault));
@@ -864,7 +881,7 @@ int orbit_destroy(orbit_ctx *c) {
     if (c->h_tab_pinned) (void)hipHostFree(c->h_tab_pinned);
     for (hipEvent_t e : {c->ev_ops, c->ev_tab, c->ev_plan_c, c->ev_plan_x, c->ev_ops_up, c->ev_lazy_all})
       if (e) (void)hipEventDestroy(e);
-    for (int b = 0; b < 2; ++b) {
+    for (int b = 0; b < kItemBufs; ++b) {
       if (c->h_items_pinned[b]) (void)hipHostFree(c->h_items_pinned[b]);
       if (c->ev_items[b]) (void)hipEventDestroy(c->ev_items[b]);
     }
@@ -1231,10 +1248,17 @@ int64_t orbit_get_work_items(orbit_ctx *c, int32_t layer, int32_t *items_out, in
   if (rc) return rc;
   std::vector<int32_t> items;
   rc = c->hs.build_work_items(layer, items);
+  c->items_valid = false;  // the builder's per-request state now describes this list, not the uploaded one
   if (rc) return set_err(c, rc, c->hs.err);
   const int64_t n = (int64_t)items.size() / 4;
   if (items_out)
-    for (int64_t i = 0; i < n * 4 && i < cap * 4; ++i) items_out[i] = items[i];
+    for (int64_t i = 0; i < n && i < cap; ++i) {
+      const int64_t len = c->hs.reqs[items[4 * i]].layers[layer].len;
+      items_out[4 * i] = items[4 * i];
+      items_out[4 * i + 1] = items[4 * i + 1];
+      items_out[4 * i + 2] = (int32_t)std::min<int64_t>(items[4 * i + 2], len - items[4 * i + 1]);  // the last chunk is ragged
+      items_out[4 * i + 3] = items[4 * i + 3];
+    }
   return n;
 } catch (const std::exception &e) {  // nothing may unwind through the C ABI
   return c ? set_err(c, ORBIT_E_NOMEM, std::string("host allocation failed: ") + e.what()) : ORBIT_E_NOMEM;

@@ -15,22 +15,26 @@ struct AttnReq {
   int32_t n_tok;            // tokens attended for this request in this layer (the appended one included)
   int32_t host_page0;       // append mode: first page of the (request, layer) run in the host arena that must
                             // receive the new token besides the page attention reads, or -1
+  int32_t n_parts;          // segments this request's tokens were cut into
 };
 
 struct AttnParams {
   uint8_t *arena;           // device, page 0 of the HBM arena
   uint8_t *host;            // device-visible page 0 of the pinned host arena, or NULL
   const int32_t *table;     // device [max_req][L][cap_pages] page ids; a negative id i names host page ~i
-  const int32_t *items;     // device [n_items][4] {request, kv head, chunk, partial slot}
+  const int32_t *work;      // device: launch order [n_workers] (segment index, or -1 = padding), then (at seg_off) the
+                            // segments [n_segs][4] {request, first token (multiple of 32), tokens, unused}
   const uint16_t *q;        // device [n_req][Hq][128] bf16
-  float *pacc;              // device [slots][G][128] un-normalised partial outputs
-  float *pml;               // device [slots][2][16] partial (max, sum) in log2 units
-  uint16_t *out;            // device [n_req][Hq][128] bf16: written here only for requests of a single chunk
+  float *pacc;              // device [n_segs * Hkv][G][128] un-normalised partial outputs; slot = segment * Hkv + kv head
+  float *pml;               // device [n_segs * Hkv][2][16] partial (max, sum) in log2 units
+  uint16_t *out;            // device [n_req][Hq][128] bf16: written here only for requests of a single segment
   float *out_f32;           // optional device [n_req][Hq][128] fp32
   const uint16_t *k_new;    // append mode: device [n_req][Hkv][128] bf16 rows of the token at position n_tok-1; else NULL
   const uint16_t *v_new;
   int64_t page_bytes;
-  int32_t L, layer, cap_pages, Hq, Hkv, G, chunk_tokens, max_chunks, n_items;
+  int32_t L, layer, cap_pages, Hq, Hkv, G;
+  int32_t n_workers;        // multiple of 8; the grid is n_workers * Hkv workgroups
+  int32_t seg_off;          // index of the first segment entry in `work`
   float scale_log2;         // softmax scale * log2(e)
   AttnReq req[kMaxRequests];
 };
@@ -40,8 +44,9 @@ struct CombineParams {
   const float *pml;
   uint16_t *out;            // device [n_req][Hq][128] bf16
   float *out_f32;           // optional
-  int32_t Hq, Hkv, G, chunk_tokens, max_chunks, n_req;
-  int32_t n_tok[kMaxRequests];  // as AttnReq::n_tok; requests of a single chunk are skipped
+  int32_t Hq, Hkv, G, n_req;
+  int32_t seg_base[kMaxRequests];  // first segment of each request
+  int32_t n_parts[kMaxRequests];   // its number of segments; requests of a single segment are skipped
 };
 
 struct AppendItem {

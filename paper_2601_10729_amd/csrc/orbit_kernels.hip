@@ -213,8 +213,9 @@ __device__ __forceinline__ void process_tile(Tile &T, const bf16x8_t (&q)[4], f3
   tile_pv<MASK>(T, pB, alpha, acc, valid, j);
 }
 
-// Two register tiles per wave: the next tile's loads are in flight while the current one is
-// processed (about 16 KiB per wave, 64 KiB per CU, outstanding at all times); 1 workgroup per CU slot.
+// One workgroup per (segment, kv head), in the launch order the host chose.  Two register tiles per
+// wave: the next tile's loads are in flight while the current one is processed (about 16 KiB per wave,
+// 64 KiB per CU, outstanding at all times); 1 workgroup per CU slot.
 // APPEND: n_tok counts a token whose K/V row is still in k_new/v_new (see last_token_tile).
 template <bool APPEND>
 __global__ __launch_bounds__(256, 1) void attention_kernel(const AttnParams p) {
@@ -224,19 +225,24 @@ __global__ __launch_bounds__(256, 1) void attention_kernel(const AttnParams p) {
   const int j = lane >> 4, nn = lane & 15;
   const uint32_t lane_off = (uint32_t)lane * 16u;
   const int G = p.G;
+  const int64_t v_off = (int64_t)p.Hkv * kTileBytes;
 
-  const int32_t *it = p.items + (int64_t)blockIdx.x * 4;
-  const int r = it[0], g = it[1], c = it[2], pslot = it[3];
+  // workgroup b runs on XCD b mod 8: the Hkv heads of a segment, which share its pages, sit 8 workgroups apart
+  const int b = blockIdx.x, jj = b >> 3;
+  const int g = jj % p.Hkv;
+  const int seg = p.work[(jj / p.Hkv) * 8 + (b & 7)];
+  if (seg < 0) return;  // padding of the launch order to a multiple of 8
+  const int64_t head_off = (int64_t)g * kTileBytes;
+  const int32_t *it = p.work + p.seg_off + (int64_t)seg * 4;
+  const int r = it[0], tok0 = it[1];
   const int n = p.req[r].n_tok;
-  const int nc = (n + p.chunk_tokens - 1) / p.chunk_tokens;
-  const int tok0 = c * p.chunk_tokens;
+  const bool single = p.req[r].n_parts == 1;
+  const int span = min(it[2], n - tok0);
   // the request's last token is handled after the paged tiles (see last_token_tile)
-  const bool has_last = c == nc - 1;
-  const int ntok = min(p.chunk_tokens, n - tok0) - (has_last ? 1 : 0);  // >= 0
+  const bool has_last = tok0 + span == n;
+  const int ntok = span - (has_last ? 1 : 0);  // >= 0
   const int ntiles = (ntok + 2 * kP - 1) / (2 * kP);
   const int32_t *row = p.table + ((int64_t)r * p.L + p.layer) * p.cap_pages + tok0 / kP;
-  const int64_t v_off = (int64_t)p.Hkv * kTileBytes;
-  const int64_t head_off = (int64_t)g * kTileBytes;
 
   bf16x8_t q[4];
   {
@@ -322,66 +328,66 @@ __global__ __launch_bounds__(256, 1) void attention_kernel(const AttnParams p) {
     for (int nb = 0; nb < 8; ++nb) *reinterpret_cast<f32x4_t *>(dst + 16 * nb) = acc[nb];
   }
   __syncthreads();
-  if (wave == 0) {
-    if (nn < G) {
-      float mw[kWaves], lw[kWaves];
+  if (wave == 0 && nn < G) {
+    float mw[kWaves], lw[kWaves];
 #pragma unroll
-      for (int w = 0; w < kWaves; ++w) {
-        mw[w] = sm_ml[w * 32 + nn];
-        lw[w] = sm_ml[w * 32 + 16 + nn];
+    for (int w = 0; w < kWaves; ++w) {
+      mw[w] = sm_ml[w * 32 + nn];
+      lw[w] = sm_ml[w * 32 + 16 + nn];
+    }
+    const float M = fmaxf(fmaxf(mw[0], mw[1]), fmaxf(mw[2], mw[3]));  // finite: some wave had a tile
+    float f[kWaves];
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) f[w] = fast_exp2(mw[w] - M);
+    float lt = lw[0] * f[0];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) lt += lw[w] * f[w];
+    if (single) {  // the only segment of this (request, kv head): normalise and write the output
+      const float inv = 1.0f / lt;
+      const int64_t o = ((int64_t)r * p.Hq + g * G + nn) * kD + 4 * j;
+#pragma unroll
+      for (int nb = 0; nb < 8; ++nb) {
+        f32x4_t v = acc[nb] * f[0];
+#pragma unroll
+        for (int w = 1; w < kWaves; ++w)
+          v += *reinterpret_cast<const f32x4_t *>(sm_acc + ((w - 1) * G + nn) * kD + 4 * j + 16 * nb) * f[w];
+        v *= inv;
+        *reinterpret_cast<u32x2_t *>(p.out + o + 16 * nb) =
+            u32x2_t{bf16_rne_bits(v[0]) | (bf16_rne_bits(v[1]) << 16), bf16_rne_bits(v[2]) | (bf16_rne_bits(v[3]) << 16)};
+        if (p.out_f32) *reinterpret_cast<f32x4_t *>(p.out_f32 + o + 16 * nb) = v;
       }
-      const float M = fmaxf(fmaxf(mw[0], mw[1]), fmaxf(mw[2], mw[3]));  // finite: some wave had a tile
-      float f[kWaves];
+    } else {
+      const int64_t pslot = (int64_t)seg * p.Hkv + g;
+      float *out = p.pacc + (pslot * G + nn) * kD + 4 * j;
 #pragma unroll
-      for (int w = 0; w < kWaves; ++w) f[w] = fast_exp2(mw[w] - M);
-      float lt = lw[0] * f[0];
+      for (int nb = 0; nb < 8; ++nb) {
+        f32x4_t o = acc[nb] * f[0];
 #pragma unroll
-      for (int w = 1; w < kWaves; ++w) lt += lw[w] * f[w];
-      if (nc == 1) {  // the only chunk of this (request, kv head): normalise and write the output
-        const float inv = 1.0f / lt;
-        const int64_t o = ((int64_t)r * p.Hq + g * G + nn) * kD + 4 * j;
-#pragma unroll
-        for (int nb = 0; nb < 8; ++nb) {
-          f32x4_t v = acc[nb] * f[0];
-#pragma unroll
-          for (int w = 1; w < kWaves; ++w)
-            v += *reinterpret_cast<const f32x4_t *>(sm_acc + ((w - 1) * G + nn) * kD + 4 * j + 16 * nb) * f[w];
-          v *= inv;
-          *reinterpret_cast<u32x2_t *>(p.out + o + 16 * nb) =
-              u32x2_t{bf16_rne_bits(v[0]) | (bf16_rne_bits(v[1]) << 16), bf16_rne_bits(v[2]) | (bf16_rne_bits(v[3]) << 16)};
-          if (p.out_f32) *reinterpret_cast<f32x4_t *>(p.out_f32 + o + 16 * nb) = v;
-        }
-      } else {
-        float *out = p.pacc + ((int64_t)pslot * G + nn) * kD + 4 * j;
-#pragma unroll
-        for (int nb = 0; nb < 8; ++nb) {
-          f32x4_t o = acc[nb] * f[0];
-#pragma unroll
-          for (int w = 1; w < kWaves; ++w)
-            o += *reinterpret_cast<const f32x4_t *>(sm_acc + ((w - 1) * G + nn) * kD + 4 * j + 16 * nb) * f[w];
-          *reinterpret_cast<f32x4_t *>(out + 16 * nb) = o;
-        }
-        if (j == 0) {
-          p.pml[(int64_t)pslot * 32 + nn] = M;
-          p.pml[(int64_t)pslot * 32 + 16 + nn] = lt;
-        }
+        for (int w = 1; w < kWaves; ++w)
+          o += *reinterpret_cast<const f32x4_t *>(sm_acc + ((w - 1) * G + nn) * kD + 4 * j + 16 * nb) * f[w];
+        *reinterpret_cast<f32x4_t *>(out + 16 * nb) = o;
+      }
+      if (j == 0) {
+        p.pml[pslot * 32 + nn] = M;
+        p.pml[pslot * 32 + 16 + nn] = lt;
       }
     }
   }
 }
 
-// One workgroup of 4 waves per (request, query head) with more than one chunk; lane handles dims
-// 2*lane, 2*lane+1; wave w takes chunks w, w+4, ...; the four partial sums are added in wave order.
+// One workgroup of 4 waves per (request, query head) with more than one segment; lane handles dims
+// 2*lane, 2*lane+1; wave w takes segments w, w+4, ... of the request; the four partial sums are added in
+// wave order.
 __global__ __launch_bounds__(256) void combine_kernel(const CombineParams p) {
   __shared__ float sm[kWaves][kD + 1];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int r = blockIdx.x / p.Hq, h = blockIdx.x % p.Hq;
   const int g = h / p.G, nn = h % p.G;
-  const int n = p.n_tok[r];
-  const int nc = (n + p.chunk_tokens - 1) / p.chunk_tokens;
+  const int nc = p.n_parts[r];
   if (nc == 1) return;  // written by the attention launch itself
-  auto slot = [&](int c) { return (int64_t)(r * p.max_chunks + c) * p.Hkv + g; };
+  const int64_t base = p.seg_base[r];
+  auto slot = [&](int c) { return (base + c) * p.Hkv + g; };
 
   float M = -INFINITY;
   for (int c = lane; c < nc; c += 64) M = fmaxf(M, p.pml[slot(c) * 32 + nn]);
@@ -553,9 +559,9 @@ __global__ __launch_bounds__(256) void blit_narrow_kernel(const BlitOp *ops, int
 // ------------------------------------------------------------------------------------ launches
 
 hipError_t launch_attention(const AttnParams &p, hipStream_t s) {
-  if (p.n_items <= 0) return hipSuccess;
+  if (p.n_workers <= 0) return hipSuccess;
   const size_t lds = (size_t)(3 * p.G * kD + kWaves * 32) * sizeof(float);
-  const dim3 grid((unsigned)p.n_items), block(256);
+  const dim3 grid((unsigned)(p.n_workers * p.Hkv)), block(256);
   if (p.k_new) hipLaunchKernelGGL(attention_kernel<true>, grid, block, lds, s, p);
   else hipLaunchKernelGGL(attention_kernel<false>, grid, block, lds, s, p);
   return hipGetLastError();

@@ -19,6 +19,13 @@ def errors(got: torch.Tensor, want: np.ndarray):
     return float(np.abs(d).max()), float(np.sqrt((d * d).sum() / max((want * want).sum(), 1e-300)))
 
 
+def release_pinned_cache():
+    """Returns torch's cached (freed) pinned host blocks to the driver."""
+    import gc
+    gc.collect()
+    torch._C._host_emptyCache()
+
+
 class GpuRun:
     """A liborbit context on cuda:0 holding workload ``w`` under ``placement``."""
 
@@ -37,7 +44,9 @@ class GpuRun:
         all_host = int(w.blocks(self.window).sum()) * w.n_layers
         hpages = all_host if host_pages is None else host_pages
         self.hbm = torch.empty(pages * w.page_bytes, dtype=torch.uint8, device=self.dev)
+        self._host_borrowed = host_tensor is not None
         if host_tensor is None:
+            release_pinned_cache()
             self.host = torch.empty(max(hpages, 1) * w.page_bytes, dtype=torch.uint8, pin_memory=True)
         else:                                   # a slice of a pinned arena the caller keeps for several runs
             assert host_tensor.is_pinned() and host_tensor.numel() >= hpages * w.page_bytes
@@ -123,6 +132,12 @@ class GpuRun:
     def close(self):
         torch.cuda.synchronize()
         self.ctx.destroy()
+        # torch keeps freed pinned blocks cached, and the boxes refuse pinned memory beyond a total that differs
+        # from box to box: hand the arenas back so that the sum over a test session stays small
+        owned = not getattr(self, "_host_borrowed", False)
+        self.hbm = self.host = None
+        if owned:
+            release_pinned_cache()
 
 
 class OracleRun:

@@ -80,7 +80,6 @@ int main(int argc, char **argv) {
   sh.page_bytes = 65536;
   sh.cap_pages = 256;
   sh.chunk_tokens = 64 * rnd(1, 8);
-  sh.max_chunks = (int)ceil_div(sh.max_tokens, sh.chunk_tokens);
   sh.window = rnd(0, 40);
   sh.slots = rnd(1, 3);
   sh.zero_copy = rnd(0, 3) == 0;
@@ -130,12 +129,16 @@ int main(int argc, char **argv) {
       for (auto &q : hs.reqs) all_nonempty &= q.layers[0].len > 0;
       if (all_nonempty) {
         CHECK(hs.build_work_items(0, items) == 0);
-        std::set<int32_t> slots;
+        CHECK((int64_t)items.size() / 4 <= hs.max_segments());
+        std::vector<int64_t> covered(hs.reqs.size(), 0);
         for (size_t i = 0; i < items.size(); i += 4) {
-          CHECK(items[i] >= 0 && items[i] < (int)hs.reqs.size() && items[i + 1] < sh.Hkv);
-          CHECK((int64_t)items[i + 2] * sh.chunk_tokens < hs.reqs[items[i]].layers[0].len);
-          CHECK(slots.insert(items[i + 3]).second);
+          CHECK(items[i] >= 0 && items[i] < (int)hs.reqs.size());
+          CHECK(items[i + 1] == covered[items[i]] && items[i + 1] % 32 == 0 && items[i + 2] >= 1);
+          CHECK(items[i + 2] == sh.chunk_tokens);
+          CHECK(items[i + 3] >= 0 && items[i + 3] < hs.work_workers && hs.work_order[items[i + 3]] == (int)(i / 4));
+          covered[items[i]] += std::min<int64_t>(items[i + 2], hs.reqs[items[i]].layers[0].len - items[i + 1]);
         }
+        for (size_t r = 0; r < hs.reqs.size(); ++r) CHECK(covered[r] == hs.reqs[r].layers[0].len);
       }
     }
   }

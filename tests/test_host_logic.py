@@ -254,31 +254,50 @@ def test_block_growth_and_window_expiry():
 
 # ------------------------------------------------------------------ work list
 
-@pytest.mark.parametrize("chunk", [64, 1024])
-def test_work_items_match_brute_force(chunk):
-    rng = np.random.default_rng(3)
-    B, L, Hkv = 6, 2, 8
-    max_tokens = 8192
-    c = ctx(L=L, max_tokens=max_tokens, chunk=chunk)
-    n = np.array([1, chunk, chunk + 1, 3 * chunk - 1, 777, 5000])
+def _expected_chunk(n, Hkv, fixed=0, n_cu=256):
+    if fixed:
+        return fixed
+    if max(n) <= 512 or (max(n) <= 4096 and len(n) * Hkv * 2 >= n_cu):   # short, or whole requests fill half of the machine
+        return max(128, 1 << int(max(n) - 1).bit_length())
+    for c in (4096, 2048, 1024, 512, 256):
+        if sum(-(-int(v) // c) for v in n) * Hkv >= n_cu:
+            return c
+    return 128
+
+
+@pytest.mark.parametrize("chunk", [0, 64, 1024])
+@pytest.mark.parametrize("lengths", [(1, 64, 65, 191, 777, 5000), (2048,), (100,), (7700, 7700, 2250, 1024),
+                                     (30000, 9000, 17, 1, 1, 25000, 33, 8191), (8192,), (32768,),
+                                     tuple(500 + 7 * r for r in range(16)), tuple(20000 + 977 * r for r in range(16))])
+def test_work_segments_match_brute_force(chunk, lengths):
+    L, Hkv = 2, 8
+    n = np.array(lengths)
+    B = len(n)
+    c = ctx(L=L, max_req=16, max_tokens=40000, hbm_pages=80000, chunk=chunk)
     c.plan_load(list(range(B)), n, np.ones((B, L), dtype=np.uint8))
-    items = c.get_work_items(1)
-    max_chunks = max(-(-int(v) // chunk) for v in n)          # slots are numbered by the largest chunk count present
-    want = {(r, g, ch): (r * max_chunks + ch) * Hkv + g
-            for r in range(B) for g in range(Hkv) for ch in range(-(-int(n[r]) // chunk))}
-    got = {(int(a), int(b), int(cc)): int(s) for a, b, cc, s in items}
-    assert got == want and len(items) == len(want)
-    # in order of first appearance, the (request, chunk) groups with a ragged chunk come last
-    first_seen = list(dict.fromkeys((int(r), int(cc)) for r, g, cc, s in items))
-    is_full = [bool((cc + 1) * chunk <= n[r]) for r, cc in first_seen]
-    assert is_full == sorted(is_full, reverse=True)
-    # the kv heads of one (request, chunk) sit 8 items apart: same XCD under round-robin dispatch
-    # (every full span of 8 groups; the last, shorter span is packed densely)
-    pos = {}
-    full_spans = (len(first_seen) // 8) * 8 * Hkv
-    for i, (r, g, cc, s) in enumerate(items[:full_spans]):
-        pos.setdefault((int(r), int(cc)), []).append(i % 8)
-    assert pos and all(len(set(v)) == 1 and len(v) == Hkv for v in pos.values())
+    items = [[int(v) for v in row] for row in c.get_work_items(1)]
+    C = _expected_chunk(lengths, Hkv, chunk)
+    want = [(r, t, min(C, int(n[r]) - t)) for r in range(B) for t in range(0, int(n[r]), C)]
+    assert [tuple(row[:3]) for row in items] == want
+    # launch order: a permutation, longest segment first, ties in list order
+    rank = [row[3] for row in items]
+    assert sorted(rank) == list(range(len(items)))
+    by_rank = sorted(range(len(items)), key=lambda i: rank[i])
+    assert by_rank == sorted(range(len(items)), key=lambda i: (-items[i][2], i))
+
+
+def test_chunk_choice_examples():
+    """One request of 8K tokens on 8 kv heads: 256-token chunks give all 256 units a workgroup; 16 short requests
+    already fill half of the machine and are not cut; a 16 x 20K batch uses the largest chunk."""
+    L = 1
+    c = ctx(L=L, max_req=16, max_tokens=40000, hbm_pages=50000)
+    for k, (n, want) in enumerate([([8192], 256), ([2048], 128), ([300], 512), ([600], 128), ([32768], 1024), ([8192] * 4, 1024),
+                                   ([500] * 16, 512), ([2048] * 16, 2048), ([5000] * 16, 4096), ([20000] * 16, 4096)]):
+        ids = list(range(100 * k, 100 * k + len(n)))
+        c.plan_load(ids, n, np.ones((len(n), L), dtype=np.uint8))
+        items = c.get_work_items(0)
+        assert int(items[:, 2].max()) == min(want, max(n)), (n, want)
+        assert len(items) == sum(-(-v // want) for v in n)
 
 
 def test_attention_on_an_empty_request_is_an_error():
@@ -377,7 +396,7 @@ def test_pause_keeps_blocks_and_evicts_only_what_is_needed():
     with pytest.raises(OrbitError) as e:
         c.request_pause(3)
     assert e.value.code == orbit.ORBIT_E_STATE
-    assert len(c.get_work_items(0)) == (1 + 1) * 8                   # only the two active requests
+    assert sorted({int(r) for r, _, _, _ in c.get_work_items(0)}) == [0, 1]    # only the two active requests
     # a new request needs 40 blocks: 100 + 40 + 80 paused > 200, so exactly one paused layer (20 blocks) goes
     c.plan_load([1, 2, 4], [160, 240, 160], ones(3))
     info = c.get_plan_info()

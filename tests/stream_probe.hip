@@ -4,9 +4,11 @@
 // Every variant reads the same 1.476 GB (22528 blocks of 64 KiB, the size of one attention launch of
 // the 8B-shaped batch-16 workload) with 2816 workgroups of 4 wavefronts, two 16 KiB register tiles per
 // wavefront in flight, 16-byte loads, no arithmetic beyond an XOR that keeps the loads alive:
-//   kernel-pattern   a workgroup owns one KV head of a 64-block chunk and reads that head's 4 KiB K
-//                    tile and 4 KiB V tile of every block; the 8 heads of a chunk run on one XCD
-//                    (workgroup i runs on XCD i mod 8) - what attention_kernel issues
+//   kernel-pattern   a workgroup owns one KV head of a 64-block chunk (1024 tokens) and reads that head's
+//                    4 KiB K tile and 4 KiB V tile of every block; the 8 heads of a chunk run on one XCD
+//                    (workgroup i runs on XCD i mod 8)
+//   kernel-pattern-4096  the same with 256-block chunks (4096 tokens, 704 workgroups) - what
+//                    attention_kernel issues at this launch size
 //   heads-scattered  the same reads, the 8 heads of a chunk on 8 different XCDs
 //   plain-loads      kernel-pattern with ordinary instead of nontemporal loads
 //   whole-blocks     a workgroup reads 8 whole consecutive blocks (the same 512 KiB per workgroup)
@@ -38,7 +40,8 @@ __device__ __forceinline__ u32x4 ld(const unsigned char *p) {
 
 // mode 0: kernel pattern, 1: heads scattered over XCDs, 2: whole blocks
 template <bool NT>
-__global__ __launch_bounds__(256, 1) void read_kernel(const unsigned char *__restrict__ base, int mode, unsigned *sink) {
+__global__ __launch_bounds__(256, 1) void read_kernel(const unsigned char *__restrict__ base, int mode, int chunk_blocks,
+                                                      unsigned *sink) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int i = blockIdx.x;
   int g, chunk;
@@ -58,7 +61,7 @@ __global__ __launch_bounds__(256, 1) void read_kernel(const unsigned char *__res
     } else {
 #pragma unroll
       for (int b = 0; b < 2; ++b) {
-        const unsigned char *blk = base + ((long)chunk * kChunkBlocks + 2 * t + b) * kBlock + g * 4096 + lane * 16;
+        const unsigned char *blk = base + ((long)chunk * chunk_blocks + 2 * t + b) * kBlock + g * 4096 + lane * 16;
 #pragma unroll
         for (int k = 0; k < 4; ++k) T.r[8 * b + k] = ld<NT>(blk + k * 1024);              // K tile
 #pragma unroll
@@ -70,7 +73,7 @@ __global__ __launch_bounds__(256, 1) void read_kernel(const unsigned char *__res
 #pragma unroll
     for (int k = 0; k < 16; ++k) acc ^= T.r[k];
   };
-  const int ntiles = 32;
+  const int ntiles = mode == 2 ? 32 : chunk_blocks / 2;
   Tile A, B;
   int t = wave;
   load(A, t);
@@ -93,7 +96,9 @@ int main() {
   // host-side bounds: the farthest byte any variant touches
   const long far_pattern = ((long)(kChunks - 1) * kChunkBlocks + 63) * kBlock + 7 * 4096 + 32768 + 3 * 1024 + 63 * 16 + 16;
   const long far_blocks = ((long)(kWorkgroups - 1) * 8) * kBlock + 31L * 16384 + 15 * 1024 + 63 * 16 + 16;
-  if (far_pattern > (long)bytes || far_blocks > (long)bytes) {
+  const long far_big = ((long)(kChunks / 4 - 1) * (4 * kChunkBlocks) + 4 * kChunkBlocks - 1) * kBlock + 7 * 4096 + 32768 + 3 * 1024 + 63 * 16 + 16;
+  static_assert(kChunks % 32 == 0, "the 4096-token variant needs whole spans of 8 chunks");
+  if (far_pattern > (long)bytes || far_blocks > (long)bytes || far_big > (long)bytes) {
     std::printf("probe addresses out of bounds\n");
     return 2;
   }
@@ -103,14 +108,16 @@ int main() {
   if (hipMemset(p, 1, bytes) != hipSuccess || hipMemset(sink, 0, 4) != hipSuccess) return 1;
   hipEvent_t e0, e1;
   if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return 1;
-  const char *names[4] = {"kernel-pattern", "heads-scattered", "plain-loads", "whole-blocks"};
-  for (int v = 0; v < 4; ++v) {
+  const char *names[5] = {"kernel-pattern", "heads-scattered", "plain-loads", "whole-blocks", "kernel-pattern-4096"};
+  for (int v = 0; v < 5; ++v) {
     const int mode = v == 1 ? 1 : (v == 3 ? 2 : 0);
+    const int chunk_blocks = v == 4 ? 4 * kChunkBlocks : kChunkBlocks;
+    const int grid = v == 4 ? kWorkgroups / 4 : kWorkgroups;
     float best = 1e30f;
     for (int rep = 0; rep < 8; ++rep) {
       (void)hipEventRecord(e0, nullptr);
-      if (v == 2) hipLaunchKernelGGL(read_kernel<false>, dim3(kWorkgroups), dim3(256), 0, nullptr, (const unsigned char *)p, mode, sink);
-      else hipLaunchKernelGGL(read_kernel<true>, dim3(kWorkgroups), dim3(256), 0, nullptr, (const unsigned char *)p, mode, sink);
+      if (v == 2) hipLaunchKernelGGL(read_kernel<false>, dim3(grid), dim3(256), 0, nullptr, (const unsigned char *)p, mode, chunk_blocks, sink);
+      else hipLaunchKernelGGL(read_kernel<true>, dim3(grid), dim3(256), 0, nullptr, (const unsigned char *)p, mode, chunk_blocks, sink);
       (void)hipEventRecord(e1, nullptr);
       if (hipEventSynchronize(e1) != hipSuccess || hipGetLastError() != hipSuccess) {
         std::printf("launch failed\n");

@@ -90,6 +90,35 @@ def test_edge_lengths(lens, chunk):
     g.close()
 
 
+@pytest.mark.parametrize("lens,want_chunk", [
+    ([600], 128),                       # too few tokens to fill the machine: the smallest chunk
+    ([8191], 256),                      # one request of 8K tokens: 32 chunks x 8 heads = one workgroup per unit
+    ([20001], 512),
+    ([9000, 10001, 8195, 7000], 1024),
+    ([20000, 17001, 19003, 18000], 2048),
+    ([6000 + 13 * r for r in range(16)], 4096),
+    ([3000 + 17 * r for r in range(16)], 4096),   # whole requests fill half of the machine: nothing is cut
+    ([300, 17, 512], 512),              # short requests are never cut
+])
+def test_every_chunk_size_a_launch_can_choose(lens, want_chunk):
+    """chunk_tokens = 0: the launch picks its chunk size from the lengths; every size it can pick, the uncut cases
+    and a step behind each (the cached work list with grown lengths) against the oracle."""
+    h = _harness()
+    w = _custom(lens, L=1, Hq=32, Hkv=8, steps=2)
+    g = h.GpuRun(w)
+    items = g.ctx.get_work_items(0)
+    assert int(items[:, 2].max()) == min(want_chunk, max(lens))
+    assert len(items) == sum(-(-n // want_chunk) for n in lens)
+    o = h.OracleRun(w, extra_tokens=2)
+    out, out32 = g.attention(0)
+    _check(out, out32, o.attention(0))
+    for s in range(2):
+        out, _ = g.step(s)
+        o.append_all()
+        _check(out[0], None, o.attention(0, s))
+    g.close()
+
+
 @pytest.mark.parametrize("Hq,Hkv", [(32, 8), (64, 8), (8, 8), (16, 1), (128, 128), (256, 128)])
 def test_head_shapes(Hq, Hkv):
     h = _harness()

@@ -135,6 +135,8 @@ typedef struct {
   int32_t reserved_;
   int64_t deferred_to_host_blocks;/* of the blocks the last plan load moved or evicted to the host: those whose
                                      copy runs beside the following steps instead of in front of them      */
+  int64_t in_place_blocks;        /* blocks of active requests that the last plan load demoted and that are read
+                                     where they were in HBM until their copies have landed                 */
 } orbit_plan_info;
 
 /* ---- lifetime (ancillary) ------------------------------------------------------------------ */
@@ -172,8 +174,13 @@ ORBIT_API int orbit_plan_check(int32_t n_req, int32_t n_layers, int32_t page_tok
  * the migrations the new plan needs at once are enqueued on copy_stream behind everything already
  * enqueued on compute_stream, and compute_stream waits for them before any later call's work.
  * Blocks that leave HBM without their pages being needed at once (orbit_plan_info.deferred_to_host_blocks)
- * are copied out on a stream of the library's own, beside the following steps; whatever touches such a
- * layer's host blocks next, and the next plan load, waits for those copies stream-side.
+ * are copied out on a stream of the library's own, beside the following steps.  Until a layer's copies have
+ * landed, attention reads such blocks of active requests where they were (orbit_plan_info.in_place_blocks:
+ * their old pages are not handed out before the next plan load), a step's new token is written there and into
+ * the host run, and the layer is not prefetched for them; the first prefetch of the layer issued after its
+ * copies have completed switches them to the staging region.  Calls that need the host copy itself
+ * (orbit_kv_fill, orbit_kv_read, orbit_kv_append, a decode window that outgrows the old pages, the zero-copy
+ * mode) and the next plan load wait for the copies stream-side.
  * ORBIT_E_STATE if a prefetched layer has not been attended yet. */
 ORBIT_API int orbit_plan_load(orbit_ctx *ctx, int32_t n_req, const int64_t *req_ids, const int32_t *ctx_len,
                     const uint8_t *placement_bitmap, int64_t hbm_budget_bytes);
@@ -392,7 +399,8 @@ ORBIT_API int orbit_profile_ewma(double *profile, const double *observed, int64_
 
 /* Page ids that attention reads for (req_id, layer): arena ids for a resident block list,
  * staging-region ids for an offloaded one.  Writes up to cap ids, returns the reserved count
- * (or a negative error).  tier: 1 = HBM, 0 = host; host_first_page: index of the run's first
+ * (or a negative error).  tier: 1 = HBM, 0 = host, 2 = host but still read in place from the HBM
+ * pages it had (then those pages are listed); host_first_page: index of the run's first
  * page in the host arena (or -1); length: tokens stored. */
 ORBIT_API int64_t orbit_get_pages(orbit_ctx *ctx, int64_t req_id, int32_t layer, int32_t *tier,
                         int64_t *host_first_page, int32_t *length, int32_t *pages_out, int64_t cap);

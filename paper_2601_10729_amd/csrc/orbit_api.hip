@@ -82,6 +82,7 @@ struct orbit_ctx {
   size_t d_ops_cap = 0;
   int32_t *h_tab_pinned = nullptr;                           // pinned snapshot the table upload reads
   hipEvent_t ev_ops = nullptr, ev_tab = nullptr;             // last use of the staging copies
+  hipEvent_t ev_tab_rows = nullptr;                          // last single-row upload from the pinned table mirror
   hipEvent_t ev_plan_c = nullptr, ev_plan_x = nullptr;       // stream ordering of a plan switch
   hipEvent_t ev_ops_up = nullptr, ev_lazy_all = nullptr;     // op list uploaded; every deferred copy of the last switch done
   std::vector<hipEvent_t> ev_lazy;                           // per layer: that layer's deferred copies done
@@ -101,6 +102,7 @@ struct orbit_ctx {
   std::vector<int64_t> copy_bytes;    // per layer, last prefetch
   std::vector<int32_t> items_key;     // chunk counts and chunk size the uploaded work list was built for
   std::vector<int32_t> items_key_tmp, items_tmp;  // scratch of ensure_work_items, kept for their storage
+  std::vector<int> flipped_tmp;       // scratch of flip_in_place_blocks
   uint8_t *static_scratch = nullptr;  // this device's copy of the library's static split-K scratch
   int64_t n_segs = 0;
   int32_t seg_off = 0;                // where the segments start in the uploaded buffer (after the span table)
@@ -157,6 +159,46 @@ int wait_deferred(orbit_ctx *c, int layer, bool on_copy_stream) {
   return ORBIT_OK;
 }
 
+// Blocks of `layer` that the last plan load demoted and that are still read where they were in HBM: once the
+// layer's deferred copies have landed (asked of the event, not waited for) they become ordinary host blocks,
+// i.e. their page-table rows point into the staging region from here on (row uploads on the compute stream,
+// behind every launch enqueued so far) and the caller prefetches them.  force: do it now and make the compute
+// stream wait for the copies; also taken when a block's next token would not fit the pages it still has.
+int flip_in_place_blocks(orbit_ctx *c, int layer, bool force) {
+  HostState &hs = c->hs;
+  if (!hs.dual_in_layer[layer]) return ORBIT_OK;
+  const Shape &sh = hs.sh;
+  for (const Req &q : hs.reqs) {
+    const LayerKV &lk = q.layers[layer];
+    if (!lk.dual_pages.empty() && lk.len / sh.P >= (int64_t)lk.dual_pages.size()) force = true;
+  }
+  if (!force && !c->host_only) {
+    const hipError_t e = hipEventQuery(c->ev_lazy[layer]);
+    if (e == hipErrorNotReady) {
+      (void)hipGetLastError();  // "not ready" is an answer, not an error a later launch check should find
+      return ORBIT_OK;
+    }
+    if (e != hipSuccess) return hip_fail(c, e, "hipEventQuery(ev_lazy)");
+  }
+  if (!c->host_only) {
+    if (int rc = wait_deferred(c, layer, false)) return rc;
+    // the last whole-table upload no longer reads the pinned mirror (a row is rewritten at most once between two
+    // of those, so row uploads need not wait for each other)
+    HIPCHECK(c, hipEventSynchronize(c->ev_tab));
+  }
+  hs.flip_layer(layer, c->flipped_tmp);
+  if (!c->host_only) {
+    for (int r : c->flipped_tmp) {
+      const size_t off = ((size_t)r * sh.L + layer) * sh.cap_pages;
+      std::memcpy(c->h_tab_pinned + off, hs.h_table.data() + off, (size_t)sh.cap_pages * sizeof(int32_t));
+      HIPCHECK(c, hipMemcpyAsync(c->d_table + off, c->h_tab_pinned + off, (size_t)sh.cap_pages * sizeof(int32_t),
+                                 hipMemcpyHostToDevice, c->cs));
+    }
+    HIPCHECK(c, hipEventRecord(c->ev_tab_rows, c->cs));
+  }
+  return ORBIT_OK;
+}
+
 // 0 = issued (or nothing to do), 1 = blocked by a prefetched layer not yet attended, <0 = error
 int prefetch_impl(orbit_ctx *c, int layer) {
   HostState &hs = c->hs;
@@ -184,13 +226,15 @@ int prefetch_impl(orbit_ctx *c, int layer) {
     }
     c->host_dirty[layer] = 0;
   }
-  if (int rc = wait_deferred(c, layer, true)) return rc;
+  if (int rc = flip_in_place_blocks(c, layer, false)) return rc;
+  if (!hs.dual_in_layer[layer])  // host blocks of this layer whose copies may still be in flight are read below
+    if (int rc = wait_deferred(c, layer, true)) return rc;
   if (c->timing && !c->host_only) HIPCHECK(c, hipEventRecord(c->t_copy0[layer], c->xs));
   int64_t bytes = 0;
   for (const CopyItem &ci : blk.copies) {
     const LayerKV &lk = hs.reqs[ci.req].layers[layer];
     const int64_t used = ceil_div(lk.len, hs.sh.P);
-    if (used == 0) continue;
+    if (used == 0 || !lk.dual_pages.empty()) continue;  // a block read in place needs no staging copy
     const int64_t nbytes = used * hs.sh.page_bytes;
     bytes += nbytes;
     if (!c->host_only)
@@ -278,7 +322,9 @@ int attention_impl(orbit_ctx *c, int layer, const void *q, void *out, float *out
     if (!c->host_only) HIPCHECK(c, hipStreamWaitEvent(c->cs, c->ev_ready[layer], 0));
     lb->consumed = true;
   }
-  if ((rc = wait_deferred(c, layer, false))) return rc;  // zero-copy reads, and the append's write into a host block
+  // zero-copy reads of a host block whose copy may be in flight wait for it; in the staged mode such a block is
+  // read in place, and the append's write into its host run cannot meet a copy (its last page was copied at once)
+  if (sh.zero_copy && (rc = wait_deferred(c, layer, false))) return rc;
   if (!c->host_only) {
     if (c->timing) HIPCHECK(c, hipEventRecord(c->t_attn0[layer], c->cs));
     AttnParams &ap = c->attn_args;  // the per-request part is rewritten below; the rest is cheap to refill
@@ -436,6 +482,7 @@ int apply_plan_gpu(orbit_ctx *c, const std::vector<std::vector<PageOp>> &phases)
   if (n_req > 0) {
     const size_t nt = n_req * sh.L * sh.cap_pages;
     HIPCHECK(c, hipEventSynchronize(c->ev_tab));
+    HIPCHECK(c, hipEventSynchronize(c->ev_tab_rows));
     std::memcpy(c->h_tab_pinned, hs.h_table.data(), nt * sizeof(int32_t));
     HIPCHECK(c, hipMemcpyAsync(c->d_table, c->h_tab_pinned, nt * sizeof(int32_t), hipMemcpyHostToDevice, c->cs));
     HIPCHECK(c, hipEventRecord(c->ev_tab, c->cs));
@@ -774,6 +821,7 @@ int orbit_create(const orbit_config *cfg, orbit_ctx **out) try {
   c->lazy_c.assign(sh.L, 0);
   c->hs.live.reserve(sh.L + 1);
   c->items_key_tmp.reserve(sh.max_req + 1);
+  c->flipped_tmp.reserve(sh.max_req);
   c->items_key.reserve(sh.max_req + 1);
   c->copy_timed.assign(sh.L, 0);
   c->copy_bytes.assign(sh.L, 0);
@@ -833,6 +881,7 @@ int orbit_create(const orbit_config *cfg, orbit_ctx **out) try {
     CREATE_CHECK(hipHostMalloc((void **)&p->h_tab_pinned, c->hs.h_table.size() * sizeof(int32_t), hipHostMallocDefault));
     CREATE_CHECK(hipEventCreateWithFlags(&p->ev_ops, hipEventDisableTiming));
     CREATE_CHECK(hipEventCreateWithFlags(&p->ev_tab, hipEventDisableTiming));
+    CREATE_CHECK(hipEventCreateWithFlags(&p->ev_tab_rows, hipEventDisableTiming));
     CREATE_CHECK(hipEventCreateWithFlags(&p->ev_plan_c, hipEventDisableTiming));
     CREATE_CHECK(hipEventCreateWithFlags(&p->ev_plan_x, hipEventDisableTiming));
     CREATE_CHECK(hipEventCreateWithFlags(&p->ev_tmp, hipEventDisableTiming));
@@ -879,7 +928,7 @@ int orbit_destroy(orbit_ctx *c) {
     (void)hipFree(c->d_ops);
     if (c->h_ops_pinned) (void)hipHostFree(c->h_ops_pinned);
     if (c->h_tab_pinned) (void)hipHostFree(c->h_tab_pinned);
-    for (hipEvent_t e : {c->ev_ops, c->ev_tab, c->ev_plan_c, c->ev_plan_x, c->ev_ops_up, c->ev_lazy_all})
+    for (hipEvent_t e : {c->ev_ops, c->ev_tab, c->ev_tab_rows, c->ev_plan_c, c->ev_plan_x, c->ev_ops_up, c->ev_lazy_all})
       if (e) (void)hipEventDestroy(e);
     for (int b = 0; b < kItemBufs; ++b) {
       if (c->h_items_pinned[b]) (void)hipHostFree(c->h_items_pinned[b]);
@@ -959,6 +1008,7 @@ static int fill_or_read(orbit_ctx *c, bool write, int64_t req_id, int32_t layer,
   if (first < 0 || n < 0 || first + n > lk.len) return set_err(c, ORBIT_E_INVAL, "token range outside the stored length");
   if (n == 0) return ORBIT_OK;
   if (!k || !v) return set_err(c, ORBIT_E_INVAL, "null argument");
+  if (!lk.dual_pages.empty() && (rc = flip_in_place_blocks(c, layer, true))) return rc;  // the host copy itself is wanted
   if (write && lk.tier == 0) {
     LiveBlock *lb = find_live(c, layer);
     if (lb && !lb->consumed) return set_err(c, ORBIT_E_STATE, "layer is prefetched; attend it before rewriting its host blocks");
@@ -1018,6 +1068,7 @@ static int append_item(orbit_ctx *c, int r, int layer, AppendItem &item) {
 // An append into a layer whose prefetch is in flight also writes the staging copy: the compute
 // stream must first see that copy landed, or the transfer could overwrite the new token.
 static int wait_for_live_copy(orbit_ctx *c, int layer) {
+  if (int rc = flip_in_place_blocks(c, layer, true)) return rc;  // this path writes host blocks and staging copies only
   if (int rc = wait_deferred(c, layer, false)) return rc;  // the append may write into a host block
   LiveBlock *lb = find_live(c, layer);
   if (lb && !lb->consumed && !c->host_only) HIPCHECK(c, hipStreamWaitEvent(c->cs, c->ev_ready[layer], 0));
@@ -1177,7 +1228,7 @@ int orbit_step(orbit_ctx *c, const void *q, const void *k_new, const void *v_new
     for (int r = 0; r < nreq; ++r) {
       LayerKV &lk = hs.reqs[r].layers[l];
       lk.len += 1;
-      if (lk.tier == 1) hbm_bytes += (int64_t)lk.len * tok_bytes;
+      if (lk.tier == 1 || !lk.dual_pages.empty()) hbm_bytes += (int64_t)lk.len * tok_bytes;
       else if (sh.zero_copy) c->copy_bytes[l] += ceil_div(lk.len, sh.P) * sh.page_bytes;  // read over the link by the kernel
     }
     if (b >= 0) find_live(c, l)->consumed = true;
@@ -1231,13 +1282,16 @@ int64_t orbit_get_pages(orbit_ctx *c, int64_t req_id, int32_t layer, int32_t *ti
   if (r < 0 && pr < 0) return set_err(c, ORBIT_E_NOT_FOUND, "unknown request id");
   const Req &q = r >= 0 ? c->hs.reqs[r] : c->hs.paused[pr];
   const LayerKV &lk = q.layers[layer];
-  if (tier) *tier = lk.tier;
+  const bool in_place = !lk.dual_pages.empty();
+  if (tier) *tier = in_place ? 2 : lk.tier;
   if (host_first_page) *host_first_page = lk.tier == 0 ? lk.host_page0 : -1;
   if (length) *length = lk.len;
-  const int64_t n = lk.tier == 1 ? (int64_t)lk.pages.size() : (r >= 0 ? q.reserved : lk.host_cap);
+  const int64_t n = in_place ? (int64_t)lk.dual_pages.size()
+                             : (lk.tier == 1 ? (int64_t)lk.pages.size() : (r >= 0 ? q.reserved : lk.host_cap));
   if (pages_out)
     for (int64_t i = 0; i < n && i < cap; ++i)
-      pages_out[i] = lk.tier == 1 ? lk.pages[i] : (r >= 0 && lk.stage_page0 >= 0 ? lk.stage_page0 + (int32_t)i : -1);
+      pages_out[i] = in_place ? lk.dual_pages[i]
+                              : (lk.tier == 1 ? lk.pages[i] : (r >= 0 && lk.stage_page0 >= 0 ? lk.stage_page0 + (int32_t)i : -1));
   return n;
 } catch (const std::exception &e) {  // nothing may unwind through the C ABI
   return c ? set_err(c, ORBIT_E_NOMEM, std::string("host allocation failed: ") + e.what()) : ORBIT_E_NOMEM;

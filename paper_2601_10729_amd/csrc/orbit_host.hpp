@@ -41,6 +41,8 @@ struct PageOp {
 struct DemoteGroup {
   int phase, layer;
   size_t first, n;
+  int req;                         // index in the new batch, or -1 for a paused request's eviction
+  std::vector<int32_t> old_pages;  // the block list it had in HBM (used and reserved pages)
 };
 
 struct LayerKV {
@@ -50,6 +52,9 @@ struct LayerKV {
   int64_t host_page0 = -1;     // first page of the host run (tier 0)
   int32_t host_cap = 0;        // pages in the host run
   int32_t stage_page0 = -1;    // first staging page (tier 0)
+  // Non-empty while a block that the last plan load demoted is still on its way to the host: the HBM
+  // pages it had (no longer owned, but untouched until the next plan load) are read in place.
+  std::vector<int32_t> dual_pages;
 };
 
 struct Req {
@@ -190,9 +195,17 @@ class HostState {
   // below the staging region and no allocation of this plan load took them) is taken out of `phases` and
   // listed here, grouped by layer: it may run beside the following steps, and only a later use of that
   // layer's host blocks, or the next plan load, has to wait for it.
+  //
+  // A deferred block of an active request stays readable where it was (LayerKV::dual_pages): attention reads
+  // those pages, the step's new token goes there and into the host run, and the layer is not prefetched for that
+  // request, until the copy has landed and `flip_layer` hands the block over to the staging schedule.  So that
+  // the new token never meets a copy in flight, the last used page of such a block is copied at once (it stays
+  // in `phases`) and only the pages before it are deferred.  (Not in the zero-copy mode, whose kernel reads the
+  // host run itself: there a deferred block is simply waited for.)
   std::vector<PageOp> deferred;          // sorted by layer
   std::vector<size_t> deferred_end;      // [L] end offset of layer l's ops in `deferred`
   std::vector<uint8_t> reuse_mark_;      // [arena_pages] scratch of the classification
+  std::vector<int32_t> dual_in_layer;    // [L] blocks of the layer that are read in place
 
   std::string err;
 
@@ -206,6 +219,7 @@ class HostState {
     h_table.assign((size_t)sh.max_req * sh.L * sh.cap_pages, 0);
     block_of_layer.assign(sh.L, -1);
     deferred_end.assign(sh.L, 0);
+    dual_in_layer.assign(sh.L, 0);
   }
 
   int find(int64_t id) const {
@@ -267,6 +281,8 @@ class HostState {
     HbmAlloc A = hbm;
     RunAlloc H = host;
     std::vector<Req> old = reqs;
+    for (auto &q : old)  // whatever was still read in place is a plain host block for this plan: its copies are
+      for (auto &lk : q.layers) lk.dual_pages.clear();  // waited for before anything of this plan load runs
     std::vector<Req> oldp = paused;
     std::vector<Req> np;  // paused after this call
     std::vector<Req> nw(n_req);
@@ -316,11 +332,26 @@ class HostState {
     std::vector<std::pair<int64_t, int64_t>> free_host;
     std::vector<DemoteGroup> groups;       // blocks leaving HBM (evictions and demotions)
     std::vector<int32_t> taken;            // HBM pages this plan load allocated
-    auto end_phase = [&]() {
-      for (int64_t p : free_hbm) A.release(p);
+    // Pages that evictions and demotions vacate are handed out again only when nothing else is free: a block
+    // whose old pages stay untouched can leave HBM beside the following steps and be read in place meanwhile.
+    std::vector<int64_t> held;
+    auto end_phase = [&](bool hold = false) {
+      for (int64_t p : free_hbm) {
+        if (hold) held.push_back(p);
+        else A.release(p);
+      }
       for (auto &pr : free_host) H.release(pr.first, pr.second);
       free_hbm.clear();
       free_host.clear();
+    };
+    auto take_page = [&]() -> int32_t {
+      int32_t p = A.alloc_below(ring_first);
+      if (p < 0 && !held.empty()) {
+        for (int64_t h : held) A.release(h);
+        held.clear();
+        p = A.alloc_below(ring_first);
+      }
+      return p;
     };
     // (a2) removable cache: paused blocks are evicted only where this plan needs the room — every
     //      paused layer with a page inside the new staging region, then, while the active resident
@@ -337,7 +368,7 @@ class HostState {
         const int64_t used = (int64_t)lk.pages.size();
         int64_t run = H.alloc(used);
         if (run < 0) return ORBIT_E_HOST_CAPACITY;
-        groups.push_back({(int)phases.size() - 1, layer, phases.back().size(), (size_t)used});
+        groups.push_back({(int)phases.size() - 1, layer, phases.back().size(), (size_t)used, -1, {}});
         for (int64_t i = 0; i < used; ++i) phases.back().push_back({OP_HBM_TO_HOST, lk.pages[i], run + i});
         for (int32_t p : lk.pages) free_hbm.push_back(p);
         evicted += used;
@@ -372,7 +403,7 @@ class HostState {
           }
       }
     }
-    end_phase();
+    end_phase(true);
     // (b) demotions HBM -> host
     phases.emplace_back();
     for (int r = 0; r < n_req; ++r)
@@ -382,7 +413,7 @@ class HostState {
         int64_t run = H.alloc(rb[r]);
         if (run < 0) return fail(ORBIT_E_HOST_CAPACITY, "host arena full or fragmented (demotion)");
         int64_t used = ceil_div(lk.len, P);
-        groups.push_back({(int)phases.size() - 1, l, phases.back().size(), (size_t)used});
+        groups.push_back({(int)phases.size() - 1, l, phases.back().size(), (size_t)used, r, lk.pages});
         for (int64_t i = 0; i < used; ++i) phases.back().push_back({OP_HBM_TO_HOST, lk.pages[i], run + i});
         to_host += used;
         for (int32_t p : lk.pages) free_hbm.push_back(p);
@@ -391,7 +422,7 @@ class HostState {
         lk.host_page0 = run;
         lk.host_cap = (int32_t)rb[r];
       }
-    end_phase();
+    end_phase(true);
     // (c) host runs that must grow
     phases.emplace_back();
     for (int r = 0; r < n_req; ++r)
@@ -420,7 +451,7 @@ class HostState {
         int64_t used = ceil_div(lk.len, P);
         for (size_t i = 0; i < lk.pages.size(); ++i) {
           if (lk.pages[i] < ring_first) continue;
-          int32_t np = A.alloc_below(ring_first);
+          int32_t np = take_page();
           if (np < 0) return fail(ORBIT_E_CAPACITY, "internal: no page below the staging region");
           taken.push_back(np);
           if ((int64_t)i < used) {
@@ -442,7 +473,7 @@ class HostState {
         bool promote = (lk.tier == 0);
         if (lk.tier != 1) lk.pages.clear();
         while ((int64_t)lk.pages.size() < rb[r]) {
-          int32_t np = A.alloc_below(ring_first);
+          int32_t np = take_page();
           if (np < 0) return fail(ORBIT_E_CAPACITY, "internal: resident allocation failed");
           taken.push_back(np);
           lk.pages.push_back(np);
@@ -469,6 +500,9 @@ class HostState {
         lk.host_page0 = run;
         lk.host_cap = (int32_t)rb[r];
       }
+
+    for (int64_t h : held) A.release(h);
+    held.clear();
 
     // staging schedule: each layer's offloaded requests occupy one contiguous range; ranges are
     // laid out round-robin over the staging region; inside a range, smallest request first.
@@ -499,24 +533,34 @@ class HostState {
     }
 
     // Which blocks may leave HBM lazily: every source page below the staging region and not handed out
-    // again by this plan load.  Their copies move from `phases` to `deferred`, grouped by layer.
+    // again by this plan load.  Their copies move from `phases` to `deferred`, grouped by layer; for a block
+    // that stays readable in place, all but the copy of its last used page.
     std::vector<PageOp> lazy;
     std::vector<size_t> lazy_end(L, 0);
-    int64_t n_deferred = 0;
+    std::vector<int32_t> dual_count(L, 0);
+    int64_t n_deferred = 0, n_in_place = 0;
     if (!groups.empty()) {
       reuse_mark_.assign((size_t)arena_pages, 0);
       for (int32_t pg : taken) reuse_mark_[pg] = 1;
-      std::vector<uint8_t> is_lazy(groups.size(), 0);
+      auto untouched = [&](int64_t pg) { return pg < ring_first && !reuse_mark_[pg]; };
+      std::vector<size_t> n_lazy(groups.size(), 0);  // ops [first, first + n_lazy) of the group are deferred
       std::vector<size_t> per_layer(L, 0);
       for (size_t gi = 0; gi < groups.size(); ++gi) {
         const DemoteGroup &g = groups[gi];
-        bool ok = g.n > 0;
-        for (size_t i = 0; i < g.n && ok; ++i) {
-          const int64_t src = phases[g.phase][g.first + i].src;
-          ok = src < ring_first && !reuse_mark_[src];
+        const bool in_place = g.req >= 0 && !sh.zero_copy;
+        bool ok = g.n > (in_place ? 1u : 0u);
+        for (size_t i = 0; i < g.n && ok; ++i) ok = untouched(phases[g.phase][g.first + i].src);
+        if (!ok) continue;
+        n_lazy[gi] = in_place ? g.n - 1 : g.n;
+        per_layer[g.layer] += n_lazy[gi];
+        if (in_place) {  // the used pages, and as many of the reserved ones behind them as are still untouched
+          size_t keep = g.n;
+          while (keep < g.old_pages.size() && untouched(g.old_pages[keep])) ++keep;
+          LayerKV &lk = nw[g.req].layers[g.layer];
+          lk.dual_pages.assign(g.old_pages.begin(), g.old_pages.begin() + keep);
+          ++dual_count[g.layer];
+          n_in_place += (int64_t)g.n;
         }
-        is_lazy[gi] = ok;
-        if (ok) per_layer[g.layer] += g.n;
       }
       size_t at = 0;
       std::vector<size_t> cursor(L, 0);
@@ -528,14 +572,14 @@ class HostState {
       lazy.resize(at);
       std::vector<std::vector<uint8_t>> drop(phases.size());
       for (size_t gi = 0; gi < groups.size(); ++gi) {
-        if (!is_lazy[gi]) continue;
+        if (!n_lazy[gi]) continue;
         const DemoteGroup &g = groups[gi];
         if (drop[g.phase].empty()) drop[g.phase].assign(phases[g.phase].size(), 0);
-        for (size_t i = 0; i < g.n; ++i) {
+        for (size_t i = 0; i < n_lazy[gi]; ++i) {
           lazy[cursor[g.layer]++] = phases[g.phase][g.first + i];
           drop[g.phase][g.first + i] = 1;
         }
-        n_deferred += (int64_t)g.n;
+        n_deferred += (int64_t)n_lazy[gi];
       }
       for (size_t ph = 0; ph < phases.size(); ++ph) {
         if (drop[ph].empty()) continue;
@@ -550,6 +594,8 @@ class HostState {
     deferred = std::move(lazy);
     deferred_end = std::move(lazy_end);
     info.deferred_to_host_blocks = n_deferred;
+    info.in_place_blocks = n_in_place;
+    dual_in_layer = std::move(dual_count);
     hbm = std::move(A);
     host = std::move(H);
     reqs = std::move(nw);
@@ -625,19 +671,37 @@ class HostState {
     return ORBIT_OK;
   }
 
+  // The blocks of `layer` that were read in place become ordinary host blocks (their copies have landed, or
+  // whoever reads them next waits): `flipped` receives the request indices whose table row changed.
+  void flip_layer(int layer, std::vector<int> &flipped) {
+    flipped.clear();
+    for (size_t r = 0; r < reqs.size(); ++r) {
+      LayerKV &lk = reqs[r].layers[layer];
+      if (lk.dual_pages.empty()) continue;
+      lk.dual_pages.clear();
+      rebuild_row((int)r, layer);
+      flipped.push_back((int)r);
+    }
+    dual_in_layer[layer] = 0;
+  }
+
   void rebuild_tables() {
     for (size_t r = 0; r < reqs.size(); ++r)
-      for (int l = 0; l < sh.L; ++l) {
-        const LayerKV &lk = reqs[r].layers[l];
-        int32_t *row = table_row((int)r, l);
-        for (int i = 0; i < sh.cap_pages; ++i) row[i] = 0;
-        if (lk.tier == 1)
-          for (size_t i = 0; i < lk.pages.size(); ++i) row[i] = lk.pages[i];
-        else if (sh.zero_copy)  // host page p is written as ~p: the kernel reads it in place
-          for (int i = 0; i < reqs[r].reserved; ++i) row[i] = ~(int32_t)(lk.host_page0 + i);
-        else
-          for (int i = 0; i < reqs[r].reserved; ++i) row[i] = lk.stage_page0 + i;
-      }
+      for (int l = 0; l < sh.L; ++l) rebuild_row((int)r, l);
+  }
+
+  void rebuild_row(int r, int l) {
+    const LayerKV &lk = reqs[r].layers[l];
+    int32_t *row = table_row(r, l);
+    for (int i = 0; i < sh.cap_pages; ++i) row[i] = 0;
+    if (!lk.dual_pages.empty())
+      for (size_t i = 0; i < lk.dual_pages.size(); ++i) row[i] = lk.dual_pages[i];
+    else if (lk.tier == 1)
+      for (size_t i = 0; i < lk.pages.size(); ++i) row[i] = lk.pages[i];
+    else if (sh.zero_copy)  // host page p is written as ~p: the kernel reads it in place
+      for (int i = 0; i < reqs[r].reserved; ++i) row[i] = ~(int32_t)(lk.host_page0 + i);
+    else
+      for (int i = 0; i < reqs[r].reserved; ++i) row[i] = lk.stage_page0 + i;
   }
 
   // ------------------------------------------------------------------------------ work list

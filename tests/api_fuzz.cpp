@@ -63,7 +63,7 @@ int main(int argc, char **argv) {
     for (int64_t id : order)
       for (int l = 0; l < L; ++l) {
         int32_t n = -1, tier = -1;
-        if (orbit_get_pages(ctx, id, l, &tier, nullptr, &n, nullptr, 0) < 0 || n != len[id] || (tier != 0 && tier != 1)) return false;
+        if (orbit_get_pages(ctx, id, l, &tier, nullptr, &n, nullptr, 0) < 0 || n != len[id] || tier < 0 || tier > 2) return false;
       }
     return true;
   };
@@ -114,6 +114,7 @@ int main(int argc, char **argv) {
         orbit_plan_info info;
         CHECK(orbit_get_plan_info(ctx, &info) == ORBIT_OK);
         CHECK(info.resident_blocks + info.staging_blocks <= info.budget_blocks && info.n_requests == (int)ids.size());
+        CHECK(info.in_place_blocks >= 0 && info.in_place_blocks <= info.moved_to_host_blocks);
         CHECK(info.deferred_to_host_blocks >= 0 &&
               info.deferred_to_host_blocks <= info.moved_to_host_blocks + info.evicted_blocks);
         CHECK(lengths_match());

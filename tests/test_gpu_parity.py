@@ -375,6 +375,122 @@ def test_plan_switches_between_steps_without_host_sync():
         _check(a[S - 1, layer], None, o.attention(layer, S - 1))
 
 
+def _step_inputs(w, S, dev):
+    """q [S][L][B][Hq][D], k_new / v_new [S][L][B][Hkv][D] of the S tokens every request appends."""
+    from workloads import gen_q_steps, gen_kv
+    L, B = w.n_layers, w.n_req
+    q = torch.stack([torch.stack([gen_q_steps(w.seed, l, int(rid), 0, S, w.n_q_heads, w.head_dim, dev)
+                                  for rid in w.req_ids], dim=1) for l in range(L)], dim=1).contiguous()
+    kv = [[gen_kv(w.seed, l, int(rid), int(w.ctx_len[r]), S, w.n_kv_heads, w.head_dim, dev)
+           for r, rid in enumerate(w.req_ids)] for l in range(L)]
+    k_new = torch.stack([torch.stack([kv[l][r][0] for r in range(B)], dim=1) for l in range(L)], dim=1).contiguous()
+    v_new = torch.stack([torch.stack([kv[l][r][1] for r in range(B)], dim=1) for l in range(L)], dim=1).contiguous()
+    return q, k_new, v_new
+
+
+@pytest.mark.parametrize("sync_after_switch", [True, False])
+def test_demoted_blocks_are_read_in_place_until_their_copies_have_landed(sync_after_switch):
+    """A switch that demotes blocks whose pages nobody needs yet: the next steps read them where they were (no
+    prefetch for them, the new tokens go into the old pages and the host run), and once the copies have landed
+    the layer's next prefetch takes them over.  Every step equals, bit for bit, a run under the same placement
+    from the start; at the end the host copy read back equals the generator's tokens."""
+    h = _harness()
+    from workloads import gen_kv
+    L, S = 3, 6
+    w = _custom([700, 1500, 300, 40], L=L, steps=S)
+    B = w.n_req
+    ones = np.ones((B, L), np.uint8)
+    x = ones.copy()
+    x[0, 1] = x[1, 1] = x[2, 0] = x[1, 2] = x[3, 2] = 0
+    kw = dict(prefetch_slots=2, budget_pages=int(w.blocks(S).sum()) * L * 3, host_pages=int(w.blocks(S).sum()) * L * 2,
+              decode_window=S)
+
+    def run(switching: bool):
+        g = h.GpuRun(w, placement=ones if switching else x, **kw)
+        q, k_new, v_new = _step_inputs(w, S, g.dev)
+        outs = torch.zeros((S, L, B, w.n_q_heads, w.head_dim), dtype=torch.bfloat16, device=g.dev)
+        torch.cuda.synchronize()
+        tiers = []
+        for s in range(S):
+            if switching and s == 1:
+                g.ctx.plan_load(w.req_ids, w.ctx_len + s, x)
+                info = g.ctx.get_plan_info()
+                # blocks of 44+1, 94+1 (twice), 19+1 pages leave; the 3-page block of the last request too
+                assert info["in_place_blocks"] == info["moved_to_host_blocks"] > 0
+                assert info["deferred_to_host_blocks"] == info["moved_to_host_blocks"] - 5
+                assert all(g.ctx.get_pages(int(w.req_ids[r]), l)["tier"] == 2 for r, l in ((0, 1), (1, 1), (2, 0), (1, 2), (3, 2)))
+                if sync_after_switch:
+                    torch.cuda.synchronize()
+            g.ctx.step(q[s], k_new[s], v_new[s], outs[s])
+            if switching and s >= 1:
+                tiers.append([g.ctx.get_pages(int(w.req_ids[r]), l)["tier"] for r, l in ((0, 1), (1, 1), (2, 0), (1, 2), (3, 2))])
+            if switching and s == 2:
+                torch.cuda.synchronize()                    # by now every copy has landed: the next step takes all over
+        g.cs.synchronize()
+        g.xs.synchronize()
+        res = outs.cpu()
+        if switching:
+            if sync_after_switch:
+                assert tiers[0] == [0] * 5                  # the copies had landed before the first step asked
+            assert tiers[-1] == [0] * 5 and tiers[2] == [0] * 5
+            for r, l in ((1, 1), (3, 2)):                   # the host copy holds old and new tokens alike
+                n = int(w.ctx_len[r]) + S
+                k, v = g.read_kv(r, l, 0, n)
+                kw_, vw_ = gen_kv(w.seed, l, int(w.req_ids[r]), 0, n, w.n_kv_heads, w.head_dim, g.dev)
+                assert torch.equal(k.view(torch.int16), kw_.view(torch.int16))
+                assert torch.equal(v.view(torch.int16), vw_.view(torch.int16))
+        g.close()
+        return res
+
+    a, b = run(True), run(False)
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    o = h.OracleRun(w, extra_tokens=S)
+    for _ in range(S):
+        o.append_all()
+    for layer in range(L):
+        _check(a[S - 1, layer], None, o.attention(layer, S - 1))
+
+
+def test_a_block_read_in_place_moves_before_it_outgrows_its_old_pages():
+    """The pages a demoted block had were reserved under the OLD plan; when the next token would not fit them the
+    block is taken over at once (the compute stream waits for the copies), with no host-side wait anywhere."""
+    h = _harness()
+    L, S = 2, 12
+    w = _custom([120, 250], L=L, steps=S)
+    ones = np.ones((2, L), np.uint8)
+    x = np.array([[1, 0], [0, 1]], np.uint8)
+    W = 8                                               # 120 + 8 = 128 tokens = exactly 8 pages under the first plan
+
+    def run(switching: bool):
+        g = h.GpuRun(w, placement=ones if switching else x, prefetch_slots=1, budget_pages=600, host_pages=400,
+                     decode_window=W, max_tokens=400)
+        q, k_new, v_new = _step_inputs(w, S, g.dev)
+        outs = torch.zeros((S, L, 2, w.n_q_heads, w.head_dim), dtype=torch.bfloat16, device=g.dev)
+        torch.cuda.synchronize()
+        for s in range(S):
+            if s == 8:                                  # the window is used up: both runs renew it here, one of them demotes
+                g.ctx.plan_load(w.req_ids, w.ctx_len + s, x)
+                if switching:
+                    p = g.ctx.get_pages(int(w.req_ids[0]), 1)
+                    assert p["tier"] == 2 and len(p["pages"]) == 8   # 128 tokens held: a ninth page is not in the old list
+            g.ctx.step(q[s], k_new[s], v_new[s], outs[s])
+            if switching and s == 8:
+                assert g.ctx.get_pages(int(w.req_ids[0]), 1)["tier"] == 0
+        g.cs.synchronize()
+        g.xs.synchronize()
+        res = outs.cpu()
+        g.close()
+        return res
+
+    a, b = run(True), run(False)
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    o = h.OracleRun(w, extra_tokens=S)
+    for _ in range(S):
+        o.append_all()
+    for layer in range(L):
+        _check(a[S - 1, layer], None, o.attention(layer, S - 1))
+
+
 @pytest.mark.parametrize("seed", range(10))
 def test_random_shapes_lengths_and_placements(seed):
     """Seeded random head shapes, chunk sizes, staging-range counts, lengths and placements; odd

@@ -144,7 +144,7 @@ def test_host_arena_capacity():
 def _layout_invariants(c, ids, L):
     info = c.get_plan_info()
     first, nstage = info["staging_first_page"], info["staging_blocks"]
-    seen_hbm, host_runs = set(), []
+    seen_hbm, host_runs, in_place = set(), [], set()
     per_layer_stage = {l: [] for l in range(L)}
     for r in ids:
         for l in range(L):
@@ -154,12 +154,17 @@ def _layout_invariants(c, ids, L):
                 assert all(0 <= q < first for q in pages)
                 assert not (seen_hbm & set(pages))
                 seen_hbm |= set(pages)
+            elif p["tier"] == 2:                # on its way to the host, read in place: pages it no longer owns
+                assert all(0 <= q < first for q in pages)
+                in_place |= set(pages)
+                host_runs.append((p["host_first_page"], p["host_first_page"] + 1))
             else:
                 assert pages == list(range(pages[0], pages[0] + len(pages)))       # contiguous staging range
                 assert first <= pages[0] and pages[-1] < first + nstage
                 per_layer_stage[l].append((pages[0], pages[-1]))
                 host_runs.append((p["host_first_page"], p["host_first_page"] + len(pages)))
     assert len(seen_hbm) == info["resident_blocks"]
+    assert not (seen_hbm & in_place)                        # nothing this plan owns was handed a page still read in place
     for l, spans in per_layer_stage.items():                # requests of one layer never share staging pages
         spans.sort()
         assert all(a[1] < b[0] for a, b in zip(spans, spans[1:]))
@@ -542,7 +547,8 @@ def test_demotions_are_deferred_unless_their_pages_are_needed_at_once():
     x[:, 1] = 0                                                # demote layer 1 of every request: 40 blocks
     c.plan_load(list(range(B)), n, x)
     info = c.get_plan_info()
-    assert info["moved_to_host_blocks"] == 40 and info["deferred_to_host_blocks"] == 40
+    # a block that stays readable in place sends its last page at once (new tokens go there) and defers the rest
+    assert info["moved_to_host_blocks"] == 40 and info["deferred_to_host_blocks"] == 36 and info["in_place_blocks"] == 40
     assert info["relocated_blocks"] == 0
     # back to all-resident, then the same demotion in an arena with no slack: the staging region (40 pages) now
     # covers resident pages 120..159; what lies there must leave or move at once, the rest may still wait
@@ -557,19 +563,75 @@ def test_demotions_are_deferred_unless_their_pages_are_needed_at_once():
     moved_in = info["relocated_blocks"]
     assert moved_in > 0                                        # residents inside the region moved into freed pages
     assert info["deferred_to_host_blocks"] < 40                # ... so the blocks that freed those pages went at once
-    assert info["deferred_to_host_blocks"] % 10 == 0 and info["deferred_to_host_blocks"] <= 40 - 10 * in_region
+    assert info["deferred_to_host_blocks"] % 9 == 0 and info["deferred_to_host_blocks"] <= 36 - 9 * in_region
+    assert info["in_place_blocks"] == info["deferred_to_host_blocks"] // 9 * 10
     _layout_invariants(c, list(range(B)), L)
     # zero-copy mode has no staging region: every demotion whose pages nobody takes is deferred
     c = ctx(L=L, hbm_pages=160, zero_copy=True)
     c.plan_load(list(range(B)), n, ones)
     c.plan_load(list(range(B)), n, x)
     assert c.get_plan_info()["deferred_to_host_blocks"] == 40
-    # a promotion in the same switch takes the lowest free pages, some of them freed by this switch's own
-    # demotions: the blocks that held those go out at once, the others may wait
+    # a promotion in the same switch takes pages that were free before it; the pages this switch's own demotions
+    # vacate are handed out only when nothing else is left, so those blocks may all wait
     y = x.copy()
     y[:, 1] = 1
     y[:, 2] = 0                                                # layer 1 back in, layer 2 out
     c.plan_load(list(range(B)), n, y)
     info = c.get_plan_info()
     assert info["moved_to_host_blocks"] == 40 and info["moved_to_hbm_blocks"] == 40
-    assert 0 <= info["deferred_to_host_blocks"] < 40 and info["deferred_to_host_blocks"] % 10 == 0
+    assert info["deferred_to_host_blocks"] == 40 and info["in_place_blocks"] == 0
+    # ... and when nothing else is left: a new resident request (30 blocks) arrives while layer 2 comes back (40
+    # blocks, 40 pages are free) and layer 3 leaves; the new request can only get pages that layer 3 vacates
+    z = y.copy()
+    z[:, 2] = 1
+    z[:, 3] = 0
+    c2 = ctx(L=L, hbm_pages=160, zero_copy=True, max_req=8)
+    c2.plan_load(list(range(B)), n, ones)
+    c2.plan_load(list(range(B)), n, x)
+    c2.plan_load(list(range(B)), n, y)
+    c2.plan_load(list(range(B)) + [9], n + [160], np.vstack([z, np.array([[1, 1, 1, 0]], dtype=np.uint8)]))
+    info = c2.get_plan_info()
+    assert info["moved_to_host_blocks"] == 40 and info["moved_to_hbm_blocks"] == 40
+    assert info["deferred_to_host_blocks"] == 10               # three of the four vacated blocks were taken at once
+
+
+def test_demoted_blocks_are_read_in_place_until_their_copies_have_landed():
+    """Host-only contexts have no copies in flight: the hand-over to the staging schedule happens at the layer's
+    first prefetch.  Until then the page list attention reads is the one the block had in HBM."""
+    L, B = 3, 3
+    n = [160, 100, 47]
+    ones = np.ones((B, L), dtype=np.uint8)
+    c = ctx(L=L, hbm_pages=2000, window=40)
+    ids = [5, 6, 7]
+    c.plan_load(ids, n, ones)
+    before = {(r, l): [int(p) for p in c.get_pages(r, l)["pages"]] for r in ids for l in range(L)}
+    x = ones.copy()
+    x[0, 1] = x[2, 1] = x[1, 2] = 0
+    c.plan_load(ids, n, x)
+    info = _layout_invariants(c, ids, L)
+    assert info["in_place_blocks"] == 10 + 3 + 7 and info["deferred_to_host_blocks"] == 9 + 2 + 6
+    for r, l in ((5, 1), (7, 1), (6, 2)):
+        p = c.get_pages(r, l)
+        assert p["tier"] == 2 and [int(v) for v in p["pages"]] == before[(r, l)]   # used and reserved pages alike
+    assert c.get_pages(6, 1)["tier"] == 1
+    # the copy schedule still has their staging ranges; the first prefetch of a layer switches its blocks over
+    c.kv_prefetch(1)
+    for r in (5, 7):
+        p = c.get_pages(r, 1)
+        assert p["tier"] == 0 and int(p["pages"][0]) >= info["staging_first_page"]
+    assert c.get_pages(6, 2)["tier"] == 2
+    c.decode_attention(1, None, None)
+    # a plan load settles whatever is still read in place
+    c.plan_load(ids, n, x)
+    assert c.get_pages(6, 2)["tier"] == 0 and c.get_plan_info()["in_place_blocks"] == 0
+    _layout_invariants(c, ids, L)
+
+
+def test_a_single_block_demotion_is_not_read_in_place():
+    L = 2
+    c = ctx(L=L, hbm_pages=500)
+    c.plan_load([1], [9], np.ones((1, L), dtype=np.uint8))
+    c.plan_load([1], [9], np.array([[1, 0]], dtype=np.uint8))
+    info = c.get_plan_info()
+    assert info["moved_to_host_blocks"] == 1 and info["deferred_to_host_blocks"] == 0 and info["in_place_blocks"] == 0
+    assert c.get_pages(1, 1)["tier"] == 0

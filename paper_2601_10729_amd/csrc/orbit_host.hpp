@@ -777,8 +777,10 @@ class HostState {
     }
     const int nseg = (int)(segs.size() / 4);
     if (nseg > max_segments()) return fail(ORBIT_E_CAPACITY, "work list larger than the buffers sized at creation");
-    std::stable_sort(work_sort_.begin(), work_sort_.end(),
-                     [](const std::pair<int32_t, int32_t> &a, const std::pair<int32_t, int32_t> &b) { return a.first > b.first; });
+    // (length descending, index ascending) is a total order: std::sort works in place, no temporary buffer
+    std::sort(work_sort_.begin(), work_sort_.end(), [](const std::pair<int32_t, int32_t> &a, const std::pair<int32_t, int32_t> &b) {
+      return a.first != b.first ? a.first > b.first : a.second < b.second;
+    });
     work_workers = (nseg + 7) & ~7;
     work_order.assign(work_workers, -1);
     for (int i = 0; i < nseg; ++i) {

@@ -305,6 +305,32 @@ def test_chunk_choice_examples():
         assert len(items) == sum(-(-v // want) for v in n)
 
 
+@pytest.mark.parametrize("Hkv", [1, 2, 8, 16, 128])
+def test_work_list_always_fits_the_buffers_sized_at_creation(Hkv):
+    """The buffers hold max_requests x ceil(max_tokens / 4096) + 2 x (256 / Hkv) + max_requests segments; the
+    chunk choice never produces more (a smaller chunk is only taken when the next larger one leaves units idle)."""
+    rng = np.random.default_rng(Hkv)
+    max_req, max_tokens, L = 12, 20000, 1
+    page = 2 * Hkv * 16 * 128 * 2
+    c = OrbitContext(n_layers=L, n_q_heads=Hkv, n_kv_heads=Hkv, max_requests=max_req, max_tokens_per_request=max_tokens,
+                     host_only=True, hbm_arena_bytes=page * (max_req * (max_tokens // 16 + 2)), host_arena_bytes=page)
+    bound = max_req * -(-max_tokens // 4096) + 2 * max(1, 256 // Hkv) + max_req
+    nid = 0
+    for trial in range(60):
+        B = int(rng.integers(1, max_req + 1))
+        kind = trial % 3
+        n = (rng.integers(1, 600, size=B) if kind == 0 else
+             rng.integers(1, max_tokens + 1, size=B) if kind == 1 else
+             np.maximum(1, (2.0 ** rng.uniform(0, np.log2(max_tokens), size=B)).astype(np.int64)))
+        ids = list(range(nid, nid + B))
+        nid += B
+        c.plan_load(ids, n, np.ones((B, L), dtype=np.uint8))
+        items = c.get_work_items(0)
+        assert len(items) <= bound
+        C = _expected_chunk([int(v) for v in n], Hkv)
+        assert len(items) == sum(-(-int(v) // C) for v in n)
+
+
 def test_attention_on_an_empty_request_is_an_error():
     c = ctx(L=1)
     c.plan_load([1, 2], [0, 5], np.ones((2, 1), dtype=np.uint8))

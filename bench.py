@@ -15,6 +15,7 @@ an SLO replay of the measured step times, and compact records of the other three
 """
 import argparse
 import dataclasses
+import gc
 import json
 import os
 import sys
@@ -362,9 +363,17 @@ def main():
     while host is None:
         try:
             host = torch.empty(host_bytes, dtype=torch.uint8, pin_memory=True)
+            # the library and torch pin small buffers of their own later on (page-table mirrors, work lists): make
+            # sure the machine still has room for them, or the larger workloads fail half-way through the run
+            probe = torch.empty(1 << 30, dtype=torch.uint8, pin_memory=True)
+            del probe
+            torch._C._host_emptyCache()
         except RuntimeError:                 # this machine pins less than asked for: take what it gives, and say so
+            host = None
+            gc.collect()
             torch.cuda.empty_cache()
-            host_bytes = host_bytes * 3 // 4
+            torch._C._host_emptyCache()
+            host_bytes -= 4 << 30
             if (host_blocks + 8) * w.page_bytes > host_bytes:
                 raise
     pinned_gib = host_bytes / (1 << 30)

@@ -179,3 +179,65 @@ def test_full_size_layer_every_element_against_oracle():
     row = np.sqrt((d * d).sum(-1) / (want * want).sum(-1))
     assert row.max() <= 2 * REL_L2, float(row.max())
     g.close()
+
+
+def test_steps_run_in_place_while_a_large_demotion_is_in_flight():
+    """A switch that sends 1 GB of KV to the host, with steps enqueued right behind it and no host-side wait: the
+    copies take tens of milliseconds, the steps a fraction of one, so several steps read the demoted blocks where
+    they were, append into them and into the host runs, and later steps take the blocks over layer by layer.  Every
+    step equals, bit for bit, a run that had the placement from the start; sampled groups are checked against the
+    oracle at the end."""
+    import time
+    import harness as h
+    from workloads import gen_q_steps, gen_kv
+    L, S = 4, 10
+    base = make_workload("llama8b_b16", 0, n_req=4)
+    lens = np.array([20000, 17001, 23000, 9000], dtype=base.ctx_len.dtype)
+    ones = np.ones((4, L), dtype=np.uint8)
+    x = ones.copy()
+    x[:, 1:] = 0                                           # three of four layers leave HBM: 0.85 GB
+    w = dataclasses.replace(base, n_layers=L, ctx_len=lens, placement=x, steps=S)
+    blocks = int(w.blocks(S).sum())
+    kw = dict(prefetch_slots=2, budget_pages=blocks * L + 2 * blocks + 64, host_pages=blocks * L + 64, decode_window=S,
+              max_tokens=int(lens.max()) + S + 16)
+
+    def inputs(dev):
+        B = w.n_req
+        q = torch.stack([torch.stack([gen_q_steps(w.seed, l, int(rid), 0, S, w.n_q_heads, w.head_dim, dev)
+                                      for rid in w.req_ids], dim=1) for l in range(L)], dim=1).contiguous()
+        kv = [[gen_kv(w.seed, l, int(rid), int(lens[r]), S, w.n_kv_heads, w.head_dim, dev)
+               for r, rid in enumerate(w.req_ids)] for l in range(L)]
+        k_new = torch.stack([torch.stack([kv[l][r][0] for r in range(B)], dim=1) for l in range(L)], dim=1).contiguous()
+        v_new = torch.stack([torch.stack([kv[l][r][1] for r in range(B)], dim=1) for l in range(L)], dim=1).contiguous()
+        return q, k_new, v_new
+
+    def run(switching: bool):
+        g = h.GpuRun(w, placement=ones if switching else x, **kw)
+        q, k_new, v_new = inputs(g.dev)
+        outs = torch.zeros((S, L, w.n_req, w.n_q_heads, w.head_dim), dtype=torch.bfloat16, device=g.dev)
+        torch.cuda.synchronize()
+        in_place = []
+        for s in range(S):
+            if switching and s == 2:
+                g.ctx.plan_load(w.req_ids, lens + s, x)
+                info = g.ctx.get_plan_info()
+                assert info["in_place_blocks"] == info["moved_to_host_blocks"] == 3 * int(np.ceil((lens + s) / 16).sum())
+                assert info["deferred_to_host_blocks"] == info["in_place_blocks"] - 12      # one page per block went at once
+            g.ctx.step(q[s], k_new[s], v_new[s], outs[s])
+            if switching and s >= 2:
+                in_place.append(sum(g.ctx.get_pages(int(rid), l)["tier"] == 2 for rid in w.req_ids for l in range(L)))
+            if switching and s == 6:
+                time.sleep(0.2)                              # the copies (about 20 ms) have landed by now
+        g.cs.synchronize()
+        g.xs.synchronize()
+        res = outs.cpu()
+        lens_end = lens.astype(np.int64) + S
+        if switching:
+            assert in_place[0] == 12                         # the step right behind the switch read everything in place
+            assert in_place[-1] == 0                         # ... and by the end every block has been taken over
+            _check_groups(h, w, [outs[S - 1][l] for l in range(L)], None, lens_end, [(1, 0, 3), (2, 2, 7), (3, 3, 0), (0, 1, 5)], step=S - 1)
+        g.close()
+        return res, in_place
+
+    (a, in_place), (b, _) = run(True), run(False)
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16)), in_place

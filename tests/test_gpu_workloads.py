@@ -55,7 +55,8 @@ def test_llama70b_shape_group_of_eight():
     import harness as h
     w = _two_layer_slice("llama70b", steps=1)
     assert w.n_req == 32 and w.n_q_heads // w.n_kv_heads == 8
-    g = h.GpuRun(w, prefetch_slots=1)
+    host_blocks = int(((1 - w.placement.astype(np.int64)) * w.blocks(1)[:, None]).sum())
+    g = h.GpuRun(w, prefetch_slots=1, host_pages=host_blocks + 8)      # pin only what this placement streams
     outs, outs32 = [], []
     for layer in range(2):
         o, o32 = g.attention(layer)
@@ -94,7 +95,8 @@ def test_heavy_mixed_under_its_byte_budget():
     import harness as h
     w = make_workload("heavy_mixed", 0, n_layers=8, steps=1)
     assert w.n_req == 64 and w.hbm_budget_bytes == 40 * 10**9 * 8 // 32
-    g = h.GpuRun(w, prefetch_slots=1, budget_pages=w.hbm_budget_bytes // w.page_bytes)
+    host_blocks = int(((1 - w.placement.astype(np.int64)) * w.blocks(1)[:, None]).sum())
+    g = h.GpuRun(w, prefetch_slots=1, budget_pages=w.hbm_budget_bytes // w.page_bytes, host_pages=host_blocks + 8)
     info = g.ctx.get_plan_info()
     assert info["resident_blocks"] + info["staging_blocks"] <= info["budget_blocks"] and info["host_blocks"] > 0
     out, stats = g.step(0, want_stats=True)

@@ -105,7 +105,6 @@ struct orbit_ctx {
   std::vector<int> flipped_tmp;       // scratch of flip_in_place_blocks
   uint8_t *static_scratch = nullptr;  // this device's copy of the library's static split-K scratch
   int64_t n_segs = 0;
-  int32_t seg_off = 0;                // where the segments start in the uploaded buffer (after the span table)
   bool items_valid = false;
   float scale_log2 = 0.f;
   AttnParams attn_args{};               // launch arguments, kept here because of their size
@@ -271,15 +270,23 @@ int ensure_work_items(orbit_ctx *c, int layer) {
   int rc = hs.build_work_items(layer, segs);
   if (rc) return set_err(c, rc, hs.err);
   c->n_segs = (int64_t)segs.size() / 4;
-  c->seg_off = (int32_t)hs.work_order.size();
   if (!c->host_only) {
     const int b = c->items_buf = (c->items_buf + 1) % kItemBufs;
     HIPCHECK(c, hipEventSynchronize(c->ev_items[b]));  // last upload from this buffer is long done
     int32_t *dst = c->h_items_pinned[b];
-    std::memcpy(dst, hs.work_order.data(), hs.work_order.size() * sizeof(int32_t));
-    std::memcpy(dst + c->seg_off, segs.data(), segs.size() * sizeof(int32_t));
-    HIPCHECK(c, hipMemcpyAsync(c->d_items, dst, ((size_t)c->seg_off + segs.size()) * sizeof(int32_t),
-                               hipMemcpyHostToDevice, c->cs));
+    for (int w = 0; w < hs.work_workers; ++w) {  // launch order; the kernel finds a segment with one load
+      const int s = hs.work_order[w];
+      if (s < 0) {
+        dst[4 * w] = -1;
+        dst[4 * w + 1] = dst[4 * w + 2] = dst[4 * w + 3] = 0;
+      } else {
+        dst[4 * w] = segs[4 * (size_t)s];
+        dst[4 * w + 1] = segs[4 * (size_t)s + 1];
+        dst[4 * w + 2] = segs[4 * (size_t)s + 2];
+        dst[4 * w + 3] = s;
+      }
+    }
+    HIPCHECK(c, hipMemcpyAsync(c->d_items, dst, (size_t)hs.work_workers * 4 * sizeof(int32_t), hipMemcpyHostToDevice, c->cs));
     HIPCHECK(c, hipEventRecord(c->ev_items[b], c->cs));
   }
   c->items_key = key;  // same capacity after the first call: no allocation
@@ -354,7 +361,6 @@ int attention_impl(orbit_ctx *c, int layer, const void *q, void *out, float *out
     ap.Hkv = sh.Hkv;
     ap.G = sh.G;
     ap.n_workers = hs.work_workers;
-    ap.seg_off = c->seg_off;
     ap.scale_log2 = c->scale_log2;
     for (int r = 0; r < nreq; ++r) {
       const LayerKV &lk = hs.reqs[r].layers[layer];
@@ -835,7 +841,7 @@ int orbit_create(const orbit_config *cfg, orbit_ctx **out) try {
   }
   c->seg_cap = c->hs.max_segments();
   c->slots = c->seg_cap * sh.Hkv;
-  const size_t items_words = (size_t)(c->seg_cap + 8) + (size_t)c->seg_cap * 4;
+  const size_t items_words = (size_t)(c->seg_cap + 8) * 4;
   if (!host_only) {  // storage of the work-list builder, so that attention calls do not touch the heap
     c->items_tmp.reserve((size_t)c->seg_cap * 4);
     c->hs.work_order.reserve((size_t)c->seg_cap + 8);

@@ -22,8 +22,8 @@ struct AttnParams {
   uint8_t *arena;           // device, page 0 of the HBM arena
   uint8_t *host;            // device-visible page 0 of the pinned host arena, or NULL
   const int32_t *table;     // device [max_req][L][cap_pages] page ids; a negative id i names host page ~i
-  const int32_t *work;      // device: launch order [n_workers] (segment index, or -1 = padding), then (at seg_off) the
-                            // segments [n_segs][4] {request, first token (multiple of 32), tokens, unused}
+  const int32_t *work;      // device [n_workers][4]: the segments in launch order, {request, first token (multiple
+                            // of 32), tokens, segment index}; request -1 = padding
   const uint16_t *q;        // device [n_req][Hq][128] bf16
   float *pacc;              // device [n_segs * Hkv][G][128] un-normalised partial outputs; slot = segment * Hkv + kv head
   float *pml;               // device [n_segs * Hkv][2][16] partial (max, sum) in log2 units
@@ -34,7 +34,6 @@ struct AttnParams {
   int64_t page_bytes;
   int32_t L, layer, cap_pages, Hq, Hkv, G;
   int32_t n_workers;        // multiple of 8; the grid is n_workers * Hkv workgroups
-  int32_t seg_off;          // index of the first segment entry in `work`
   float scale_log2;         // softmax scale * log2(e)
   AttnReq req[kMaxRequests];
 };

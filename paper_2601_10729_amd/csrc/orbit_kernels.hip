@@ -230,11 +230,10 @@ __global__ __launch_bounds__(256, 1) void attention_kernel(const AttnParams p) {
   // workgroup b runs on XCD b mod 8: the Hkv heads of a segment, which share its pages, sit 8 workgroups apart
   const int b = blockIdx.x, jj = b >> 3;
   const int g = jj % p.Hkv;
-  const int seg = p.work[(jj / p.Hkv) * 8 + (b & 7)];
-  if (seg < 0) return;  // padding of the launch order to a multiple of 8
+  const int32_t *it = p.work + (int64_t)((jj / p.Hkv) * 8 + (b & 7)) * 4;
+  const int r = it[0], tok0 = it[1], seg = it[3];
+  if (r < 0) return;  // padding of the launch order to a multiple of 8
   const int64_t head_off = (int64_t)g * kTileBytes;
-  const int32_t *it = p.work + p.seg_off + (int64_t)seg * 4;
-  const int r = it[0], tok0 = it[1];
   const int n = p.req[r].n_tok;
   const bool single = p.req[r].n_parts == 1;
   const int span = min(it[2], n - tok0);

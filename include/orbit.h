@@ -178,9 +178,9 @@ ORBIT_API int orbit_plan_check(int32_t n_req, int32_t n_layers, int32_t page_tok
  * landed, attention reads such blocks of active requests where they were (orbit_plan_info.in_place_blocks:
  * their old pages are not handed out before the next plan load), a step's new token is written there and into
  * the host run, and the layer is not prefetched for them; the first prefetch of the layer issued after its
- * copies have completed switches them to the staging region.  Calls that need the host copy itself
- * (orbit_kv_fill, orbit_kv_read, orbit_kv_append, a decode window that outgrows the old pages, the zero-copy
- * mode) and the next plan load wait for the copies stream-side.
+ * copies have completed (in the zero-copy mode: the first attention call) switches them to the staging region
+ * (to their host pages).  Calls that need the host copy itself (orbit_kv_fill, orbit_kv_read, orbit_kv_append, a
+ * decode window that outgrows the old pages) and the next plan load wait for the copies stream-side.
  * ORBIT_E_STATE if a prefetched layer has not been attended yet. */
 ORBIT_API int orbit_plan_load(orbit_ctx *ctx, int32_t n_req, const int64_t *req_ids, const int32_t *ctx_len,
                     const uint8_t *placement_bitmap, int64_t hbm_budget_bytes);

@@ -163,13 +163,15 @@ int wait_deferred(orbit_ctx *c, int layer, bool on_copy_stream) {
 // i.e. their page-table rows point into the staging region from here on (row uploads on the compute stream,
 // behind every launch enqueued so far) and the caller prefetches them.  force: do it now and make the compute
 // stream wait for the copies; also taken when a block's next token would not fit the pages it still has.
-int flip_in_place_blocks(orbit_ctx *c, int layer, bool force) {
+// grow: tokens the caller is about to add to every request of the layer before attending (1 in front of a step's
+// length bump, 0 behind it).
+int flip_in_place_blocks(orbit_ctx *c, int layer, bool force, int grow = 1) {
   HostState &hs = c->hs;
   if (!hs.dual_in_layer[layer]) return ORBIT_OK;
   const Shape &sh = hs.sh;
   for (const Req &q : hs.reqs) {
     const LayerKV &lk = q.layers[layer];
-    if (!lk.dual_pages.empty() && lk.len / sh.P >= (int64_t)lk.dual_pages.size()) force = true;
+    if (!lk.dual_pages.empty() && ceil_div((int64_t)lk.len + grow, sh.P) > (int64_t)lk.dual_pages.size()) force = true;
   }
   if (!force && !c->host_only) {
     const hipError_t e = hipEventQuery(c->ev_lazy[layer]);
@@ -329,9 +331,10 @@ int attention_impl(orbit_ctx *c, int layer, const void *q, void *out, float *out
     if (!c->host_only) HIPCHECK(c, hipStreamWaitEvent(c->cs, c->ev_ready[layer], 0));
     lb->consumed = true;
   }
-  // zero-copy reads of a host block whose copy may be in flight wait for it; in the staged mode such a block is
-  // read in place, and the append's write into its host run cannot meet a copy (its last page was copied at once)
-  if (sh.zero_copy && (rc = wait_deferred(c, layer, false))) return rc;
+  // a block whose copy to the host may be in flight is read in place, and the append's write into its host run
+  // cannot meet a copy (its last page was copied at once).  The staged mode hands such blocks over in the layer's
+  // prefetch; the zero-copy mode, which has none, here: the lengths already count the token of a fused append
+  if (sh.zero_copy && (rc = flip_in_place_blocks(c, layer, false, 0))) return rc;
   if (!c->host_only) {
     if (c->timing) HIPCHECK(c, hipEventRecord(c->t_attn0[layer], c->cs));
     AttnParams &ap = c->attn_args;  // the per-request part is rewritten below; the rest is cheap to refill
@@ -365,8 +368,8 @@ int attention_impl(orbit_ctx *c, int layer, const void *q, void *out, float *out
     for (int r = 0; r < nreq; ++r) {
       const LayerKV &lk = hs.reqs[r].layers[layer];
       ap.req[r].n_tok = lk.len;
-      // a staged block has a second home: the host run that the next step's prefetch reads
-      ap.req[r].host_page0 = (k_new && lk.tier == 0 && !sh.zero_copy) ? (int32_t)lk.host_page0 : -1;
+      // a staged block, and one still read in place, has a second home: its host run
+      ap.req[r].host_page0 = (k_new && lk.tier == 0 && (!sh.zero_copy || !lk.dual_pages.empty())) ? (int32_t)lk.host_page0 : -1;
       ap.req[r].n_parts = hs.work_n_parts[r];
     }
     HIPCHECK(c, launch_attention(ap, c->cs));

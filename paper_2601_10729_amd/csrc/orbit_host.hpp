@@ -200,8 +200,8 @@ class HostState {
   // those pages, the step's new token goes there and into the host run, and the layer is not prefetched for that
   // request, until the copy has landed and `flip_layer` hands the block over to the staging schedule.  So that
   // the new token never meets a copy in flight, the last used page of such a block is copied at once (it stays
-  // in `phases`) and only the pages before it are deferred.  (Not in the zero-copy mode, whose kernel reads the
-  // host run itself: there a deferred block is simply waited for.)
+  // in `phases`) and only the pages before it are deferred.  In the zero-copy mode the hand-over switches the
+  // row to the host pages instead of a staging range.
   std::vector<PageOp> deferred;          // sorted by layer
   std::vector<size_t> deferred_end;      // [L] end offset of layer l's ops in `deferred`
   std::vector<uint8_t> reuse_mark_;      // [arena_pages] scratch of the classification
@@ -547,7 +547,7 @@ class HostState {
       std::vector<size_t> per_layer(L, 0);
       for (size_t gi = 0; gi < groups.size(); ++gi) {
         const DemoteGroup &g = groups[gi];
-        const bool in_place = g.req >= 0 && !sh.zero_copy;
+        const bool in_place = g.req >= 0;
         bool ok = g.n > (in_place ? 1u : 0u);
         for (size_t i = 0; i < g.n && ok; ++i) ok = untouched(phases[g.phase][g.first + i].src);
         if (!ok) continue;

@@ -22,7 +22,7 @@ using namespace orbit;
   } while (0)
 
 static void check_layout(const HostState &hs) {
-  std::set<int32_t> seen;
+  std::set<int32_t> seen, in_place;
   std::vector<std::pair<int64_t, int64_t>> runs;
   auto visit = [&](const Req &q, bool active) {
     for (int l = 0; l < hs.sh.L; ++l) {
@@ -39,7 +39,14 @@ static void check_layout(const HostState &hs) {
         CHECK(lk.host_page0 >= 0 && lk.host_page0 + lk.host_cap <= hs.host_pages);
         CHECK(lk.host_cap >= ceil_div(lk.len, hs.sh.P));
         runs.push_back({lk.host_page0, lk.host_page0 + lk.host_cap});
-        if (active && hs.sh.zero_copy) {
+        if (active && !lk.dual_pages.empty()) {  // still read in place: the table row lists pages nobody owns any more
+          const int32_t *row = &hs.h_table[((size_t)(&q - hs.reqs.data()) * hs.sh.L + l) * hs.sh.cap_pages];
+          CHECK((int64_t)lk.dual_pages.size() >= ceil_div(lk.len, hs.sh.P));
+          for (size_t i = 0; i < lk.dual_pages.size(); ++i) {
+            CHECK(row[i] == lk.dual_pages[i] && row[i] >= 0 && row[i] < hs.info.staging_first_page);
+            CHECK(!hs.hbm.used[row[i]] && in_place.insert(row[i]).second);
+          }
+        } else if (active && hs.sh.zero_copy) {
           CHECK(lk.stage_page0 < 0 && hs.info.staging_blocks == 0 && hs.blocks.empty());
           const int32_t *row = &hs.h_table[((size_t)(&q - hs.reqs.data()) * hs.sh.L + l) * hs.sh.cap_pages];
           for (int i = 0; i < q.reserved; ++i) CHECK(~row[i] == lk.host_page0 + i);   // in-place host page ids
@@ -118,9 +125,21 @@ int main(int argc, char **argv) {
     } else if (!hs.reqs.empty()) {  // append one token everywhere when the window allows it
       bool room = true;
       for (auto &q : hs.reqs) room &= q.layers[0].len / sh.P < q.reserved;
-      if (room)
+      if (room) {
+        // what the step path does for blocks still read in place: hand a layer over when a block would outgrow the
+        // pages it has left (and, here, now and then as if its copies had landed)
+        std::vector<int> flipped;
+        for (int l = 0; l < sh.L && hs.has_plan; ++l) {
+          bool must = rnd(0, 3) == 0;
+          for (auto &q : hs.reqs) {
+            const LayerKV &lk = q.layers[l];
+            must |= !lk.dual_pages.empty() && ceil_div((int64_t)lk.len + 1, sh.P) > (int64_t)lk.dual_pages.size();
+          }
+          if (must && hs.dual_in_layer[l]) hs.flip_layer(l, flipped);
+        }
         for (auto &q : hs.reqs)
           for (auto &lk : q.layers) lk.len += 1;
+      }
     }
     if (hs.has_plan) {
       check_layout(hs);

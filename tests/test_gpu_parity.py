@@ -388,8 +388,9 @@ def _step_inputs(w, S, dev):
     return q, k_new, v_new
 
 
+@pytest.mark.parametrize("zero_copy", [False, True])
 @pytest.mark.parametrize("sync_after_switch", [True, False])
-def test_demoted_blocks_are_read_in_place_until_their_copies_have_landed(sync_after_switch):
+def test_demoted_blocks_are_read_in_place_until_their_copies_have_landed(sync_after_switch, zero_copy):
     """A switch that demotes blocks whose pages nobody needs yet: the next steps read them where they were (no
     prefetch for them, the new tokens go into the old pages and the host run), and once the copies have landed
     the layer's next prefetch takes them over.  Every step equals, bit for bit, a run under the same placement
@@ -403,7 +404,7 @@ def test_demoted_blocks_are_read_in_place_until_their_copies_have_landed(sync_af
     x = ones.copy()
     x[0, 1] = x[1, 1] = x[2, 0] = x[1, 2] = x[3, 2] = 0
     kw = dict(prefetch_slots=2, budget_pages=int(w.blocks(S).sum()) * L * 3, host_pages=int(w.blocks(S).sum()) * L * 2,
-              decode_window=S)
+              decode_window=S, zero_copy=zero_copy)
 
     def run(switching: bool):
         g = h.GpuRun(w, placement=ones if switching else x, **kw)
@@ -451,7 +452,8 @@ def test_demoted_blocks_are_read_in_place_until_their_copies_have_landed(sync_af
         _check(a[S - 1, layer], None, o.attention(layer, S - 1))
 
 
-def test_a_block_read_in_place_moves_before_it_outgrows_its_old_pages():
+@pytest.mark.parametrize("zero_copy", [False, True])
+def test_a_block_read_in_place_moves_before_it_outgrows_its_old_pages(zero_copy):
     """The pages a demoted block had were reserved under the OLD plan; when the next token would not fit them the
     block is taken over at once (the compute stream waits for the copies), with no host-side wait anywhere."""
     h = _harness()
@@ -463,7 +465,7 @@ def test_a_block_read_in_place_moves_before_it_outgrows_its_old_pages():
 
     def run(switching: bool):
         g = h.GpuRun(w, placement=ones if switching else x, prefetch_slots=1, budget_pages=600, host_pages=400,
-                     decode_window=W, max_tokens=400)
+                     decode_window=W, max_tokens=400, zero_copy=zero_copy)
         q, k_new, v_new = _step_inputs(w, S, g.dev)
         outs = torch.zeros((S, L, 2, w.n_q_heads, w.head_dim), dtype=torch.bfloat16, device=g.dev)
         torch.cuda.synchronize()

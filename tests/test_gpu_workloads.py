@@ -183,7 +183,8 @@ def test_full_size_layer_every_element_against_oracle():
     g.close()
 
 
-def test_steps_run_in_place_while_a_large_demotion_is_in_flight():
+@pytest.mark.parametrize("zero_copy", [False, True])
+def test_steps_run_in_place_while_a_large_demotion_is_in_flight(zero_copy):
     """A switch that sends 1 GB of KV to the host, with steps enqueued right behind it and no host-side wait: the
     copies take tens of milliseconds, the steps a fraction of one, so several steps read the demoted blocks where
     they were, append into them and into the host runs, and later steps take the blocks over layer by layer.  Every
@@ -201,7 +202,7 @@ def test_steps_run_in_place_while_a_large_demotion_is_in_flight():
     w = dataclasses.replace(base, n_layers=L, ctx_len=lens, placement=x, steps=S)
     blocks = int(w.blocks(S).sum())
     kw = dict(prefetch_slots=2, budget_pages=blocks * L + 2 * blocks + 64, host_pages=blocks * L + 64, decode_window=S,
-              max_tokens=int(lens.max()) + S + 16)
+              max_tokens=int(lens.max()) + S + 16, zero_copy=zero_copy)
 
     def inputs(dev):
         B = w.n_req

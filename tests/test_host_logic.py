@@ -592,11 +592,14 @@ def test_demotions_are_deferred_unless_their_pages_are_needed_at_once():
     assert info["deferred_to_host_blocks"] % 9 == 0 and info["deferred_to_host_blocks"] <= 36 - 9 * in_region
     assert info["in_place_blocks"] == info["deferred_to_host_blocks"] // 9 * 10
     _layout_invariants(c, list(range(B)), L)
-    # zero-copy mode has no staging region: every demotion whose pages nobody takes is deferred
+    # zero-copy mode has no staging region: every demotion whose pages nobody takes is deferred and read in place
     c = ctx(L=L, hbm_pages=160, zero_copy=True)
     c.plan_load(list(range(B)), n, ones)
     c.plan_load(list(range(B)), n, x)
-    assert c.get_plan_info()["deferred_to_host_blocks"] == 40
+    assert c.get_plan_info()["deferred_to_host_blocks"] == 36 and c.get_plan_info()["in_place_blocks"] == 40
+    assert c.get_pages(2, 1)["tier"] == 2
+    c.decode_attention(1, None, None)                          # no copies in flight in a host-only context: handed over
+    assert c.get_pages(2, 1)["tier"] == 0
     # a promotion in the same switch takes pages that were free before it; the pages this switch's own demotions
     # vacate are handed out only when nothing else is left, so those blocks may all wait
     y = x.copy()
@@ -605,7 +608,7 @@ def test_demotions_are_deferred_unless_their_pages_are_needed_at_once():
     c.plan_load(list(range(B)), n, y)
     info = c.get_plan_info()
     assert info["moved_to_host_blocks"] == 40 and info["moved_to_hbm_blocks"] == 40
-    assert info["deferred_to_host_blocks"] == 40 and info["in_place_blocks"] == 0
+    assert info["deferred_to_host_blocks"] == 36 and info["in_place_blocks"] == 40
     # ... and when nothing else is left: a new resident request (30 blocks) arrives while layer 2 comes back (40
     # blocks, 40 pages are free) and layer 3 leaves; the new request can only get pages that layer 3 vacates
     z = y.copy()
@@ -618,7 +621,7 @@ def test_demotions_are_deferred_unless_their_pages_are_needed_at_once():
     c2.plan_load(list(range(B)) + [9], n + [160], np.vstack([z, np.array([[1, 1, 1, 0]], dtype=np.uint8)]))
     info = c2.get_plan_info()
     assert info["moved_to_host_blocks"] == 40 and info["moved_to_hbm_blocks"] == 40
-    assert info["deferred_to_host_blocks"] == 10               # three of the four vacated blocks were taken at once
+    assert info["deferred_to_host_blocks"] == 9 and info["in_place_blocks"] == 10   # three of the four vacated blocks were taken at once
 
 
 def test_demoted_blocks_are_read_in_place_until_their_copies_have_landed():

@@ -14,8 +14,9 @@
  *    the text.  No exception or abort crosses this boundary.
  *  - "device" pointers are HIP device memory; "host" pointers are ordinary host memory unless
  *    "pinned" is stated.  The library never frees or reallocates caller memory.
- *  - All GPU work is enqueued on the two caller-owned streams and is asynchronous to the host
- *    unless a call says it synchronises.  One context must be driven by one thread at a time.
+ *  - All GPU work is enqueued on the two caller-owned streams (the deferred copies of a plan
+ *    switch on one stream the library owns) and is asynchronous to the host unless a call says
+ *    it synchronises.  One context must be driven by one thread at a time.
  *  - bf16 everywhere for Q, K, V and the output; accumulation is fp32.
  *  - Keep the streams a process actually uses few: HIP maps them onto four hardware queues per
  *    process by default, and a further busy stream that lands on the queue of compute_stream or
@@ -103,7 +104,8 @@ typedef struct {
   float   attn_ms_total;                 /* sum of attn_ms                                      */
   float   copy_ms_total;                 /* sum of copy_ms                                      */
   float   stall_ms_total;                /* compute_stream time spent waiting for prefetches    */
-  int64_t hbm_kv_bytes;                  /* KV bytes attended from resident blocks              */
+  int64_t hbm_kv_bytes;                  /* KV bytes attended from resident blocks (and from blocks
+                                            still read in place after a plan switch)            */
   int64_t link_kv_bytes;                 /* KV bytes moved host -> staging this step (zero-copy
                                             mode: read over the link by the attention kernel)   */
   int64_t hbm_blocks_reserved;           /* resident blocks + staging region (left of Eq. (1))  */

@@ -37,11 +37,13 @@ struct PageOp {
   int kind;
   int64_t src, dst;  // page index in the HBM arena or in the host arena, by kind
 };
-// One (request, layer) block that leaves HBM in a plan load: ops [first, first + n) of phase `phase`.
+// One (request, layer) block that leaves HBM in a plan load (phase `phase`): its first n pages are copied to
+// the host run starting at host_run.
 struct DemoteGroup {
   int phase, layer;
-  size_t first, n;
+  size_t n;
   int req;                         // index in the new batch, or -1 for a paused request's eviction
+  int64_t host_run;
   std::vector<int32_t> old_pages;  // the block list it had in HBM (used and reserved pages)
 };
 
@@ -368,9 +370,8 @@ class HostState {
         const int64_t used = (int64_t)lk.pages.size();
         int64_t run = H.alloc(used);
         if (run < 0) return ORBIT_E_HOST_CAPACITY;
-        groups.push_back({(int)phases.size() - 1, layer, phases.back().size(), (size_t)used, -1, {}});
-        for (int64_t i = 0; i < used; ++i) phases.back().push_back({OP_HBM_TO_HOST, lk.pages[i], run + i});
         for (int32_t p : lk.pages) free_hbm.push_back(p);
+        groups.push_back({(int)phases.size() - 1, layer, (size_t)used, -1, run, std::move(lk.pages)});
         evicted += used;
         lk.pages.clear();
         lk.tier = 0;
@@ -413,10 +414,9 @@ class HostState {
         int64_t run = H.alloc(rb[r]);
         if (run < 0) return fail(ORBIT_E_HOST_CAPACITY, "host arena full or fragmented (demotion)");
         int64_t used = ceil_div(lk.len, P);
-        groups.push_back({(int)phases.size() - 1, l, phases.back().size(), (size_t)used, r, lk.pages});
-        for (int64_t i = 0; i < used; ++i) phases.back().push_back({OP_HBM_TO_HOST, lk.pages[i], run + i});
         to_host += used;
         for (int32_t p : lk.pages) free_hbm.push_back(p);
+        groups.push_back({(int)phases.size() - 1, l, (size_t)used, r, run, std::move(lk.pages)});
         lk.pages.clear();
         lk.tier = 0;
         lk.host_page0 = run;
@@ -532,9 +532,10 @@ class HostState {
       nb.push_back(std::move(sb));
     }
 
-    // Which blocks may leave HBM lazily: every source page below the staging region and not handed out
-    // again by this plan load.  Their copies move from `phases` to `deferred`, grouped by layer; for a block
-    // that stays readable in place, all but the copy of its last used page.
+    // The copies of the blocks that leave HBM are written out only now, when it is known which of them may run
+    // lazily: every source page below the staging region and not handed out again by this plan load.  Those go
+    // to `deferred`, grouped by layer (for a block that stays readable in place: all but the copy of its last
+    // used page); the others to the phase of their group, in group order.
     std::vector<PageOp> lazy;
     std::vector<size_t> lazy_end(L, 0);
     std::vector<int32_t> dual_count(L, 0);
@@ -543,24 +544,27 @@ class HostState {
       reuse_mark_.assign((size_t)arena_pages, 0);
       for (int32_t pg : taken) reuse_mark_[pg] = 1;
       auto untouched = [&](int64_t pg) { return pg < ring_first && !reuse_mark_[pg]; };
-      std::vector<size_t> n_lazy(groups.size(), 0);  // ops [first, first + n_lazy) of the group are deferred
-      std::vector<size_t> per_layer(L, 0);
+      std::vector<size_t> n_lazy(groups.size(), 0);  // the first n_lazy copies of the group are deferred
+      std::vector<size_t> per_layer(L, 0), urgent(phases.size(), 0);
       for (size_t gi = 0; gi < groups.size(); ++gi) {
-        const DemoteGroup &g = groups[gi];
+        DemoteGroup &g = groups[gi];
         const bool in_place = g.req >= 0;
         bool ok = g.n > (in_place ? 1u : 0u);
-        for (size_t i = 0; i < g.n && ok; ++i) ok = untouched(phases[g.phase][g.first + i].src);
-        if (!ok) continue;
-        n_lazy[gi] = in_place ? g.n - 1 : g.n;
-        per_layer[g.layer] += n_lazy[gi];
-        if (in_place) {  // the used pages, and as many of the reserved ones behind them as are still untouched
-          size_t keep = g.n;
-          while (keep < g.old_pages.size() && untouched(g.old_pages[keep])) ++keep;
-          LayerKV &lk = nw[g.req].layers[g.layer];
-          lk.dual_pages.assign(g.old_pages.begin(), g.old_pages.begin() + keep);
-          ++dual_count[g.layer];
-          n_in_place += (int64_t)g.n;
+        for (size_t i = 0; i < g.n && ok; ++i) ok = untouched(g.old_pages[i]);
+        if (ok) {
+          n_lazy[gi] = in_place ? g.n - 1 : g.n;
+          per_layer[g.layer] += n_lazy[gi];
+          if (in_place) {  // the used pages, and as many of the reserved ones behind them as are still untouched
+            size_t keep = g.n;
+            while (keep < g.old_pages.size() && untouched(g.old_pages[keep])) ++keep;
+            LayerKV &lk = nw[g.req].layers[g.layer];
+            lk.dual_pages.assign(g.old_pages.begin(), g.old_pages.begin() + keep);
+            ++dual_count[g.layer];
+            n_in_place += (int64_t)g.n;
+          }
         }
+        urgent[g.phase] += g.n - n_lazy[gi];
+        n_deferred += (int64_t)n_lazy[gi];
       }
       size_t at = 0;
       std::vector<size_t> cursor(L, 0);
@@ -570,23 +574,15 @@ class HostState {
         lazy_end[l] = at;
       }
       lazy.resize(at);
-      std::vector<std::vector<uint8_t>> drop(phases.size());
+      for (size_t ph = 0; ph < phases.size(); ++ph)
+        if (urgent[ph]) phases[ph].reserve(phases[ph].size() + urgent[ph]);
       for (size_t gi = 0; gi < groups.size(); ++gi) {
-        if (!n_lazy[gi]) continue;
         const DemoteGroup &g = groups[gi];
-        if (drop[g.phase].empty()) drop[g.phase].assign(phases[g.phase].size(), 0);
-        for (size_t i = 0; i < n_lazy[gi]; ++i) {
-          lazy[cursor[g.layer]++] = phases[g.phase][g.first + i];
-          drop[g.phase][g.first + i] = 1;
+        for (size_t i = 0; i < g.n; ++i) {
+          const PageOp op{OP_HBM_TO_HOST, g.old_pages[i], g.host_run + (int64_t)i};
+          if (i < n_lazy[gi]) lazy[cursor[g.layer]++] = op;
+          else phases[g.phase].push_back(op);
         }
-        n_deferred += (int64_t)n_lazy[gi];
-      }
-      for (size_t ph = 0; ph < phases.size(); ++ph) {
-        if (drop[ph].empty()) continue;
-        std::vector<PageOp> keep;
-        for (size_t i = 0; i < phases[ph].size(); ++i)
-          if (!drop[ph][i]) keep.push_back(phases[ph][i]);
-        phases[ph] = std::move(keep);
       }
     }
 

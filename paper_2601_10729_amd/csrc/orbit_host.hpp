@@ -465,6 +465,18 @@ class HostState {
     end_phase();
     // (e) growth of resident lists, promotions host -> HBM, new resident requests
     phases.emplace_back();
+    {
+      size_t n_promote = 0, n_take = 0;
+      for (int r = 0; r < n_req; ++r)
+        for (int l = 0; l < L; ++l) {
+          const LayerKV &lk = nw[r].layers[l];
+          if (!x[(size_t)r * L + l]) continue;
+          if (lk.tier == 0) n_promote += (size_t)ceil_div(lk.len, P);
+          n_take += (size_t)rb[r] - (lk.tier == 1 ? std::min<size_t>(lk.pages.size(), (size_t)rb[r]) : 0);
+        }
+      phases.back().reserve(n_promote);
+      taken.reserve(taken.size() + n_take);
+    }
     for (int r = 0; r < n_req; ++r)
       for (int l = 0; l < L; ++l) {
         LayerKV &lk = nw[r].layers[l];
@@ -472,6 +484,7 @@ class HostState {
         int64_t used = ceil_div(lk.len, P);
         bool promote = (lk.tier == 0);
         if (lk.tier != 1) lk.pages.clear();
+        lk.pages.reserve((size_t)rb[r]);
         while ((int64_t)lk.pages.size() < rb[r]) {
           int32_t np = take_page();
           if (np < 0) return fail(ORBIT_E_CAPACITY, "internal: resident allocation failed");

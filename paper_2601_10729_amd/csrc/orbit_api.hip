@@ -24,7 +24,12 @@ using namespace orbit;
 namespace {
 std::string g_create_error;
 constexpr int kItemBufs = 2;  // pinned staging buffers of the work list
-constexpr int kDeferredCopyWorkgroups = 128;  // half a workgroup per CU: link-bound copies beside the decode steps
+// Width of the kernel that carries the deferred copies of a plan switch.  Nobody waits for these copies before the
+// next plan load: the blocks are read in place meanwhile, so a narrow kernel (about 20 GB/s) is the better one: it
+// leaves the compute units and the host->device direction of the link to the steps (measured behind an 11.5 GB
+// demotion, steps 1-3 after the switch: 66 / 64 / 109 ms with 8 workgroups, 80 / 115 / 184 ms with 32,
+// 120 / 154 / 203 ms with 128, 209 / 203 / 203 ms with 512; a steady step takes 203 ms).
+constexpr int kDeferredCopyWorkgroups = 8;
 static_assert(kMaxRequests == ORBIT_MAX_REQUESTS, "per-request launch arguments are sized by ORBIT_MAX_REQUESTS");
 }  // namespace
 

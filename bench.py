@@ -252,6 +252,43 @@ def resident_variant(run, n_steps=3):
             "avg_launch_ms": attn, "avg_combine_ms": float(st["comb_ms"].mean()), "bytes_per_launch": launch_bytes}
 
 
+def small_launches(torch, host, streams, seed):
+    """Per-layer time of small all-resident batches of the 8B head shape (the paper's own regime: batch 4 and up, a
+    few thousand tokens per request), with the chunk size the launch picks and with a fixed 1024-token chunk."""
+    import numpy as np
+    import harness
+    from workloads import make_workload
+    out = []
+    for B, n in ((1, 2048), (1, 8192), (4, 2048), (4, 8192), (16, 512), (16, 2048)):
+        w = make_workload("llama8b_b16", seed, n_req=B)
+        L = 4
+        w = dataclasses.replace(w, n_layers=L, placement=np.ones((B, L), dtype=np.uint8),
+                                ctx_len=np.full(B, n, dtype=w.ctx_len.dtype), steps=0)
+        rec = {"n_req": B, "tokens_per_request": n, "kv_mb_per_layer": B * n * 4096 / 1e6}
+        for key, chunk in (("us_per_layer", 0), ("us_per_layer_fixed_1024", 1024)):
+            g = harness.GpuRun(w, chunk_tokens=chunk, host_tensor=host, streams=streams, host_pages=8)
+            q = torch.stack([g.q_layer(l) for l in range(L)]).contiguous()
+            o = torch.empty_like(q)
+            torch.cuda.synchronize()
+            for _ in range(3):
+                for l in range(L):
+                    g.ctx.decode_attention(l, q[l], o[l])
+            g.cs.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(g.cs)
+            for _ in range(10):
+                for l in range(L):
+                    g.ctx.decode_attention(l, q[l], o[l])
+            e1.record(g.cs)
+            g.cs.synchronize()
+            rec[key] = e0.elapsed_time(e1) / (10 * L) * 1e3
+            if chunk == 0:
+                rec["chunk_tokens_chosen"] = int(g.ctx.get_work_items(0)[:, 2].max())
+            g.close()
+        out.append(rec)
+    return out
+
+
 def other_workload(torch, name, args, host, streams, link_peak):
     """Compact record of one of the other BASELINE configurations: the largest layer slice (all requests kept)
     whose offloaded blocks fit the pinned arena, 1 warm-up + 3 timed + 3 event-timed steps, all-resident variant."""
@@ -562,6 +599,13 @@ def main():
                 others.append({"workload": name, "error": repr(e)[:300]})
                 torch.cuda.empty_cache()
 
+    small = None
+    if others is not None:
+        try:
+            small = small_launches(torch, host, streams, args.seed)
+        except Exception as e:
+            small = {"error": repr(e)[:300]}
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(dataclasses.replace(w, ctx_len=(w.ctx_len + W).astype(np.int32)))
@@ -586,6 +630,7 @@ def main():
         "all_resident_variant": resident,
         "plan_switch": plan_switch,
         "other_workloads": others,
+        "small_launches": small,
         "first_step_ms": first_step_ms,
         "host_enqueue_ms_per_step": host_enqueue_ms,
         "ms_per_step_with_events": ms_per_step_events,

@@ -402,7 +402,7 @@ def main():
             host = torch.empty(host_bytes, dtype=torch.uint8, pin_memory=True)
             # the library and torch pin small buffers of their own later on (page-table mirrors, work lists): make
             # sure the machine still has room for them, or the larger workloads fail half-way through the run
-            probe = torch.empty(1 << 30, dtype=torch.uint8, pin_memory=True)
+            probe = torch.empty(4 << 30, dtype=torch.uint8, pin_memory=True)
             del probe
             torch._C._host_emptyCache()
         except RuntimeError:                 # this machine pins less than asked for: take what it gives, and say so

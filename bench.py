@@ -15,7 +15,6 @@ an SLO replay of the measured step times, and compact records of the other three
 """
 import argparse
 import dataclasses
-import gc
 import json
 import os
 import sys
@@ -252,6 +251,29 @@ def resident_variant(run, n_steps=3):
             "avg_launch_ms": attn, "avg_combine_ms": float(st["comb_ms"].mean()), "bytes_per_launch": launch_bytes}
 
 
+_PINNED = []          # (runtime, pointer) of arenas pinned by pin_exact: they live until the process ends
+
+
+def pin_exact(torch, nbytes):
+    """A uint8 tensor over `nbytes` of pinned host memory, pinned at exactly that size (hipHostMalloc of the HIP
+    runtime torch itself uses; torch.empty(pin_memory=True) would round the size up to a power of two)."""
+    import ctypes
+    path = os.path.join(os.path.dirname(torch.__file__), "lib", "libamdhip64.so")
+    if not os.path.exists(path):
+        return torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
+    torch.cuda.init()
+    hip = ctypes.CDLL(path)
+    ptr = ctypes.c_void_p()
+    rc = hip.hipHostMalloc(ctypes.byref(ptr), ctypes.c_size_t(nbytes), ctypes.c_uint(0))
+    if rc != 0:
+        hip.hipGetLastError()            # clear it: the next launch check must not find this refusal
+        raise RuntimeError(f"hipHostMalloc({nbytes}) failed with {rc}")
+    t = torch.frombuffer((ctypes.c_uint8 * nbytes).from_address(ptr.value), dtype=torch.uint8)
+    assert t.is_pinned()
+    _PINNED.append((hip, ptr))
+    return t
+
+
 def small_launches(torch, host, streams, seed):
     """Per-layer time of small all-resident batches of the 8B head shape (the paper's own regime: batch 4 and up, a
     few thousand tokens per request), with the chunk size the launch picks and with a fixed 1024-token chunk."""
@@ -348,7 +370,7 @@ def main():
     ap.add_argument("--placement", default="workload", choices=["workload", "resident", "host"])
     ap.add_argument("--n-req", type=int, default=None, help="truncate the batch")
     ap.add_argument("--n-layers", type=int, default=None, help="run a slice of the layers (all requests kept)")
-    ap.add_argument("--max-host-gib", type=float, default=60.0,
+    ap.add_argument("--max-host-gib", type=float, default=62.0,
                     help="size of the one pinned host arena every workload of this run lives in; workloads are cut to "
                          "fit (this pool's boxes refuse more than about 64 GiB of pinned memory in total)")
     ap.add_argument("--zero-copy", action="store_true",
@@ -394,22 +416,15 @@ def main():
             break
         n_req = w.n_req - 1            # this host cannot pin that much: drop the last request and say so
 
-    # one pinned arena for the whole run: the pinned pool of this machine is small, and torch keeps freed pinned
-    # blocks cached, so separate allocations per workload would add up
+    # one pinned arena for the whole run.  These machines pin at most about 65 GiB per process, and torch rounds a
+    # pinned request up to a power of two (60 GiB would take 64), so the arena is pinned at its exact size through
+    # the HIP runtime that torch has loaded and wrapped as a tensor (torch sees it as pinned: copies from it are
+    # asynchronous).  What is left stays free for the pinned buffers of the library and of torch.
     host = None
     while host is None:
         try:
-            host = torch.empty(host_bytes, dtype=torch.uint8, pin_memory=True)
-            # the library and torch pin small buffers of their own later on (page-table mirrors, work lists): make
-            # sure the machine still has room for them, or the larger workloads fail half-way through the run
-            probe = torch.empty(4 << 30, dtype=torch.uint8, pin_memory=True)
-            del probe
-            torch._C._host_emptyCache()
+            host = pin_exact(torch, host_bytes)
         except RuntimeError:                 # this machine pins less than asked for: take what it gives, and say so
-            host = None
-            gc.collect()
-            torch.cuda.empty_cache()
-            torch._C._host_emptyCache()
             host_bytes -= 4 << 30
             if (host_blocks + 8) * w.page_bytes > host_bytes:
                 raise

@@ -139,6 +139,9 @@ typedef struct {
                                      copy runs beside the following steps instead of in front of them      */
   int64_t in_place_blocks;        /* blocks of active requests that the last plan load demoted and that are read
                                      where they were in HBM until their copies have landed                 */
+  int64_t reclaimed_blocks;       /* blocks the last plan load wanted in HBM that were still being read in place
+                                     there: they took their pages back, nothing was copied (not counted in
+                                     moved_to_hbm_blocks)                                                   */
 } orbit_plan_info;
 
 /* ---- lifetime (ancillary) ------------------------------------------------------------------ */
@@ -182,7 +185,9 @@ ORBIT_API int orbit_plan_check(int32_t n_req, int32_t n_layers, int32_t page_tok
  * the host run, and the layer is not prefetched for them; the first prefetch of the layer issued after its
  * copies have completed (in the zero-copy mode: the first attention call) switches them to the staging region
  * (to their host pages).  Calls that need the host copy itself (orbit_kv_fill, orbit_kv_read, orbit_kv_append, a
- * decode window that outgrows the old pages) and the next plan load wait for the copies stream-side.
+ * decode window that outgrows the old pages) and the next plan load wait for the copies stream-side.  If that
+ * next plan load wants such a block in HBM again, the block keeps the pages it is being read from and nothing is
+ * copied (orbit_plan_info.reclaimed_blocks).
  * ORBIT_E_STATE if a prefetched layer has not been attended yet. */
 ORBIT_API int orbit_plan_load(orbit_ctx *ctx, int32_t n_req, const int64_t *req_ids, const int32_t *ctx_len,
                     const uint8_t *placement_bitmap, int64_t hbm_budget_bytes);

@@ -283,8 +283,31 @@ class HostState {
     HbmAlloc A = hbm;
     RunAlloc H = host;
     std::vector<Req> old = reqs;
-    for (auto &q : old)  // whatever was still read in place is a plain host block for this plan: its copies are
-      for (auto &lk : q.layers) lk.dual_pages.clear();  // waited for before anything of this plan load runs
+    // A block that the last plan load sent to the host, that is still read in place and that this plan wants in
+    // HBM again takes its pages back: they hold all of its tokens (a step's new token went there too), so nothing
+    // is copied.  Its host run is given up; the copy that may still be writing into it runs ahead of whatever
+    // this or a later plan load puts there.
+    int64_t reclaimed = 0;
+    for (int r = 0; r < n_req; ++r) {
+      const int o = find(ids[r]);
+      if (o < 0) continue;
+      for (int l = 0; l < L; ++l) {
+        LayerKV &lk = old[o].layers[l];
+        if (lk.dual_pages.empty() || !x[(size_t)r * L + l]) continue;
+        lk.pages = std::move(lk.dual_pages);
+        lk.dual_pages.clear();
+        while ((int64_t)lk.pages.size() > rb[r]) lk.pages.pop_back();
+        for (int32_t pg : lk.pages) A.used[pg] = 1;
+        H.release(lk.host_page0, lk.host_cap);
+        lk.tier = 1;
+        lk.host_page0 = -1;
+        lk.host_cap = 0;
+        lk.stage_page0 = -1;
+        reclaimed += ceil_div(lk.len, P);
+      }
+    }
+    for (auto &q : old)  // whatever else was still read in place is a plain host block for this plan: its copies
+      for (auto &lk : q.layers) lk.dual_pages.clear();  // are waited for before anything of this plan load runs
     std::vector<Req> oldp = paused;
     std::vector<Req> np;  // paused after this call
     std::vector<Req> nw(n_req);
@@ -604,6 +627,7 @@ class HostState {
     deferred_end = std::move(lazy_end);
     info.deferred_to_host_blocks = n_deferred;
     info.in_place_blocks = n_in_place;
+    info.reclaimed_blocks = reclaimed;
     dual_in_layer = std::move(dual_count);
     hbm = std::move(A);
     host = std::move(H);

@@ -244,3 +244,60 @@ def test_steps_run_in_place_while_a_large_demotion_is_in_flight(zero_copy):
 
     (a, in_place), (b, _) = run(True), run(False)
     assert torch.equal(a.view(torch.int16), b.view(torch.int16)), in_place
+
+
+@pytest.mark.parametrize("zero_copy", [False, True])
+def test_blocks_demoted_and_wanted_back_at_once_never_move(zero_copy):
+    """A plan sends 0.85 GB to the host, one step runs (reading and appending in place), and the next plan wants
+    everything resident again while the copies are still travelling: the blocks take their pages back, nothing is
+    copied to HBM, and every step equals a run that never switched, bit for bit."""
+    import harness as h
+    from workloads import gen_q_steps, gen_kv
+    L, S = 4, 5
+    base = make_workload("llama8b_b16", 0, n_req=4)
+    lens = np.array([20000, 17001, 23000, 9000], dtype=base.ctx_len.dtype)
+    ones = np.ones((4, L), dtype=np.uint8)
+    x = ones.copy()
+    x[:, 1:] = 0
+    w = dataclasses.replace(base, n_layers=L, ctx_len=lens, placement=ones, steps=S)
+    blocks = int(w.blocks(S).sum())
+    kw = dict(prefetch_slots=2, budget_pages=blocks * L + 2 * blocks + 64, host_pages=blocks * L + 64, decode_window=S,
+              max_tokens=int(lens.max()) + S + 16, zero_copy=zero_copy)
+
+    def run(switching: bool):
+        g = h.GpuRun(w, placement=ones, **kw)
+        B = w.n_req
+        q = torch.stack([torch.stack([gen_q_steps(w.seed, l, int(rid), 0, S, w.n_q_heads, w.head_dim, g.dev)
+                                      for rid in w.req_ids], dim=1) for l in range(L)], dim=1).contiguous()
+        kv = [[gen_kv(w.seed, l, int(rid), int(lens[r]), S, w.n_kv_heads, w.head_dim, g.dev)
+               for r, rid in enumerate(w.req_ids)] for l in range(L)]
+        k_new = torch.stack([torch.stack([kv[l][r][0] for r in range(B)], dim=1) for l in range(L)], dim=1).contiguous()
+        v_new = torch.stack([torch.stack([kv[l][r][1] for r in range(B)], dim=1) for l in range(L)], dim=1).contiguous()
+        outs = torch.zeros((S, L, B, w.n_q_heads, w.head_dim), dtype=torch.bfloat16, device=g.dev)
+        torch.cuda.synchronize()
+        for s in range(S):
+            if switching and s == 1:
+                g.ctx.plan_load(w.req_ids, lens + s, x)
+                assert g.ctx.get_plan_info()["in_place_blocks"] > 0
+            if switching and s == 2:
+                g.ctx.plan_load(w.req_ids, lens + s, ones)
+                info = g.ctx.get_plan_info()
+                assert info["reclaimed_blocks"] == 3 * int(np.ceil((lens + s) / 16).sum()) and info["moved_to_hbm_blocks"] == 0
+            g.ctx.step(q[s], k_new[s], v_new[s], outs[s])
+        g.cs.synchronize()
+        g.xs.synchronize()
+        res = outs.cpu()
+        if switching:                                       # the KV reads back complete, appended tokens included
+            for r, l in ((0, 1), (3, 3)):
+                n = int(lens[r]) + S
+                k, v = g.read_kv(r, l, n - 40, 40)
+                kw_, vw_ = gen_kv(w.seed, l, int(w.req_ids[r]), n - 40, 40, w.n_kv_heads, w.head_dim, g.dev)
+                assert torch.equal(k.view(torch.int16), kw_.view(torch.int16))
+                assert torch.equal(v.view(torch.int16), vw_.view(torch.int16))
+            _check_groups(h, w, [outs[S - 1][l] for l in range(L)], None, lens.astype(np.int64) + S,
+                          [(1, 0, 3), (2, 2, 7), (3, 3, 0)], step=S - 1)
+        g.close()
+        return res
+
+    a, b = run(True), run(False)
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))

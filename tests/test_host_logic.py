@@ -202,7 +202,8 @@ def test_plan_switch_moves_exactly_the_delta():
         c.plan_load(ids, n, x1)
         info = _layout_invariants(c, ids, L)
         assert info["moved_to_host_blocks"] == int((((x0 == 1) & (x1 == 0)) * b[:, None]).sum())
-        assert info["moved_to_hbm_blocks"] == int((((x0 == 0) & (x1 == 1)) * b[:, None]).sum())
+        # a block that left HBM in the previous switch and is still read in place there takes its pages back
+        assert info["moved_to_hbm_blocks"] + info["reclaimed_blocks"] == int((((x0 == 0) & (x1 == 1)) * b[:, None]).sum())
         x0 = x1
     c.plan_load(ids, n, x0)                                # identical plan: nothing moves
     info = c.get_plan_info()
@@ -609,8 +610,9 @@ def test_demotions_are_deferred_unless_their_pages_are_needed_at_once():
     info = c.get_plan_info()
     assert info["moved_to_host_blocks"] == 40 and info["moved_to_hbm_blocks"] == 40
     assert info["deferred_to_host_blocks"] == 36 and info["in_place_blocks"] == 40
-    # ... and when nothing else is left: a new resident request (30 blocks) arrives while layer 2 comes back (40
-    # blocks, 40 pages are free) and layer 3 leaves; the new request can only get pages that layer 3 vacates
+    # ... and when nothing else is left: a new resident request (30 blocks) arrives while layer 2 comes back (it
+    # is still read in place: it takes its 40 pages back, nothing is copied) and layer 3 leaves; the new request can
+    # only get pages that layer 3 vacates
     z = y.copy()
     z[:, 2] = 1
     z[:, 3] = 0
@@ -620,7 +622,7 @@ def test_demotions_are_deferred_unless_their_pages_are_needed_at_once():
     c2.plan_load(list(range(B)), n, y)
     c2.plan_load(list(range(B)) + [9], n + [160], np.vstack([z, np.array([[1, 1, 1, 0]], dtype=np.uint8)]))
     info = c2.get_plan_info()
-    assert info["moved_to_host_blocks"] == 40 and info["moved_to_hbm_blocks"] == 40
+    assert info["moved_to_host_blocks"] == 40 and info["moved_to_hbm_blocks"] == 0 and info["reclaimed_blocks"] == 40
     assert info["deferred_to_host_blocks"] == 9 and info["in_place_blocks"] == 10   # three of the four vacated blocks were taken at once
 
 
@@ -654,6 +656,37 @@ def test_demoted_blocks_are_read_in_place_until_their_copies_have_landed():
     c.plan_load(ids, n, x)
     assert c.get_pages(6, 2)["tier"] == 0 and c.get_plan_info()["in_place_blocks"] == 0
     _layout_invariants(c, ids, L)
+
+
+def test_a_block_still_read_in_place_takes_its_pages_back():
+    """Demote, then promote again before the copies have landed: the block never left its pages, so the second
+    switch copies nothing and the page lists are the original ones (grown by the new reservation)."""
+    L, B = 3, 3
+    n = [160, 100, 47]
+    ones = np.ones((B, L), dtype=np.uint8)
+    c = ctx(L=L, hbm_pages=2000, window=40)
+    ids = [5, 6, 7]
+    c.plan_load(ids, n, ones)
+    before = {(r, l): [int(p) for p in c.get_pages(r, l)["pages"]] for r in ids for l in range(L)}
+    x = ones.copy()
+    x[0, 1] = x[2, 1] = x[1, 2] = 0
+    c.plan_load(ids, n, x)
+    y = ones.copy()
+    y[2, 1] = 0                                          # (7, 1) stays out; (5, 1) and (6, 2) come back
+    c.plan_load(ids, n, y)
+    info = _layout_invariants(c, ids, L)
+    assert info["reclaimed_blocks"] == 10 + 7 and info["moved_to_hbm_blocks"] == 0 and info["moved_to_host_blocks"] == 0
+    for r, l in ((5, 1), (6, 2)):
+        p = c.get_pages(r, l)
+        assert p["tier"] == 1 and [int(v) for v in p["pages"]] == before[(r, l)]
+    assert c.get_pages(7, 1)["tier"] == 0                # a plan load settles what stays on the host
+    # once a layer has been handed over (in a host-only context: at its first prefetch), coming back is a real copy
+    c.plan_load(ids, n, x)
+    c.kv_prefetch(1)
+    c.decode_attention(1, None, None)
+    c.plan_load(ids, n, ones)
+    info = c.get_plan_info()
+    assert info["reclaimed_blocks"] == 7 and info["moved_to_hbm_blocks"] == 10 + 3
 
 
 def test_a_single_block_demotion_is_not_read_in_place():

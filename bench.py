@@ -400,7 +400,7 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     K, W = args.steps, args.warmup
-    total_steps = 1 + W + 2 * K + 22     # first, warm-up, timed, event-timed, searched-plan, all-resident variants, switch back
+    total_steps = 1 + W + 2 * K + 26     # first, warm-up, timed, event-timed, searched-plan, all-resident variants, switch back
     n_req, n_layers = args.n_req, args.n_layers
     host_bytes = int(args.max_host_gib * (1 << 30))
     while True:
@@ -591,8 +591,30 @@ def main():
                            "six_steps_vs_steady": sum(after) / (6 * steady_ms),
                            "note": "first_step_after_switch_ms runs from the orbit_plan_load call to the output of the step "
                                    "behind it (compute stream); the following entries are the next steps, each to its output"}
+            # a planner that changes its mind: everything resident (a real promotion: the blocks had been handed
+            # over), the workload's placement again, one step, and everything resident once more while the copies of
+            # the second switch are still travelling - the blocks take back the pages they are being read from
+            run.switch(np.ones_like(w.placement))
+            run.step()
+            run.drain()
+            t0 = time.perf_counter()
+            run.g.ctx.plan_load(w.req_ids, run.lengths().astype("int32"), w.placement)
+            run.step()
+            run.g.cs.synchronize()
+            t1 = time.perf_counter()
+            run.g.ctx.plan_load(w.req_ids, run.lengths().astype("int32"), np.ones_like(w.placement))
+            back = run.g.ctx.get_plan_info()
+            run.step()
+            run.g.cs.synchronize()
+            t2 = time.perf_counter()
+            plan_switch["change_of_mind"] = {
+                "demote_and_step_ms": (t1 - t0) * 1e3, "promote_back_and_step_ms": (t2 - t1) * 1e3,
+                "reclaimed_blocks": back["reclaimed_blocks"], "copied_to_hbm_blocks": back["moved_to_hbm_blocks"],
+                "waited_for_deferred": back["waited_for_deferred"],
+                "note": "the second switch comes one step after the first: what is still read in place is not copied back"}
         except Exception as e:
-            plan_switch = {"error": repr(e)[:300]}
+            plan_switch = (plan_switch or {})
+            plan_switch["error"] = repr(e)[:300]
     setup_s = run.setup_s
     run.close()
     if args.calibrate_copy:

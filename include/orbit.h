@@ -142,6 +142,9 @@ typedef struct {
   int64_t reclaimed_blocks;       /* blocks the last plan load wanted in HBM that were still being read in place
                                      there: they took their pages back, nothing was copied (not counted in
                                      moved_to_hbm_blocks)                                                   */
+  int64_t waited_for_deferred;    /* 1 if the last plan load made its copies wait for deferred copies of earlier plan
+                                     loads (it touched a page one of them reads or writes), 0 if it ran beside
+                                     them or none were outstanding                                           */
 } orbit_plan_info;
 
 /* ---- lifetime (ancillary) ------------------------------------------------------------------ */
@@ -185,9 +188,11 @@ ORBIT_API int orbit_plan_check(int32_t n_req, int32_t n_layers, int32_t page_tok
  * the host run, and the layer is not prefetched for them; the first prefetch of the layer issued after its
  * copies have completed (in the zero-copy mode: the first attention call) switches them to the staging region
  * (to their host pages).  Calls that need the host copy itself (orbit_kv_fill, orbit_kv_read, orbit_kv_append, a
- * decode window that outgrows the old pages) and the next plan load wait for the copies stream-side.  If that
- * next plan load wants such a block in HBM again, the block keeps the pages it is being read from and nothing is
- * copied (orbit_plan_info.reclaimed_blocks).
+ * decode window that outgrows the old pages) wait for the copies stream-side.  The next plan load ends the in-place
+ * reads: a block it wants in HBM again keeps the pages it is being read from and nothing is copied
+ * (orbit_plan_info.reclaimed_blocks); any other is read from its host run once its layer's copies have landed.  It
+ * waits for the copies itself only if it hands out an HBM page one of them still reads or a host page one of them
+ * still writes, or moves a block whose host run they are still filling (orbit_plan_info.waited_for_deferred).
  * ORBIT_E_STATE if a prefetched layer has not been attended yet. */
 ORBIT_API int orbit_plan_load(orbit_ctx *ctx, int32_t n_req, const int64_t *req_ids, const int32_t *ctx_len,
                     const uint8_t *placement_bitmap, int64_t hbm_budget_bytes);

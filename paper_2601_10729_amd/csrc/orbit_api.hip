@@ -92,7 +92,16 @@ struct orbit_ctx {
   hipEvent_t ev_ops_up = nullptr, ev_lazy_all = nullptr;     // op list uploaded; every deferred copy of the last switch done
   std::vector<hipEvent_t> ev_lazy;                           // per layer: that layer's deferred copies done
   std::vector<uint8_t> lazy_x, lazy_c;                       // per layer: copy / compute stream has yet to wait for ev_lazy[l]
+  // A plan load that runs beside the deferred copies of earlier ones and defers copies of its own in a layer keeps
+  // that layer's older event here: the blocks those older copies carry are plain host blocks by now, and whoever
+  // reads them waits for this one, whatever the newer copies (whose blocks are read in place) are doing.
+  std::vector<hipEvent_t> ev_lazy_prev;
+  std::vector<uint8_t> prev_x, prev_c;                       // per layer: copy / compute stream has yet to wait for ev_lazy_prev[l]
   bool lazy_outstanding = false;
+  BlitOp *d_lazy[2] = {nullptr, nullptr};   // op lists of deferred copies: two, because the copies of one switch may
+  size_t d_lazy_cap[2] = {0, 0};            // still be running when the next switch enqueues its own
+  hipEvent_t ev_lazy_buf[2] = {nullptr, nullptr};  // the kernels that read d_lazy[i] are done
+  int lazy_buf = 0;
   int32_t *h_items_pinned[kItemBufs] = {};
   hipEvent_t ev_items[kItemBufs] = {};
   int items_buf = 0;
@@ -160,7 +169,24 @@ int wait_deferred(orbit_ctx *c, int layer, bool on_copy_stream) {
   if (!flag[layer]) return ORBIT_OK;
   HIPCHECK(c, hipStreamWaitEvent(on_copy_stream ? c->xs : c->cs, c->ev_lazy[layer], 0));
   flag[layer] = 0;
+  (on_copy_stream ? c->prev_x : c->prev_c)[layer] = 0;  // the copies run in order: the newer event covers the older
   return ORBIT_OK;
+}
+
+// The same for the copies that plan loads before the last one deferred: their blocks are never read in place any more.
+int wait_deferred_older(orbit_ctx *c, int layer, bool on_copy_stream) {
+  if (c->host_only) return ORBIT_OK;
+  std::vector<uint8_t> &flag = on_copy_stream ? c->prev_x : c->prev_c;
+  if (!flag[layer]) return ORBIT_OK;
+  HIPCHECK(c, hipStreamWaitEvent(on_copy_stream ? c->xs : c->cs, c->ev_lazy_prev[layer], 0));
+  flag[layer] = 0;
+  return ORBIT_OK;
+}
+
+// In front of a read of the layer's plain host blocks (those not read in place).  While blocks of the layer are still
+// read in place, the last plan load's copies are theirs and only the older ones matter.
+int settle_host_blocks(orbit_ctx *c, int layer, bool on_copy_stream) {
+  return c->hs.dual_in_layer[layer] ? wait_deferred_older(c, layer, on_copy_stream) : wait_deferred(c, layer, on_copy_stream);
 }
 
 // Blocks of `layer` that the last plan load demoted and that are still read where they were in HBM: once the
@@ -233,8 +259,7 @@ int prefetch_impl(orbit_ctx *c, int layer) {
     c->host_dirty[layer] = 0;
   }
   if (int rc = flip_in_place_blocks(c, layer, false)) return rc;
-  if (!hs.dual_in_layer[layer])  // host blocks of this layer whose copies may still be in flight are read below
-    if (int rc = wait_deferred(c, layer, true)) return rc;
+  if (int rc = settle_host_blocks(c, layer, true)) return rc;  // they are read below
   if (c->timing && !c->host_only) HIPCHECK(c, hipEventRecord(c->t_copy0[layer], c->xs));
   int64_t bytes = 0;
   for (const CopyItem &ci : blk.copies) {
@@ -340,6 +365,7 @@ int attention_impl(orbit_ctx *c, int layer, const void *q, void *out, float *out
   // cannot meet a copy (its last page was copied at once).  The staged mode hands such blocks over in the layer's
   // prefetch; the zero-copy mode, which has none, here: the lengths already count the token of a fused append
   if (sh.zero_copy && (rc = flip_in_place_blocks(c, layer, false, 0))) return rc;
+  if (sh.zero_copy && (rc = settle_host_blocks(c, layer, false))) return rc;  // host blocks are read where they are
   if (!c->host_only) {
     if (c->timing) HIPCHECK(c, hipEventRecord(c->t_attn0[layer], c->cs));
     AttnParams &ap = c->attn_args;  // the per-request part is rewritten below; the rest is cheap to refill
@@ -418,16 +444,50 @@ int check_layer(orbit_ctx *c, int layer) {
 // waits for everything already enqueued on the compute stream, then runs the page migrations
 // (one blit per phase, in order); the compute stream waits for them and then receives the new
 // page table (lengths travel with every launch).  The pinned staging copies are reused only after their last transfer.
+// Before a plan load: if the deferred copies of earlier ones have all landed, the new one has nothing to look out for.
+int retire_deferred(orbit_ctx *c) {
+  if (c->host_only || !c->lazy_outstanding) return ORBIT_OK;
+  const hipError_t e = hipEventQuery(c->ev_lazy_all);
+  if (e == hipErrorNotReady) {
+    (void)hipGetLastError();
+    return ORBIT_OK;
+  }
+  if (e != hipSuccess) return hip_fail(c, e, "hipEventQuery(ev_lazy_all)");
+  std::fill(c->lazy_x.begin(), c->lazy_x.end(), 0);
+  std::fill(c->lazy_c.begin(), c->lazy_c.end(), 0);
+  std::fill(c->prev_x.begin(), c->prev_x.end(), 0);
+  std::fill(c->prev_c.begin(), c->prev_c.end(), 0);
+  c->lazy_outstanding = false;
+  c->hs.forget_deferred();
+  return ORBIT_OK;
+}
+
 int apply_plan_gpu(orbit_ctx *c, const std::vector<std::vector<PageOp>> &phases) {
   if (c->host_only) return ORBIT_OK;
   const HostState &hs = c->hs;
   const Shape &sh = hs.sh;
   HIPCHECK(c, hipEventRecord(c->ev_plan_c, c->cs));
   HIPCHECK(c, hipStreamWaitEvent(c->xs, c->ev_plan_c, 0));
-  if (c->lazy_outstanding) {  // pages and host runs the last switch's deferred copies still use may change hands now
+  // Deferred copies of earlier switches may still be running.  This switch waits for them only if it touches a page
+  // they touch (HostState::needs_lazy_wait), or if it needs the op-list buffer their kernels still read.
+  const int lb = c->lazy_buf ^ 1;
+  bool wait_lazy = c->lazy_outstanding && hs.needs_lazy_wait;
+  if (c->lazy_outstanding && !wait_lazy && !hs.deferred.empty()) {
+    const hipError_t e = hipEventQuery(c->ev_lazy_buf[lb]);
+    if (e == hipErrorNotReady) {
+      (void)hipGetLastError();
+      wait_lazy = true;
+    } else if (e != hipSuccess) {
+      return hip_fail(c, e, "hipEventQuery(ev_lazy_buf)");
+    }
+  }
+  c->hs.info.waited_for_deferred = wait_lazy;
+  if (wait_lazy) {
     HIPCHECK(c, hipStreamWaitEvent(c->xs, c->ev_lazy_all, 0));
     std::fill(c->lazy_x.begin(), c->lazy_x.end(), 0);
     std::fill(c->lazy_c.begin(), c->lazy_c.end(), 0);  // the compute stream waits for this switch below
+    std::fill(c->prev_x.begin(), c->prev_x.end(), 0);
+    std::fill(c->prev_c.begin(), c->prev_c.end(), 0);
     c->lazy_outstanding = false;
   }
   size_t urgent = 0;
@@ -463,7 +523,20 @@ int apply_plan_gpu(orbit_ctx *c, const std::vector<std::vector<PageOp>> &phases)
     for (auto &ph : phases)
       for (const PageOp &op : ph) c->h_ops_pinned[n++] = to_blit(op);
     for (const PageOp &op : hs.deferred) c->h_ops_pinned[n++] = to_blit(op);
-    HIPCHECK(c, hipMemcpyAsync(c->d_ops, c->h_ops_pinned, total * sizeof(BlitOp), hipMemcpyHostToDevice, c->xs));
+    if (urgent) HIPCHECK(c, hipMemcpyAsync(c->d_ops, c->h_ops_pinned, urgent * sizeof(BlitOp), hipMemcpyHostToDevice, c->xs));
+    if (!hs.deferred.empty()) {
+      if (hs.deferred.size() > c->d_lazy_cap[lb]) {
+        HIPCHECK(c, hipEventSynchronize(c->ev_lazy_buf[lb]));  // the kernels that read the old buffer
+        if (c->d_lazy[lb]) HIPCHECK(c, hipFree(c->d_lazy[lb]));
+        c->d_lazy[lb] = nullptr;
+        c->d_lazy_cap[lb] = 0;
+        const size_t cap = hs.deferred.size() + hs.deferred.size() / 4;
+        HIPCHECK(c, hipMalloc((void **)&c->d_lazy[lb], cap * sizeof(BlitOp)));
+        c->d_lazy_cap[lb] = cap;
+      }
+      HIPCHECK(c, hipMemcpyAsync(c->d_lazy[lb], c->h_ops_pinned + urgent, hs.deferred.size() * sizeof(BlitOp),
+                                 hipMemcpyHostToDevice, c->xs));
+    }
     HIPCHECK(c, hipEventRecord(c->ev_ops_up, c->xs));
     size_t at = 0;
     for (auto &ph : phases) {
@@ -480,13 +553,20 @@ int apply_plan_gpu(orbit_ctx *c, const std::vector<std::vector<PageOp>> &phases)
       for (int l = 0; l < sh.L; ++l) {
         const size_t hi = hs.deferred_end[l];
         if (hi > lo) {
-          HIPCHECK(c, launch_blit_narrow(c->d_ops + urgent + lo, (int64_t)(hi - lo), pb, kDeferredCopyWorkgroups, c->ds));
+          HIPCHECK(c, launch_blit_narrow(c->d_lazy[lb] + lo, (int64_t)(hi - lo), pb, kDeferredCopyWorkgroups, c->ds));
+          if (c->lazy_x[l] || c->lazy_c[l]) {  // copies of an earlier plan load that a stream has not waited for yet
+            std::swap(c->ev_lazy[l], c->ev_lazy_prev[l]);
+            c->prev_x[l] |= c->lazy_x[l];
+            c->prev_c[l] |= c->lazy_c[l];
+          }
           HIPCHECK(c, hipEventRecord(c->ev_lazy[l], c->ds));
           c->lazy_x[l] = c->lazy_c[l] = 1;
         }
         lo = hi;
       }
       HIPCHECK(c, hipEventRecord(c->ev_lazy_all, c->ds));
+      HIPCHECK(c, hipEventRecord(c->ev_lazy_buf[lb], c->ds));
+      c->lazy_buf = lb;
       c->lazy_outstanding = true;
     }
   }
@@ -833,6 +913,8 @@ int orbit_create(const orbit_config *cfg, orbit_ctx **out) try {
   c->host_dirty.assign(sh.L, 0);
   c->lazy_x.assign(sh.L, 0);
   c->lazy_c.assign(sh.L, 0);
+  c->prev_x.assign(sh.L, 0);
+  c->prev_c.assign(sh.L, 0);
   c->hs.live.reserve(sh.L + 1);
   c->items_key_tmp.reserve(sh.max_req + 1);
   c->flipped_tmp.reserve(sh.max_req);
@@ -901,13 +983,14 @@ int orbit_create(const orbit_config *cfg, orbit_ctx **out) try {
     CREATE_CHECK(hipEventCreateWithFlags(&p->ev_tmp, hipEventDisableTiming));
     CREATE_CHECK(hipEventCreateWithFlags(&p->ev_ops_up, hipEventDisableTiming));
     CREATE_CHECK(hipEventCreateWithFlags(&p->ev_lazy_all, hipEventDisableTiming));
+    for (int b = 0; b < 2; ++b) CREATE_CHECK(hipEventCreateWithFlags(&p->ev_lazy_buf[b], hipEventDisableTiming));
     CREATE_CHECK(hipStreamCreateWithFlags(&p->ds, hipStreamNonBlocking));  // default priority, as the caller's streams
     CREATE_CHECK(hipEventCreate(&p->t_step0));
     CREATE_CHECK(hipEventCreate(&p->t_step1));
 #undef CREATE_CHECK
     int rc = 0;
     if ((rc = make_events(p, p->ev_ready, sh.L, false)) || (rc = make_events(p, p->ev_done, sh.L, false)) ||
-        (rc = make_events(p, p->ev_lazy, sh.L, false)) ||
+        (rc = make_events(p, p->ev_lazy, sh.L, false)) || (rc = make_events(p, p->ev_lazy_prev, sh.L, false)) ||
         (rc = make_events(p, p->t_wait0, sh.L, true)) || (rc = make_events(p, p->t_wait1, sh.L, true)) ||
         (rc = make_events(p, p->t_attn0, sh.L, true)) || (rc = make_events(p, p->t_attn1, sh.L, true)) ||
         (rc = make_events(p, p->t_comb1, sh.L, true)) || (rc = make_events(p, p->t_copy0, sh.L, true)) ||
@@ -940,6 +1023,10 @@ int orbit_destroy(orbit_ctx *c) {
     (void)hipFree(c->d_pacc);
     (void)hipFree(c->d_pml);
     (void)hipFree(c->d_ops);
+    for (int b = 0; b < 2; ++b) {
+      (void)hipFree(c->d_lazy[b]);
+      if (c->ev_lazy_buf[b]) (void)hipEventDestroy(c->ev_lazy_buf[b]);
+    }
     if (c->h_ops_pinned) (void)hipHostFree(c->h_ops_pinned);
     if (c->h_tab_pinned) (void)hipHostFree(c->h_tab_pinned);
     for (hipEvent_t e : {c->ev_ops, c->ev_tab, c->ev_tab_rows, c->ev_plan_c, c->ev_plan_x, c->ev_ops_up, c->ev_lazy_all})
@@ -954,6 +1041,7 @@ int orbit_destroy(orbit_ctx *c) {
     drop_events(c->ev_ready);
     drop_events(c->ev_done);
     drop_events(c->ev_lazy);
+    drop_events(c->ev_lazy_prev);
     drop_events(c->t_wait0);
     drop_events(c->t_wait1);
     drop_events(c->t_attn0);
@@ -972,6 +1060,7 @@ int orbit_plan_load(orbit_ctx *c, int32_t n_req, const int64_t *req_ids, const i
   for (auto &lb : c->hs.live)
     if (!lb.consumed) return set_err(c, ORBIT_E_STATE, "a prefetched layer was never attended; finish it before a new plan");
   std::vector<std::vector<PageOp>> phases;
+  if (int rr = retire_deferred(c)) return rr;
   int rc = c->hs.plan_load(n_req, req_ids, ctx_len, placement_bitmap, hbm_budget_bytes, phases);
   if (rc) return set_err(c, rc, c->hs.err);
   c->items_valid = false;
@@ -987,6 +1076,7 @@ int orbit_request_pause(orbit_ctx *c, int64_t req_id) try {
   for (auto &lb : c->hs.live)
     if (!lb.consumed) return set_err(c, ORBIT_E_STATE, "a prefetched layer was never attended; finish it before pausing");
   std::vector<std::vector<PageOp>> phases;
+  if (int rr = retire_deferred(c)) return rr;
   int rc = c->hs.pause(req_id, phases);
   if (rc) return set_err(c, rc, c->hs.err);
   c->items_valid = false;

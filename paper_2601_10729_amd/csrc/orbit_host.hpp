@@ -208,6 +208,14 @@ class HostState {
   std::vector<size_t> deferred_end;      // [L] end offset of layer l's ops in `deferred`
   std::vector<uint8_t> reuse_mark_;      // [arena_pages] scratch of the classification
   std::vector<int32_t> dual_in_layer;    // [L] blocks of the layer that are read in place
+  // Deferred copies of earlier plan loads may still be running when the next one comes.  It has to wait for them
+  // only if it touches what they touch: it hands out an HBM page one of them still reads (to a block, or to the
+  // staging region), or a host page one of them still writes (as part of a new or grown host run), or it reads
+  // such a host page.  The marks collect the pages of every deferred copy since the last such wait.
+  std::vector<uint8_t> lazy_src_mark_, lazy_dst_mark_;  // [arena_pages], [host_pages]
+  int64_t lazy_src_top_ = 0;             // one past the highest marked HBM page
+  bool lazy_marks_any_ = false;
+  bool needs_lazy_wait = false;          // verdict of the last successful plan_load
 
   std::string err;
 
@@ -222,6 +230,17 @@ class HostState {
     block_of_layer.assign(sh.L, -1);
     deferred_end.assign(sh.L, 0);
     dual_in_layer.assign(sh.L, 0);
+    lazy_src_mark_.assign((size_t)arena_pages, 0);
+    lazy_dst_mark_.assign((size_t)host_pages, 0);
+  }
+
+  // Every deferred copy has landed (the caller has seen it on the device): nothing is left to collide with.
+  void forget_deferred() {
+    if (!lazy_marks_any_) return;
+    std::fill(lazy_src_mark_.begin(), lazy_src_mark_.end(), 0);
+    std::fill(lazy_dst_mark_.begin(), lazy_dst_mark_.end(), 0);
+    lazy_marks_any_ = false;
+    lazy_src_top_ = 0;
   }
 
   int find(int64_t id) const {
@@ -306,8 +325,8 @@ class HostState {
         reclaimed += ceil_div(lk.len, P);
       }
     }
-    for (auto &q : old)  // whatever else was still read in place is a plain host block for this plan: its copies
-      for (auto &lk : q.layers) lk.dual_pages.clear();  // are waited for before anything of this plan load runs
+    for (auto &q : old)  // whatever else was still read in place is a plain host block for this plan: a step waits
+      for (auto &lk : q.layers) lk.dual_pages.clear();  // for its layer's copies before it reads the host run
     std::vector<Req> oldp = paused;
     std::vector<Req> np;  // paused after this call
     std::vector<Req> nw(n_req);
@@ -356,6 +375,7 @@ class HostState {
     std::vector<int64_t> free_hbm;
     std::vector<std::pair<int64_t, int64_t>> free_host;
     std::vector<DemoteGroup> groups;       // blocks leaving HBM (evictions and demotions)
+    std::vector<std::pair<int64_t, int64_t>> new_host;  // host page ranges this plan load hands out (start, pages)
     std::vector<int32_t> taken;            // HBM pages this plan load allocated
     // Pages that evictions and demotions vacate are handed out again only when nothing else is free: a block
     // whose old pages stay untouched can leave HBM beside the following steps and be read in place meanwhile.
@@ -393,6 +413,7 @@ class HostState {
         const int64_t used = (int64_t)lk.pages.size();
         int64_t run = H.alloc(used);
         if (run < 0) return ORBIT_E_HOST_CAPACITY;
+        new_host.push_back({run, used});
         for (int32_t p : lk.pages) free_hbm.push_back(p);
         groups.push_back({(int)phases.size() - 1, layer, (size_t)used, -1, run, std::move(lk.pages)});
         evicted += used;
@@ -436,6 +457,7 @@ class HostState {
         if (lk.tier != 1 || x[(size_t)r * L + l]) continue;
         int64_t run = H.alloc(rb[r]);
         if (run < 0) return fail(ORBIT_E_HOST_CAPACITY, "host arena full or fragmented (demotion)");
+        new_host.push_back({run, rb[r]});
         int64_t used = ceil_div(lk.len, P);
         to_host += used;
         for (int32_t p : lk.pages) free_hbm.push_back(p);
@@ -453,11 +475,13 @@ class HostState {
         LayerKV &lk = nw[r].layers[l];
         if (lk.tier != 0 || x[(size_t)r * L + l] || lk.host_cap >= rb[r]) continue;
         if (H.extend(lk.host_page0, lk.host_cap, rb[r])) {  // room right behind the run: no copy
+          new_host.push_back({lk.host_page0 + lk.host_cap, rb[r] - lk.host_cap});
           lk.host_cap = (int32_t)rb[r];
           continue;
         }
         int64_t run = H.alloc(rb[r]);
         if (run < 0) return fail(ORBIT_E_HOST_CAPACITY, "host arena full or fragmented (growth)");
+        new_host.push_back({run, rb[r]});
         int64_t used = ceil_div(lk.len, P);
         for (int64_t i = 0; i < used; ++i) phases.back().push_back({OP_HOST_TO_HOST, lk.host_page0 + i, run + i});
         free_host.push_back({lk.host_page0, lk.host_cap});
@@ -532,6 +556,7 @@ class HostState {
         if (lk.tier != 2) continue;
         int64_t run = H.alloc(rb[r]);
         if (run < 0) return fail(ORBIT_E_HOST_CAPACITY, "host arena full or fragmented (new request)");
+        new_host.push_back({run, rb[r]});
         lk.tier = 0;
         lk.host_page0 = run;
         lk.host_cap = (int32_t)rb[r];
@@ -622,12 +647,37 @@ class HostState {
       }
     }
 
+    // Must the copies that earlier plan loads deferred be waited for?  (see lazy_src_mark_)
+    bool wait_lazy = false;
+    if (lazy_marks_any_) {
+      wait_lazy = lazy_src_top_ > ring_first;
+      for (size_t i = 0; i < taken.size() && !wait_lazy; ++i) wait_lazy = lazy_src_mark_[taken[i]];
+      for (size_t i = 0; i < new_host.size() && !wait_lazy; ++i)
+        for (int64_t pg = new_host[i].first; pg < new_host[i].first + new_host[i].second && !wait_lazy; ++pg)
+          wait_lazy = lazy_dst_mark_[pg];
+      for (size_t ph = 0; ph < phases.size() && !wait_lazy; ++ph)
+        for (const PageOp &op : phases[ph])
+          if ((op.kind == OP_HOST_TO_HBM || op.kind == OP_HOST_TO_HOST) && lazy_dst_mark_[op.src]) {
+            wait_lazy = true;
+            break;
+          }
+    }
+
     // commit
+    needs_lazy_wait = wait_lazy;
+    if (wait_lazy) forget_deferred();
+    for (const PageOp &op : lazy) {
+      lazy_src_top_ = std::max(lazy_src_top_, op.src + 1);
+      lazy_src_mark_[op.src] = 1;
+      lazy_dst_mark_[op.dst] = 1;
+      lazy_marks_any_ = true;
+    }
     deferred = std::move(lazy);
     deferred_end = std::move(lazy_end);
     info.deferred_to_host_blocks = n_deferred;
     info.in_place_blocks = n_in_place;
     info.reclaimed_blocks = reclaimed;
+    info.waited_for_deferred = wait_lazy;  // (with a device behind it, the caller may still find a reason to wait)
     dual_in_layer = std::move(dual_count);
     hbm = std::move(A);
     host = std::move(H);

@@ -70,6 +70,60 @@ static void check_layout(const HostState &hs) {
   CHECK(hs.info.resident_blocks + hs.info.staging_blocks <= hs.info.budget_blocks);
 }
 
+// The deferred copies that no plan load has waited for yet, each with the block it carries.  A plan load that says it
+// need not wait for them (needs_lazy_wait == false) must leave them alone: an HBM page one of them reads stays with
+// its block or with nobody and outside the staging region, a host page one of them writes stays with its block or
+// with nobody, and none of the copies the plan load runs at once writes either kind of page or reads such a host page.
+struct PendingCopy {
+  int64_t src, dst, id;
+  int layer;
+};
+
+static void check_pending(const HostState &hs, const std::vector<std::vector<PageOp>> &phases,
+                          std::vector<PendingCopy> &pending) {
+  if (hs.needs_lazy_wait) pending.clear();
+  std::vector<int> src_at((size_t)hs.arena_pages, -1), dst_at((size_t)hs.host_pages, -1);
+  for (size_t i = 0; i < pending.size(); ++i) {
+    src_at[pending[i].src] = (int)i;
+    dst_at[pending[i].dst] = (int)i;
+    CHECK(pending[i].src < hs.info.staging_first_page);
+  }
+  for (auto &ph : phases)
+    for (auto &op : ph) {
+      if (op.kind == OP_HOST_TO_HBM || op.kind == OP_HBM_TO_HBM) CHECK(src_at[op.dst] < 0);
+      if (op.kind == OP_HBM_TO_HOST || op.kind == OP_HOST_TO_HOST) CHECK(dst_at[op.dst] < 0);
+      if (op.kind == OP_HOST_TO_HBM || op.kind == OP_HOST_TO_HOST) CHECK(dst_at[op.src] < 0);
+    }
+  auto visit = [&](const Req &q) {
+    for (int l = 0; l < hs.sh.L; ++l) {
+      const LayerKV &lk = q.layers[l];
+      if (lk.tier == 1)
+        for (int32_t p : lk.pages)
+          if (src_at[p] >= 0) CHECK(pending[src_at[p]].id == q.id && pending[src_at[p]].layer == l);
+      if (lk.tier == 0)
+        for (int64_t p = lk.host_page0; p < lk.host_page0 + lk.host_cap; ++p)
+          if (dst_at[p] >= 0) CHECK(pending[dst_at[p]].id == q.id && pending[dst_at[p]].layer == l);
+    }
+  };
+  for (auto &q : hs.reqs) visit(q);
+  for (auto &q : hs.paused) visit(q);
+  // this plan load's own deferred copies join the list, under the block whose host run they fill
+  for (auto &op : hs.deferred) {
+    CHECK(op.kind == OP_HBM_TO_HOST && dst_at[op.dst] < 0);
+    PendingCopy pc{op.src, op.dst, -1, -1};
+    auto owner = [&](const Req &q) {
+      for (int l = 0; l < hs.sh.L; ++l) {
+        const LayerKV &lk = q.layers[l];
+        if (lk.tier == 0 && op.dst >= lk.host_page0 && op.dst < lk.host_page0 + lk.host_cap) { pc.id = q.id; pc.layer = l; }
+      }
+    };
+    for (auto &q : hs.reqs) owner(q);
+    for (auto &q : hs.paused) owner(q);
+    CHECK(pc.id >= 0);
+    pending.push_back(pc);
+  }
+}
+
 int main(int argc, char **argv) {
   const unsigned seed = argc > 1 ? (unsigned)std::atoi(argv[1]) : 1u;
   const int rounds = argc > 2 ? std::atoi(argv[2]) : 300;
@@ -94,7 +148,8 @@ int main(int argc, char **argv) {
   hs.init(sh, 3000, 3000);
   std::vector<int64_t> known_ids;
   std::vector<int32_t> known_len;
-  int ok = 0, rejected = 0;
+  int ok = 0, rejected = 0, not_waited = 0;
+  std::vector<PendingCopy> pending;
   for (int it = 0; it < rounds; ++it) {
     const int action = rnd(0, 9);
     std::vector<std::vector<PageOp>> phases;
@@ -117,9 +172,17 @@ int main(int argc, char **argv) {
       rc == 0 ? ++ok : ++rejected;
       for (auto &ph : phases)
         for (auto &op : ph) CHECK(op.src >= 0 && op.dst >= 0);
+      if (rc == 0) {
+        not_waited += !pending.empty() && !hs.needs_lazy_wait;
+        check_pending(hs, phases, pending);
+      }
     } else if (action <= 7 && !hs.reqs.empty()) {  // pause one
       int rc = hs.pause(hs.reqs[rnd(0, (int)hs.reqs.size() - 1)].id, phases);
       rc == 0 ? ++ok : ++rejected;
+      if (rc == 0) {
+        not_waited += !pending.empty() && !hs.needs_lazy_wait;
+        check_pending(hs, phases, pending);
+      }
     } else if (action == 8 && !hs.paused.empty()) {
       CHECK(hs.drop_paused(hs.paused[rnd(0, (int)hs.paused.size() - 1)].id) == 0);
     } else if (!hs.reqs.empty()) {  // append one token everywhere when the window allows it
@@ -176,6 +239,7 @@ int main(int argc, char **argv) {
     d.push(i, t);
     while (d.pop_due(t, &tok, &when)) CHECK(when <= t);
   }
-  std::printf("host fuzz ok: seed %u, %d plan changes accepted, %d rejected\n", seed, ok, rejected);
+  std::printf("host fuzz ok: seed %u, %d plan changes accepted, %d rejected, %d ran beside earlier deferred copies\n", seed, ok,
+              rejected, not_waited);
   return 0;
 }

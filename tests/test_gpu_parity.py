@@ -728,8 +728,8 @@ def test_poisoned_staging_ranges_change_nothing():
             assert torch.equal(a.view(torch.int16), b.view(torch.int16))
 
 
-@pytest.mark.parametrize("seed", range(6))
-def test_unsynchronised_switches_pauses_and_steps(seed):
+@pytest.mark.parametrize("seed", list(range(6)) + [104])   # 104: a layer with blocks read in place beside host blocks
+def test_unsynchronised_switches_pauses_and_steps(seed):    # whose copies an earlier, still running switch had started
     """Seeded random plans, pauses / resumes and steps (whole steps and per-layer calls) enqueued back to back
     with no host-side wait anywhere, on contexts large enough that a switch's copies (the deferred ones run on
     the library's own stream) are still in flight for several of the steps behind it.  Every step's output equals,

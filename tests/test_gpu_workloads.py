@@ -301,3 +301,68 @@ def test_blocks_demoted_and_wanted_back_at_once_never_move(zero_copy):
 
     a, b = run(True), run(False)
     assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+@pytest.mark.parametrize("zero_copy", [False, True])
+def test_plan_loads_that_run_beside_the_copies_of_earlier_ones(zero_copy):
+    """Four plan loads in five steps, with no host-side wait anywhere: layer 1 leaves HBM (0.28 GB of deferred
+    copies), then layer 2 as well, beside the first copies and from a second op list, then layer 3, then layer 1
+    is wanted back, which reads what the first copies wrote and so waits for them.  Every step equals, bit for
+    bit, a run that never switched; the KV of a block that went out and came back reads back complete."""
+    import harness as h
+    from workloads import gen_q_steps, gen_kv
+    L, S = 4, 8
+    base = make_workload("llama8b_b16", 0, n_req=4)
+    lens = np.array([20000, 17001, 23000, 9000], dtype=base.ctx_len.dtype)
+    ones = np.ones((4, L), dtype=np.uint8)
+    plans = {}
+    x = ones.copy()
+    for s, (layer, v) in {1: (1, 0), 2: (2, 0), 3: (3, 0), 5: (1, 1)}.items():
+        x = x.copy()
+        x[:, layer] = v
+        plans[s] = x
+    w = dataclasses.replace(base, n_layers=L, ctx_len=lens, placement=ones, steps=S)
+    blocks = int(w.blocks(S).sum())
+    kw = dict(prefetch_slots=2, budget_pages=blocks * L + 2 * blocks + 64, host_pages=blocks * L + 64, decode_window=S,
+              max_tokens=int(lens.max()) + S + 16, zero_copy=zero_copy)
+
+    def run(switching: bool):
+        g = h.GpuRun(w, placement=ones, **kw)
+        B = w.n_req
+        q = torch.stack([torch.stack([gen_q_steps(w.seed, l, int(rid), 0, S, w.n_q_heads, w.head_dim, g.dev)
+                                      for rid in w.req_ids], dim=1) for l in range(L)], dim=1).contiguous()
+        kv = [[gen_kv(w.seed, l, int(rid), int(lens[r]), S, w.n_kv_heads, w.head_dim, g.dev)
+               for r, rid in enumerate(w.req_ids)] for l in range(L)]
+        k_new = torch.stack([torch.stack([kv[l][r][0] for r in range(B)], dim=1) for l in range(L)], dim=1).contiguous()
+        v_new = torch.stack([torch.stack([kv[l][r][1] for r in range(B)], dim=1) for l in range(L)], dim=1).contiguous()
+        outs = torch.zeros((S, L, B, w.n_q_heads, w.head_dim), dtype=torch.bfloat16, device=g.dev)
+        torch.cuda.synchronize()
+        waited = []
+        for s in range(S):
+            if switching and s in plans:
+                g.ctx.plan_load(w.req_ids, lens + s, plans[s])
+                info = g.ctx.get_plan_info()
+                waited.append(info["waited_for_deferred"])
+                if s < 5:
+                    assert info["deferred_to_host_blocks"] > 0 and info["moved_to_hbm_blocks"] == 0
+                else:
+                    assert info["moved_to_hbm_blocks"] == int(np.ceil((lens + s) / 16).sum())
+            g.ctx.step(q[s], k_new[s], v_new[s], outs[s])
+        g.cs.synchronize()
+        g.xs.synchronize()
+        res = outs.cpu()
+        if switching:
+            assert waited[0] == 0 and waited[1] == 0, waited   # (the later ones depend on how far the copies have come)
+            for r, l in ((0, 1), (2, 3), (1, 2)):
+                n = int(lens[r]) + S
+                k, v = g.read_kv(r, l, n - 40, 40)
+                kw_, vw_ = gen_kv(w.seed, l, int(w.req_ids[r]), n - 40, 40, w.n_kv_heads, w.head_dim, g.dev)
+                assert torch.equal(k.view(torch.int16), kw_.view(torch.int16))
+                assert torch.equal(v.view(torch.int16), vw_.view(torch.int16))
+            _check_groups(h, w, [outs[S - 1][l] for l in range(L)], None, lens.astype(np.int64) + S,
+                          [(1, 0, 3), (2, 2, 7), (3, 3, 0), (0, 1, 2)], step=S - 1)
+        g.close()
+        return res
+
+    a, b = run(True), run(False)
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))

@@ -697,3 +697,64 @@ def test_a_single_block_demotion_is_not_read_in_place():
     info = c.get_plan_info()
     assert info["moved_to_host_blocks"] == 1 and info["deferred_to_host_blocks"] == 0 and info["in_place_blocks"] == 0
     assert c.get_pages(1, 1)["tier"] == 0
+
+
+def test_a_plan_load_waits_for_earlier_deferred_copies_only_when_it_touches_their_pages():
+    """Blocks of 10 pages are demoted with deferred copies; the next plan loads are judged one by one: whether they
+    must wait for those copies follows from the pages they hand out and the blocks they move."""
+    L, B = 4, 2
+    n = [160, 160]
+    ids = [1, 2]
+    ones = np.ones((B, L), dtype=np.uint8)
+
+    def fresh(hbm_pages):
+        c = ctx(L=L, hbm_pages=hbm_pages, host_pages=4000, window=0, slots=1)
+        c.plan_load(ids, n, ones)
+        x = ones.copy()
+        x[:, 1] = 0                                          # layer 1 leaves: 2 x 9 deferred pages, 2 at once
+        c.plan_load(ids, n, x)
+        info = c.get_plan_info()
+        assert info["deferred_to_host_blocks"] == 18 and info["waited_for_deferred"] == 0
+        return c, x
+
+    # the blocks come back while their copies travel: they keep their pages, nobody else's page is touched
+    c, x = fresh(2000)
+    c.plan_load(ids, n, ones)
+    assert c.get_plan_info()["reclaimed_blocks"] == 20 and c.get_plan_info()["waited_for_deferred"] == 0
+
+    # another layer leaves as well, into host pages nobody has used: beside the first copies
+    c, x = fresh(2000)
+    x2 = x.copy()
+    x2[:, 2] = 0
+    c.plan_load(ids, n, x2)
+    info = c.get_plan_info()
+    assert info["deferred_to_host_blocks"] == 18 and info["waited_for_deferred"] == 0
+    # ... and a third plan load that brings layer 1 back reads host pages the first copies write
+    x3 = x2.copy()
+    x3[:, 1] = 1
+    c.plan_load(ids, n, x3)
+    info = c.get_plan_info()
+    assert info["moved_to_hbm_blocks"] == 20 and info["waited_for_deferred"] == 1
+    # after that wait nothing is outstanding but the copies of layer 2, which this one leaves alone
+    x4 = x3.copy()
+    x4[:, 3] = 0
+    c.plan_load(ids, n, x4)
+    assert c.get_plan_info()["waited_for_deferred"] == 0
+
+    # a new request that needs the vacated HBM pages: the arena has no other page left
+    c, x = fresh(hbm_pages=4 * 20 + 20)                      # 80 resident + 20 staging at the start
+    c.plan_load(ids + [3], n + [16], np.array([[1, 0, 1, 1], [1, 0, 1, 1], [1, 1, 1, 1]], dtype=np.uint8))
+    assert c.get_plan_info()["waited_for_deferred"] == 1
+
+    # the staging region grows down over the vacated pages
+    c, x = fresh(2000)
+    x5 = np.zeros((B, L), dtype=np.uint8)
+    c.plan_load(ids, n, x5, hbm_budget_bytes=60 * PAGE)
+    assert c.get_plan_info()["waited_for_deferred"] == 1
+
+    # the request leaves and a newcomer gets its host pages
+    c, x = fresh(2000)
+    c.plan_load([2], [160], x[1:])
+    assert c.get_plan_info()["waited_for_deferred"] == 0    # dropping alone touches nothing
+    c.plan_load([2, 9], [160, 100], np.array([[1, 0, 1, 1], [0, 0, 0, 0]], dtype=np.uint8))
+    assert c.get_plan_info()["waited_for_deferred"] == 1

@@ -400,7 +400,7 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     K, W = args.steps, args.warmup
-    total_steps = 1 + W + 2 * K + 26     # first, warm-up, timed, event-timed, searched-plan, all-resident variants, switch back
+    total_steps = 1 + W + 2 * K + 27     # first, warm-up, timed, event-timed, searched-plan, all-resident variants, switch back
     n_req, n_layers = args.n_req, args.n_layers
     host_bytes = int(args.max_host_gib * (1 << 30))
     while True:
@@ -602,16 +602,24 @@ def main():
             run.step()
             run.g.cs.synchronize()
             t1 = time.perf_counter()
+            run.g.ctx.plan_load(w.req_ids, run.lengths().astype("int32"), w.placement)   # the same plan, one token on
+            again = run.g.ctx.get_plan_info()
+            run.step()
+            run.g.cs.synchronize()
+            t2 = time.perf_counter()
             run.g.ctx.plan_load(w.req_ids, run.lengths().astype("int32"), np.ones_like(w.placement))
             back = run.g.ctx.get_plan_info()
             run.step()
             run.g.cs.synchronize()
-            t2 = time.perf_counter()
+            t3 = time.perf_counter()
             plan_switch["change_of_mind"] = {
-                "demote_and_step_ms": (t1 - t0) * 1e3, "promote_back_and_step_ms": (t2 - t1) * 1e3,
+                "demote_and_step_ms": (t1 - t0) * 1e3,
+                "same_plan_again_and_step_ms": (t2 - t1) * 1e3, "still_in_place_blocks": again["still_in_place_blocks"],
+                "promote_back_and_step_ms": (t3 - t2) * 1e3,
                 "reclaimed_blocks": back["reclaimed_blocks"], "copied_to_hbm_blocks": back["moved_to_hbm_blocks"],
-                "waited_for_deferred": back["waited_for_deferred"],
-                "note": "the second switch comes one step after the first: what is still read in place is not copied back"}
+                "waited_for_deferred": [again["waited_for_deferred"], back["waited_for_deferred"]],
+                "note": "plan loads one step apart while the first one's copies are travelling: what is still read "
+                        "in place stays where it is, and is not copied back when it is wanted in HBM again"}
         except Exception as e:
             plan_switch = (plan_switch or {})
             plan_switch["error"] = repr(e)[:300]

@@ -142,6 +142,9 @@ typedef struct {
   int64_t reclaimed_blocks;       /* blocks the last plan load wanted in HBM that were still being read in place
                                      there: they took their pages back, nothing was copied (not counted in
                                      moved_to_hbm_blocks)                                                   */
+  int64_t still_in_place_blocks;  /* blocks that an earlier plan load demoted, that were still read in place when the
+                                     last one came and that go on being read in place under it (they stay offloaded
+                                     and it left their old pages alone)                                      */
   int64_t waited_for_deferred;    /* 1 if the last plan load made its copies wait for deferred copies of earlier plan
                                      loads (it touched a page one of them reads or writes), 0 if it ran beside
                                      them or none were outstanding                                           */
@@ -184,13 +187,15 @@ ORBIT_API int orbit_plan_check(int32_t n_req, int32_t n_layers, int32_t page_tok
  * Blocks that leave HBM without their pages being needed at once (orbit_plan_info.deferred_to_host_blocks)
  * are copied out on a stream of the library's own, beside the following steps.  Until a layer's copies have
  * landed, attention reads such blocks of active requests where they were (orbit_plan_info.in_place_blocks:
- * their old pages are not handed out before the next plan load), a step's new token is written there and into
+ * their old pages are not handed out before a later plan load), a step's new token is written there and into
  * the host run, and the layer is not prefetched for them; the first prefetch of the layer issued after its
  * copies have completed (in the zero-copy mode: the first attention call) switches them to the staging region
  * (to their host pages).  Calls that need the host copy itself (orbit_kv_fill, orbit_kv_read, orbit_kv_append, a
- * decode window that outgrows the old pages) wait for the copies stream-side.  The next plan load ends the in-place
- * reads: a block it wants in HBM again keeps the pages it is being read from and nothing is copied
- * (orbit_plan_info.reclaimed_blocks); any other is read from its host run once its layer's copies have landed.  It
+ * decode window that outgrows the old pages) wait for the copies stream-side.  Under the next plan load a block that
+ * is still read in place and stays offloaded goes on being read in place if its old pages are not needed
+ * (orbit_plan_info.still_in_place_blocks); one that the plan wants in HBM again keeps the pages it is being read from
+ * and nothing is copied (orbit_plan_info.reclaimed_blocks); any other is read from its host run once its layer's
+ * copies have landed.  The plan load
  * waits for the copies itself only if it hands out an HBM page one of them still reads or a host page one of them
  * still writes, or moves a block whose host run they are still filling (orbit_plan_info.waited_for_deferred).
  * ORBIT_E_STATE if a prefetched layer has not been attended yet. */

@@ -60,7 +60,8 @@ class orbit_plan_info(C.Structure):
                 ("n_requests", C.c_int32), ("chunk_tokens", C.c_int32), ("evicted_blocks", C.c_int64),
                 ("paused_resident_blocks", C.c_int64), ("paused_requests", C.c_int32), ("reserved_", C.c_int32),
                 ("deferred_to_host_blocks", C.c_int64), ("in_place_blocks", C.c_int64),
-                ("reclaimed_blocks", C.c_int64), ("waited_for_deferred", C.c_int64)]
+                ("reclaimed_blocks", C.c_int64), ("still_in_place_blocks", C.c_int64),
+                ("waited_for_deferred", C.c_int64)]
 
     def as_dict(self):
         return {f: getattr(self, f) for f, _ in self._fields_}

@@ -24,8 +24,8 @@ using namespace orbit;
 namespace {
 std::string g_create_error;
 constexpr int kItemBufs = 2;  // pinned staging buffers of the work list
-// Width of the kernel that carries the deferred copies of a plan switch.  Nobody waits for these copies before the
-// next plan load: the blocks are read in place meanwhile, so a narrow kernel (about 20 GB/s) is the better one: it
+// Width of the kernel that carries the deferred copies of a plan switch.  Nobody waits for these copies before a
+// plan load that needs their pages: the blocks are read in place meanwhile, so a narrow kernel (about 20 GB/s) is the better one: it
 // leaves the compute units and the host->device direction of the link to the steps (measured behind an 11.5 GB
 // demotion, steps 1-3 after the switch: 66 / 64 / 109 ms with 8 workgroups, 80 / 115 / 184 ms with 32,
 // 120 / 154 / 203 ms with 128, 209 / 203 / 203 ms with 512; a steady step takes 203 ms).
@@ -97,6 +97,7 @@ struct orbit_ctx {
   // reads them waits for this one, whatever the newer copies (whose blocks are read in place) are doing.
   std::vector<hipEvent_t> ev_lazy_prev;
   std::vector<uint8_t> prev_x, prev_c;                       // per layer: copy / compute stream has yet to wait for ev_lazy_prev[l]
+  std::vector<uint8_t> settle_full;  // per layer: a plain host block's copies are among those ev_lazy[l] stands for
   bool lazy_outstanding = false;
   BlitOp *d_lazy[2] = {nullptr, nullptr};   // op lists of deferred copies: two, because the copies of one switch may
   size_t d_lazy_cap[2] = {0, 0};            // still be running when the next switch enqueues its own
@@ -184,9 +185,12 @@ int wait_deferred_older(orbit_ctx *c, int layer, bool on_copy_stream) {
 }
 
 // In front of a read of the layer's plain host blocks (those not read in place).  While blocks of the layer are still
-// read in place, the last plan load's copies are theirs and only the older ones matter.
+// read in place, the layer's newest copies are theirs and only the older ones matter, unless a plan load found a
+// plain block whose copies belong to the newest as well (settle_full).
 int settle_host_blocks(orbit_ctx *c, int layer, bool on_copy_stream) {
-  return c->hs.dual_in_layer[layer] ? wait_deferred_older(c, layer, on_copy_stream) : wait_deferred(c, layer, on_copy_stream);
+  if (c->host_only) return ORBIT_OK;
+  return c->hs.dual_in_layer[layer] && !c->settle_full[layer] ? wait_deferred_older(c, layer, on_copy_stream)
+                                                               : wait_deferred(c, layer, on_copy_stream);
 }
 
 // Blocks of `layer` that the last plan load demoted and that are still read where they were in HBM: once the
@@ -457,6 +461,7 @@ int retire_deferred(orbit_ctx *c) {
   std::fill(c->lazy_c.begin(), c->lazy_c.end(), 0);
   std::fill(c->prev_x.begin(), c->prev_x.end(), 0);
   std::fill(c->prev_c.begin(), c->prev_c.end(), 0);
+  std::fill(c->settle_full.begin(), c->settle_full.end(), 0);
   c->lazy_outstanding = false;
   c->hs.forget_deferred();
   return ORBIT_OK;
@@ -490,6 +495,12 @@ int apply_plan_gpu(orbit_ctx *c, const std::vector<std::vector<PageOp>> &phases)
     std::fill(c->prev_c.begin(), c->prev_c.end(), 0);
     c->lazy_outstanding = false;
   }
+  // Plain host blocks that earlier deferred copies may still be writing (HostState::plain_pending, nothing after a
+  // wait): where the layer keeps blocks read in place, a reader of the plain ones must not skip the layer's event.
+  // (A layer that gets copies of this plan load moves that event to ev_lazy_prev below instead.)
+  for (int l = 0; l < sh.L; ++l)
+    c->settle_full[l] = (c->lazy_x[l] || c->lazy_c[l]) && hs.plain_pending[l] && hs.dual_in_layer[l] &&
+                        hs.deferred_end[l] == (l ? hs.deferred_end[l - 1] : 0);
   size_t urgent = 0;
   for (auto &ph : phases) urgent += ph.size();
   const size_t total = urgent + hs.deferred.size();
@@ -554,7 +565,8 @@ int apply_plan_gpu(orbit_ctx *c, const std::vector<std::vector<PageOp>> &phases)
         const size_t hi = hs.deferred_end[l];
         if (hi > lo) {
           HIPCHECK(c, launch_blit_narrow(c->d_lazy[lb] + lo, (int64_t)(hi - lo), pb, kDeferredCopyWorkgroups, c->ds));
-          if (c->lazy_x[l] || c->lazy_c[l]) {  // copies of an earlier plan load that a stream has not waited for yet
+          if ((c->lazy_x[l] || c->lazy_c[l]) && hs.plain_pending[l]) {  // copies of an earlier plan load, into a block
+            // that is no longer read in place, that a stream has not waited for yet
             std::swap(c->ev_lazy[l], c->ev_lazy_prev[l]);
             c->prev_x[l] |= c->lazy_x[l];
             c->prev_c[l] |= c->lazy_c[l];
@@ -915,6 +927,7 @@ int orbit_create(const orbit_config *cfg, orbit_ctx **out) try {
   c->lazy_c.assign(sh.L, 0);
   c->prev_x.assign(sh.L, 0);
   c->prev_c.assign(sh.L, 0);
+  c->settle_full.assign(sh.L, 0);
   c->hs.live.reserve(sh.L + 1);
   c->items_key_tmp.reserve(sh.max_req + 1);
   c->flipped_tmp.reserve(sh.max_req);

@@ -55,7 +55,7 @@ struct LayerKV {
   int32_t host_cap = 0;        // pages in the host run
   int32_t stage_page0 = -1;    // first staging page (tier 0)
   // Non-empty while a block that the last plan load demoted is still on its way to the host: the HBM
-  // pages it had (no longer owned, but untouched until the next plan load) are read in place.
+  // pages it had (no longer owned, but untouched until a later plan load hands them out) are read in place.
   std::vector<int32_t> dual_pages;
 };
 
@@ -196,7 +196,7 @@ class HostState {
   // decode loop).  An HBM -> host copy whose source pages the new plan does not need at once (they lie
   // below the staging region and no allocation of this plan load took them) is taken out of `phases` and
   // listed here, grouped by layer: it may run beside the following steps, and only a later use of that
-  // layer's host blocks, or the next plan load, has to wait for it.
+  // layer's host blocks, or a later plan load that touches its pages (lazy_src_mark_), has to wait for it.
   //
   // A deferred block of an active request stays readable where it was (LayerKV::dual_pages): attention reads
   // those pages, the step's new token goes there and into the host run, and the layer is not prefetched for that
@@ -216,6 +216,10 @@ class HostState {
   int64_t lazy_src_top_ = 0;             // one past the highest marked HBM page
   bool lazy_marks_any_ = false;
   bool needs_lazy_wait = false;          // verdict of the last successful plan_load
+  // [L] after the last plan load: the layer has an active host block that is not read in place and whose host run
+  // a deferred copy not yet waited for may still be writing (whoever reads it must wait for the layer's copies even
+  // while other blocks of the layer are read in place)
+  std::vector<uint8_t> plain_pending;
 
   std::string err;
 
@@ -232,6 +236,7 @@ class HostState {
     dual_in_layer.assign(sh.L, 0);
     lazy_src_mark_.assign((size_t)arena_pages, 0);
     lazy_dst_mark_.assign((size_t)host_pages, 0);
+    plain_pending.assign(sh.L, 0);
   }
 
   // Every deferred copy has landed (the caller has seen it on the device): nothing is left to collide with.
@@ -265,7 +270,19 @@ class HostState {
   int plan_load(int32_t n_req, const int64_t *ids, const int32_t *ctx_len, const uint8_t *bitmap,
                 int64_t budget_bytes, std::vector<std::vector<PageOp>> &phases, int64_t pause_id = -1,
                 bool do_pause = false) {
+    // A host run gets a few pages more than the request has reserved, so that the next plan load, which reserves
+    // for a longer context, need not move the run (a copy of the whole block within the host arena, and a wait for
+    // whatever is still being written into it); if the arena has no room for that, the plan is laid out without.
+    int rc = plan_load_once(n_req, ids, ctx_len, bitmap, budget_bytes, phases, pause_id, do_pause, true);
+    if (rc == ORBIT_E_HOST_CAPACITY) rc = plan_load_once(n_req, ids, ctx_len, bitmap, budget_bytes, phases, pause_id, do_pause, false);
+    return rc;
+  }
+
+  int plan_load_once(int32_t n_req, const int64_t *ids, const int32_t *ctx_len, const uint8_t *bitmap,
+                     int64_t budget_bytes, std::vector<std::vector<PageOp>> &phases, int64_t pause_id, bool do_pause,
+                     bool host_slack) {
     phases.clear();
+    auto host_room = [&](int64_t blocks) { return blocks + (host_slack ? std::max<int64_t>(1, blocks >> 5) : 0); };
     if (n_req < 0 || n_req > sh.max_req) return fail(ORBIT_E_INVAL, "n_req out of range");
     if (n_req > 0 && (!ids || !ctx_len || !bitmap)) return fail(ORBIT_E_INVAL, "null argument");
     if (budget_bytes < 0) return fail(ORBIT_E_INVAL, "negative budget");
@@ -325,8 +342,41 @@ class HostState {
         reclaimed += ceil_div(lk.len, P);
       }
     }
-    for (auto &q : old)  // whatever else was still read in place is a plain host block for this plan: a step waits
-      for (auto &lk : q.layers) lk.dual_pages.clear();  // for its layer's copies before it reads the host run
+    // A block that is still read in place and stays offloaded goes on being read in place if this plan load leaves
+    // its pages alone: they are held back like the pages the plan load vacates, and what became of them is seen at
+    // the end.  Blocks of requests that leave the batch become plain host blocks: a step waits for their layer's
+    // copies before it reads the host run.
+    struct StillInPlace { int r, l; int64_t host_page0; };
+    std::vector<StillInPlace> still;
+    std::vector<int64_t> held, held_marked;
+    {
+      std::vector<uint8_t> stays(old.size(), 0);
+      for (int r = 0; r < n_req; ++r) {
+        const int o = find(ids[r]);
+        if (o < 0) continue;
+        stays[o] = 1;
+        for (int l = 0; l < L; ++l) {
+          const LayerKV &lk = old[o].layers[l];
+          if (lk.dual_pages.empty()) continue;
+          still.push_back({r, l, lk.host_page0});
+          for (int32_t pg : lk.dual_pages) {
+            A.used[pg] = 1;
+            held.push_back(pg);
+          }
+        }
+      }
+      for (size_t o = 0; o < old.size(); ++o)
+        if (!stays[o])
+          for (auto &lk : old[o].layers) lk.dual_pages.clear();
+      // Free pages that a deferred copy not yet waited for may still read are held back too (handing one out costs
+      // that wait), but go before the others when pages run short.
+      if (lazy_marks_any_)
+        for (int64_t pg = 0; pg < lazy_src_top_; ++pg)
+          if (lazy_src_mark_[pg] && !A.used[pg]) {
+            A.used[pg] = 1;
+            held_marked.push_back(pg);
+          }
+    }
     std::vector<Req> oldp = paused;
     std::vector<Req> np;  // paused after this call
     std::vector<Req> nw(n_req);
@@ -379,7 +429,6 @@ class HostState {
     std::vector<int32_t> taken;            // HBM pages this plan load allocated
     // Pages that evictions and demotions vacate are handed out again only when nothing else is free: a block
     // whose old pages stay untouched can leave HBM beside the following steps and be read in place meanwhile.
-    std::vector<int64_t> held;
     auto end_phase = [&](bool hold = false) {
       for (int64_t p : free_hbm) {
         if (hold) held.push_back(p);
@@ -391,9 +440,10 @@ class HostState {
     };
     auto take_page = [&]() -> int32_t {
       int32_t p = A.alloc_below(ring_first);
-      if (p < 0 && !held.empty()) {
-        for (int64_t h : held) A.release(h);
-        held.clear();
+      for (auto *pool : {&held_marked, &held}) {
+        if (p >= 0 || pool->empty()) continue;
+        for (int64_t h : *pool) A.release(h);
+        pool->clear();
         p = A.alloc_below(ring_first);
       }
       return p;
@@ -455,9 +505,10 @@ class HostState {
       for (int l = 0; l < L; ++l) {
         LayerKV &lk = nw[r].layers[l];
         if (lk.tier != 1 || x[(size_t)r * L + l]) continue;
-        int64_t run = H.alloc(rb[r]);
+        const int64_t room = host_room(rb[r]);
+        int64_t run = H.alloc(room);
         if (run < 0) return fail(ORBIT_E_HOST_CAPACITY, "host arena full or fragmented (demotion)");
-        new_host.push_back({run, rb[r]});
+        new_host.push_back({run, room});
         int64_t used = ceil_div(lk.len, P);
         to_host += used;
         for (int32_t p : lk.pages) free_hbm.push_back(p);
@@ -465,7 +516,7 @@ class HostState {
         lk.pages.clear();
         lk.tier = 0;
         lk.host_page0 = run;
-        lk.host_cap = (int32_t)rb[r];
+        lk.host_cap = (int32_t)room;
       }
     end_phase(true);
     // (c) host runs that must grow
@@ -474,19 +525,22 @@ class HostState {
       for (int l = 0; l < L; ++l) {
         LayerKV &lk = nw[r].layers[l];
         if (lk.tier != 0 || x[(size_t)r * L + l] || lk.host_cap >= rb[r]) continue;
-        if (H.extend(lk.host_page0, lk.host_cap, rb[r])) {  // room right behind the run: no copy
-          new_host.push_back({lk.host_page0 + lk.host_cap, rb[r] - lk.host_cap});
-          lk.host_cap = (int32_t)rb[r];
+        const int64_t room = host_room(rb[r]);
+        const int64_t grown = H.extend(lk.host_page0, lk.host_cap, room) ? room
+                              : H.extend(lk.host_page0, lk.host_cap, rb[r]) ? rb[r] : 0;
+        if (grown) {  // room right behind the run: no copy
+          new_host.push_back({lk.host_page0 + lk.host_cap, grown - lk.host_cap});
+          lk.host_cap = (int32_t)grown;
           continue;
         }
-        int64_t run = H.alloc(rb[r]);
+        int64_t run = H.alloc(room);
         if (run < 0) return fail(ORBIT_E_HOST_CAPACITY, "host arena full or fragmented (growth)");
-        new_host.push_back({run, rb[r]});
+        new_host.push_back({run, room});
         int64_t used = ceil_div(lk.len, P);
         for (int64_t i = 0; i < used; ++i) phases.back().push_back({OP_HOST_TO_HOST, lk.host_page0 + i, run + i});
         free_host.push_back({lk.host_page0, lk.host_cap});
         lk.host_page0 = run;
-        lk.host_cap = (int32_t)rb[r];
+        lk.host_cap = (int32_t)room;
       }
     end_phase();
     // (d) resident blocks sitting at or above the new staging region move below it
@@ -554,16 +608,19 @@ class HostState {
       for (int l = 0; l < L; ++l) {
         LayerKV &lk = nw[r].layers[l];
         if (lk.tier != 2) continue;
-        int64_t run = H.alloc(rb[r]);
+        const int64_t room = host_room(rb[r]);
+        int64_t run = H.alloc(room);
         if (run < 0) return fail(ORBIT_E_HOST_CAPACITY, "host arena full or fragmented (new request)");
-        new_host.push_back({run, rb[r]});
+        new_host.push_back({run, room});
         lk.tier = 0;
         lk.host_page0 = run;
-        lk.host_cap = (int32_t)rb[r];
+        lk.host_cap = (int32_t)room;
       }
 
-    for (int64_t h : held) A.release(h);
-    held.clear();
+    for (auto *pool : {&held_marked, &held}) {
+      for (int64_t h : *pool) A.release(h);
+      pool->clear();
+    }
 
     // staging schedule: each layer's offloaded requests occupy one contiguous range; ranges are
     // laid out round-robin over the staging region; inside a range, smallest request first.
@@ -600,18 +657,36 @@ class HostState {
     std::vector<PageOp> lazy;
     std::vector<size_t> lazy_end(L, 0);
     std::vector<int32_t> dual_count(L, 0);
-    int64_t n_deferred = 0, n_in_place = 0;
-    if (!groups.empty()) {
+    int64_t n_deferred = 0, n_in_place = 0, n_still = 0;
+    if (!groups.empty() || !still.empty()) {
       reuse_mark_.assign((size_t)arena_pages, 0);
       for (int32_t pg : taken) reuse_mark_[pg] = 1;
-      auto untouched = [&](int64_t pg) { return pg < ring_first && !reuse_mark_[pg]; };
+    }
+    auto untouched = [&](int64_t pg) { return pg < ring_first && !reuse_mark_[pg]; };
+    // The staging region grows downwards as the requests' reservations grow (a page per request and staging range
+    // every 16 tokens): a copy is deferred only if its source lies a little below the region, so that the next plan
+    // loads with the same placement need not wait for it.
+    const int64_t defer_below = ring_first - (sh.zero_copy ? 0 : (int64_t)sh.slots * n_req);
+    for (const StillInPlace &c : still) {  // its used pages untouched, its host run where it was: read in place on
+      LayerKV &lk = nw[c.r].layers[c.l];
+      size_t keep = 0;
+      while (keep < lk.dual_pages.size() && untouched(lk.dual_pages[keep])) ++keep;
+      if (lk.tier == 0 && lk.host_page0 == c.host_page0 && (int64_t)keep >= std::max<int64_t>(ceil_div(lk.len, P), 1)) {
+        lk.dual_pages.resize(keep);
+        ++dual_count[c.l];
+        n_still += ceil_div(lk.len, P);
+      } else {
+        lk.dual_pages.clear();
+      }
+    }
+    if (!groups.empty()) {
       std::vector<size_t> n_lazy(groups.size(), 0);  // the first n_lazy copies of the group are deferred
       std::vector<size_t> per_layer(L, 0), urgent(phases.size(), 0);
       for (size_t gi = 0; gi < groups.size(); ++gi) {
         DemoteGroup &g = groups[gi];
         const bool in_place = g.req >= 0;
         bool ok = g.n > (in_place ? 1u : 0u);
-        for (size_t i = 0; i < g.n && ok; ++i) ok = untouched(g.old_pages[i]);
+        for (size_t i = 0; i < g.n && ok; ++i) ok = untouched(g.old_pages[i]) && g.old_pages[i] < defer_below;
         if (ok) {
           n_lazy[gi] = in_place ? g.n - 1 : g.n;
           per_layer[g.layer] += n_lazy[gi];
@@ -666,6 +741,15 @@ class HostState {
     // commit
     needs_lazy_wait = wait_lazy;
     if (wait_lazy) forget_deferred();
+    std::fill(plain_pending.begin(), plain_pending.end(), 0);
+    if (lazy_marks_any_)
+      for (int r = 0; r < n_req; ++r)
+        for (int l = 0; l < L; ++l) {
+          const LayerKV &lk = nw[r].layers[l];
+          if (lk.tier != 0 || !lk.dual_pages.empty() || plain_pending[l]) continue;
+          for (int64_t pg = lk.host_page0; pg < lk.host_page0 + lk.host_cap && !plain_pending[l]; ++pg)
+            plain_pending[l] = lazy_dst_mark_[pg];
+        }
     for (const PageOp &op : lazy) {
       lazy_src_top_ = std::max(lazy_src_top_, op.src + 1);
       lazy_src_mark_[op.src] = 1;
@@ -676,6 +760,7 @@ class HostState {
     deferred_end = std::move(lazy_end);
     info.deferred_to_host_blocks = n_deferred;
     info.in_place_blocks = n_in_place;
+    info.still_in_place_blocks = n_still;
     info.reclaimed_blocks = reclaimed;
     info.waited_for_deferred = wait_lazy;  // (with a device behind it, the caller may still find a reason to wait)
     dual_in_layer = std::move(dual_count);

@@ -124,6 +124,58 @@ static void check_pending(const HostState &hs, const std::vector<std::vector<Pag
   }
 }
 
+// Where every block's tokens are: a tag (request, layer, block index) per HBM page and per host page, moved by the
+// copies a plan load asks for (the deferred ones after the others, as late as they may run), set where a step writes
+// a token and where a new request's KV is filled in.  Whatever an active or paused block would be read from must
+// carry the block's own tags; a block read in place must carry them in both of its homes.
+struct Tag {
+  int64_t id = -1;
+  int l = -1, i = -1;
+  bool is(int64_t id_, int l_, int i_) const { return id == id_ && l == l_ && i == i_; }
+};
+
+struct ContentModel {
+  std::vector<Tag> hbm, host;
+  std::set<int64_t> known;
+  void run(const PageOp &op) {
+    const Tag t = (op.kind == OP_HBM_TO_HOST || op.kind == OP_HBM_TO_HBM) ? hbm[op.src] : host[op.src];
+    ((op.kind == OP_HOST_TO_HBM || op.kind == OP_HBM_TO_HBM) ? hbm[op.dst] : host[op.dst]) = t;
+  }
+  void after_plan(const HostState &hs, const std::vector<std::vector<PageOp>> &phases) {
+    for (auto &ph : phases)
+      for (auto &op : ph) run(op);
+    for (auto &op : hs.deferred) run(op);
+    for (auto &q : hs.reqs)
+      if (known.insert(q.id).second)  // a new request: the caller fills its KV in
+        for (int l = 0; l < hs.sh.L; ++l)
+          for (int i = 0; i < (int)ceil_div(q.layers[l].len, hs.sh.P); ++i) write(q, l, i);
+  }
+  void write(const Req &q, int l, int i) {
+    const LayerKV &lk = q.layers[l];
+    const Tag t{q.id, l, i};
+    if (lk.tier == 1) hbm[lk.pages[i]] = t;
+    else host[lk.host_page0 + i] = t;
+    if (!lk.dual_pages.empty()) {
+      CHECK(i < (int)lk.dual_pages.size());
+      hbm[lk.dual_pages[i]] = t;
+    }
+  }
+  void check(const HostState &hs) const {
+    auto visit = [&](const Req &q) {
+      for (int l = 0; l < hs.sh.L; ++l) {
+        const LayerKV &lk = q.layers[l];
+        for (int i = 0; i < (int)ceil_div(lk.len, hs.sh.P); ++i) {
+          if (lk.tier == 1) CHECK(hbm[lk.pages[i]].is(q.id, l, i));
+          else CHECK(host[lk.host_page0 + i].is(q.id, l, i));
+          if (!lk.dual_pages.empty()) CHECK(hbm[lk.dual_pages[i]].is(q.id, l, i));
+        }
+      }
+    };
+    for (auto &q : hs.reqs) visit(q);
+    for (auto &q : hs.paused) visit(q);
+  }
+};
+
 int main(int argc, char **argv) {
   const unsigned seed = argc > 1 ? (unsigned)std::atoi(argv[1]) : 1u;
   const int rounds = argc > 2 ? std::atoi(argv[2]) : 300;
@@ -150,6 +202,10 @@ int main(int argc, char **argv) {
   std::vector<int32_t> known_len;
   int ok = 0, rejected = 0, not_waited = 0;
   std::vector<PendingCopy> pending;
+  ContentModel content;
+  content.hbm.resize(3000);
+  content.host.resize(3000);
+  int kept_in_place = 0;
   for (int it = 0; it < rounds; ++it) {
     const int action = rnd(0, 9);
     std::vector<std::vector<PageOp>> phases;
@@ -175,6 +231,8 @@ int main(int argc, char **argv) {
       if (rc == 0) {
         not_waited += !pending.empty() && !hs.needs_lazy_wait;
         check_pending(hs, phases, pending);
+        content.after_plan(hs, phases);
+        kept_in_place += hs.info.still_in_place_blocks > 0;
       }
     } else if (action <= 7 && !hs.reqs.empty()) {  // pause one
       int rc = hs.pause(hs.reqs[rnd(0, (int)hs.reqs.size() - 1)].id, phases);
@@ -182,6 +240,8 @@ int main(int argc, char **argv) {
       if (rc == 0) {
         not_waited += !pending.empty() && !hs.needs_lazy_wait;
         check_pending(hs, phases, pending);
+        content.after_plan(hs, phases);
+        kept_in_place += hs.info.still_in_place_blocks > 0;
       }
     } else if (action == 8 && !hs.paused.empty()) {
       CHECK(hs.drop_paused(hs.paused[rnd(0, (int)hs.paused.size() - 1)].id) == 0);
@@ -201,11 +261,15 @@ int main(int argc, char **argv) {
           if (must && hs.dual_in_layer[l]) hs.flip_layer(l, flipped);
         }
         for (auto &q : hs.reqs)
-          for (auto &lk : q.layers) lk.len += 1;
+          for (int l = 0; l < sh.L; ++l) {
+            content.write(q, l, q.layers[l].len / sh.P);
+            q.layers[l].len += 1;
+          }
       }
     }
     if (hs.has_plan) {
       check_layout(hs);
+      content.check(hs);
       std::vector<int32_t> items;
       bool all_nonempty = !hs.reqs.empty();
       for (auto &q : hs.reqs) all_nonempty &= q.layers[0].len > 0;
@@ -239,7 +303,7 @@ int main(int argc, char **argv) {
     d.push(i, t);
     while (d.pop_due(t, &tok, &when)) CHECK(when <= t);
   }
-  std::printf("host fuzz ok: seed %u, %d plan changes accepted, %d rejected, %d ran beside earlier deferred copies\n", seed, ok,
-              rejected, not_waited);
+  std::printf("host fuzz ok: seed %u, %d plan changes accepted, %d rejected, %d ran beside earlier deferred copies, %d kept blocks read in place\n",
+              seed, ok, rejected, not_waited, kept_in_place);
   return 0;
 }

@@ -307,7 +307,8 @@ def test_blocks_demoted_and_wanted_back_at_once_never_move(zero_copy):
 def test_plan_loads_that_run_beside_the_copies_of_earlier_ones(zero_copy):
     """Four plan loads in five steps, with no host-side wait anywhere: layer 1 leaves HBM (0.28 GB of deferred
     copies), then layer 2 as well, beside the first copies and from a second op list, then layer 3, then layer 1
-    is wanted back, which reads what the first copies wrote and so waits for them.  Every step equals, bit for
+    is wanted back (a real copy that waits for the first copies, or none at all if the layer is still read in
+    place, as earlier plan loads leave it when they do not need its pages).  Every step equals, bit for
     bit, a run that never switched; the KV of a block that went out and came back reads back complete."""
     import harness as h
     from workloads import gen_q_steps, gen_kv
@@ -345,8 +346,8 @@ def test_plan_loads_that_run_beside_the_copies_of_earlier_ones(zero_copy):
                 waited.append(info["waited_for_deferred"])
                 if s < 5:
                     assert info["deferred_to_host_blocks"] > 0 and info["moved_to_hbm_blocks"] == 0
-                else:
-                    assert info["moved_to_hbm_blocks"] == int(np.ceil((lens + s) / 16).sum())
+                else:                                       # copied back, or never left (if still read in place)
+                    assert info["moved_to_hbm_blocks"] + info["reclaimed_blocks"] == int(np.ceil((lens + s) / 16).sum())
             g.ctx.step(q[s], k_new[s], v_new[s], outs[s])
         g.cs.synchronize()
         g.xs.synchronize()

@@ -652,10 +652,20 @@ def test_demoted_blocks_are_read_in_place_until_their_copies_have_landed():
         assert p["tier"] == 0 and int(p["pages"][0]) >= info["staging_first_page"]
     assert c.get_pages(6, 2)["tier"] == 2
     c.decode_attention(1, None, None)
-    # a plan load settles whatever is still read in place
+    # a plan load that leaves the block offloaded and its old pages alone leaves it where it is read
     c.plan_load(ids, n, x)
-    assert c.get_pages(6, 2)["tier"] == 0 and c.get_plan_info()["in_place_blocks"] == 0
+    info = c.get_plan_info()
+    p = c.get_pages(6, 2)
+    assert p["tier"] == 2 and [int(v) for v in p["pages"]] == before[(6, 2)]
+    assert info["in_place_blocks"] == 0 and info["still_in_place_blocks"] == 7 and info["waited_for_deferred"] == 0
     _layout_invariants(c, ids, L)
+    # ... one that needs the pages does not: two newcomers that fill the arena up to the staging region
+    free_pages = info["staging_first_page"] - info["resident_blocks"]
+    rest = (free_pages - 512 * L) // L                   # blocks per layer left beside a request of 512 blocks
+    c.plan_load(ids + [8, 9], n + [8192 - 40, 16 * rest - 40], np.vstack([x, np.ones((2, L), dtype=np.uint8)]))
+    info = c.get_plan_info()
+    assert c.get_pages(6, 2)["tier"] == 0 and info["still_in_place_blocks"] == 0 and info["waited_for_deferred"] == 1
+    _layout_invariants(c, ids + [8, 9], L)
 
 
 def test_a_block_still_read_in_place_takes_its_pages_back():
@@ -679,7 +689,8 @@ def test_a_block_still_read_in_place_takes_its_pages_back():
     for r, l in ((5, 1), (6, 2)):
         p = c.get_pages(r, l)
         assert p["tier"] == 1 and [int(v) for v in p["pages"]] == before[(r, l)]
-    assert c.get_pages(7, 1)["tier"] == 0                # a plan load settles what stays on the host
+    assert c.get_pages(7, 1)["tier"] == 2                # what stays offloaded goes on being read in place
+    assert info["still_in_place_blocks"] == 3
     # once a layer has been handed over (in a host-only context: at its first prefetch), coming back is a real copy
     c.plan_load(ids, n, x)
     c.kv_prefetch(1)
@@ -729,7 +740,11 @@ def test_a_plan_load_waits_for_earlier_deferred_copies_only_when_it_touches_thei
     c.plan_load(ids, n, x2)
     info = c.get_plan_info()
     assert info["deferred_to_host_blocks"] == 18 and info["waited_for_deferred"] == 0
-    # ... and a third plan load that brings layer 1 back reads host pages the first copies write
+    assert info["still_in_place_blocks"] == 20           # layer 1 goes on being read in place
+    # ... and, once layer 1 has been handed over to its host runs (in a host-only context: at its first prefetch),
+    # a third plan load that brings it back reads host pages the first copies write
+    c.kv_prefetch(1)
+    c.decode_attention(1, None, None)
     x3 = x2.copy()
     x3[:, 1] = 1
     c.plan_load(ids, n, x3)

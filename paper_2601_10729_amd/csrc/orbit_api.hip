@@ -189,6 +189,9 @@ int wait_deferred_older(orbit_ctx *c, int layer, bool on_copy_stream) {
 // plain block whose copies belong to the newest as well (settle_full).
 int settle_host_blocks(orbit_ctx *c, int layer, bool on_copy_stream) {
   if (c->host_only) return ORBIT_OK;
+  bool any = false;  // (a layer whose blocks are all resident, or all read in place, has nothing to wait for)
+  for (const Req &q : c->hs.reqs) any |= q.layers[layer].tier == 0 && q.layers[layer].dual_pages.empty();
+  if (!any) return ORBIT_OK;
   return c->hs.dual_in_layer[layer] && !c->settle_full[layer] ? wait_deferred_older(c, layer, on_copy_stream)
                                                                : wait_deferred(c, layer, on_copy_stream);
 }
@@ -473,11 +476,19 @@ int apply_plan_gpu(orbit_ctx *c, const std::vector<std::vector<PageOp>> &phases)
   const Shape &sh = hs.sh;
   HIPCHECK(c, hipEventRecord(c->ev_plan_c, c->cs));
   HIPCHECK(c, hipStreamWaitEvent(c->xs, c->ev_plan_c, 0));
-  // Deferred copies of earlier switches may still be running.  This switch waits for them only if it touches a page
-  // they touch (HostState::needs_lazy_wait), or if it needs the op-list buffer their kernels still read.
+  // Deferred copies of earlier switches may still be running.  This switch waits for those of a layer only if it
+  // touches a page they touch (HostState::wait_layer), and for all of them if it needs the op-list buffer their
+  // kernels still read.
   const int lb = c->lazy_buf ^ 1;
-  bool wait_lazy = c->lazy_outstanding && hs.needs_lazy_wait;
-  if (c->lazy_outstanding && !wait_lazy && !hs.deferred.empty()) {
+  bool wait_lazy = false, waited_some = false;
+  if (c->lazy_outstanding && hs.needs_lazy_wait)
+    for (int l = 0; l < sh.L; ++l) {  // the copy stream waits for the layers this plan load collides with; the
+      if (!hs.wait_layer[l]) continue;  // compute stream waits for the copy stream below
+      HIPCHECK(c, hipStreamWaitEvent(c->xs, c->ev_lazy[l], 0));
+      c->lazy_x[l] = c->lazy_c[l] = c->prev_x[l] = c->prev_c[l] = 0;
+      waited_some = true;
+    }
+  if (c->lazy_outstanding && !hs.deferred.empty()) {
     const hipError_t e = hipEventQuery(c->ev_lazy_buf[lb]);
     if (e == hipErrorNotReady) {
       (void)hipGetLastError();
@@ -486,7 +497,7 @@ int apply_plan_gpu(orbit_ctx *c, const std::vector<std::vector<PageOp>> &phases)
       return hip_fail(c, e, "hipEventQuery(ev_lazy_buf)");
     }
   }
-  c->hs.info.waited_for_deferred = wait_lazy;
+  c->hs.info.waited_for_deferred = wait_lazy || waited_some;
   if (wait_lazy) {
     HIPCHECK(c, hipStreamWaitEvent(c->xs, c->ev_lazy_all, 0));
     std::fill(c->lazy_x.begin(), c->lazy_x.end(), 0);

@@ -212,10 +212,12 @@ class HostState {
   // only if it touches what they touch: it hands out an HBM page one of them still reads (to a block, or to the
   // staging region), or a host page one of them still writes (as part of a new or grown host run), or it reads
   // such a host page.  The marks collect the pages of every deferred copy since the last such wait.
-  std::vector<uint8_t> lazy_src_mark_, lazy_dst_mark_;  // [arena_pages], [host_pages]
+  std::vector<uint8_t> lazy_src_mark_, lazy_dst_mark_;  // [arena_pages], [host_pages]: 0, or 1 + the layer of the copy
   int64_t lazy_src_top_ = 0;             // one past the highest marked HBM page
   bool lazy_marks_any_ = false;
-  bool needs_lazy_wait = false;          // verdict of the last successful plan_load
+  bool needs_lazy_wait = false;          // verdict of the last successful plan_load: any layer's copies ...
+  std::vector<uint8_t> wait_layer;       // ... and which layers' [L]
+  static_assert(ORBIT_MAX_LAYERS < 255, "a page mark holds layer + 1 in a byte");
   // [L] after the last plan load: the layer has an active host block that is not read in place and whose host run
   // a deferred copy not yet waited for may still be writing (whoever reads it must wait for the layer's copies even
   // while other blocks of the layer are read in place)
@@ -237,6 +239,7 @@ class HostState {
     lazy_src_mark_.assign((size_t)arena_pages, 0);
     lazy_dst_mark_.assign((size_t)host_pages, 0);
     plain_pending.assign(sh.L, 0);
+    wait_layer.assign(sh.L, 0);
   }
 
   // Every deferred copy has landed (the caller has seen it on the device): nothing is left to collide with.
@@ -722,25 +725,36 @@ class HostState {
       }
     }
 
-    // Must the copies that earlier plan loads deferred be waited for?  (see lazy_src_mark_)
+    // Which of the copies that earlier plan loads deferred must be waited for?  (see lazy_src_mark_; a mark names
+    // the layer whose copies touch the page, and the copies of a layer have one event)
+    std::vector<uint8_t> wait(L, 0);
     bool wait_lazy = false;
     if (lazy_marks_any_) {
-      wait_lazy = lazy_src_top_ > ring_first;
-      for (size_t i = 0; i < taken.size() && !wait_lazy; ++i) wait_lazy = lazy_src_mark_[taken[i]];
-      for (size_t i = 0; i < new_host.size() && !wait_lazy; ++i)
-        for (int64_t pg = new_host[i].first; pg < new_host[i].first + new_host[i].second && !wait_lazy; ++pg)
-          wait_lazy = lazy_dst_mark_[pg];
-      for (size_t ph = 0; ph < phases.size() && !wait_lazy; ++ph)
-        for (const PageOp &op : phases[ph])
-          if ((op.kind == OP_HOST_TO_HBM || op.kind == OP_HOST_TO_HOST) && lazy_dst_mark_[op.src]) {
-            wait_lazy = true;
-            break;
-          }
+      auto hit = [&](uint8_t mark) {
+        if (mark) wait[mark - 1] = 1, wait_lazy = true;
+      };
+      for (int64_t pg = ring_first; pg < lazy_src_top_; ++pg) hit(lazy_src_mark_[pg]);
+      for (int32_t pg : taken) hit(lazy_src_mark_[pg]);
+      for (auto &run : new_host)
+        for (int64_t pg = run.first; pg < run.first + run.second; ++pg) hit(lazy_dst_mark_[pg]);
+      for (auto &ph : phases)
+        for (const PageOp &op : ph)
+          if (op.kind == OP_HOST_TO_HBM || op.kind == OP_HOST_TO_HOST) hit(lazy_dst_mark_[op.src]);
     }
 
     // commit
     needs_lazy_wait = wait_lazy;
-    if (wait_lazy) forget_deferred();
+    wait_layer = wait;
+    if (wait_lazy) {  // what has been waited for is forgotten
+      bool any = false;
+      for (auto *marks : {&lazy_src_mark_, &lazy_dst_mark_})
+        for (uint8_t &mk : *marks) {
+          if (mk && wait[mk - 1]) mk = 0;
+          any |= mk != 0;
+        }
+      lazy_marks_any_ = any;
+      if (!any) lazy_src_top_ = 0;
+    }
     std::fill(plain_pending.begin(), plain_pending.end(), 0);
     if (lazy_marks_any_)
       for (int r = 0; r < n_req; ++r)
@@ -750,12 +764,13 @@ class HostState {
           for (int64_t pg = lk.host_page0; pg < lk.host_page0 + lk.host_cap && !plain_pending[l]; ++pg)
             plain_pending[l] = lazy_dst_mark_[pg];
         }
-    for (const PageOp &op : lazy) {
-      lazy_src_top_ = std::max(lazy_src_top_, op.src + 1);
-      lazy_src_mark_[op.src] = 1;
-      lazy_dst_mark_[op.dst] = 1;
-      lazy_marks_any_ = true;
-    }
+    for (int l = 0; l < L; ++l)
+      for (size_t i = l ? lazy_end[l - 1] : 0; i < lazy_end[l]; ++i) {
+        const PageOp &op = lazy[i];
+        lazy_src_top_ = std::max(lazy_src_top_, op.src + 1);
+        lazy_src_mark_[op.src] = lazy_dst_mark_[op.dst] = (uint8_t)(l + 1);
+        lazy_marks_any_ = true;
+      }
     deferred = std::move(lazy);
     deferred_end = std::move(lazy_end);
     info.deferred_to_host_blocks = n_deferred;

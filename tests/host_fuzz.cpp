@@ -71,7 +71,7 @@ static void check_layout(const HostState &hs) {
 }
 
 // The deferred copies that no plan load has waited for yet, each with the block it carries.  A plan load that says it
-// need not wait for them (needs_lazy_wait == false) must leave them alone: an HBM page one of them reads stays with
+// need not wait for them (needs_lazy_wait == false, or a layer it does not name in wait_layer) must leave them alone: an HBM page one of them reads stays with
 // its block or with nobody and outside the staging region, a host page one of them writes stays with its block or
 // with nobody, and none of the copies the plan load runs at once writes either kind of page or reads such a host page.
 struct PendingCopy {
@@ -81,7 +81,12 @@ struct PendingCopy {
 
 static void check_pending(const HostState &hs, const std::vector<std::vector<PageOp>> &phases,
                           std::vector<PendingCopy> &pending) {
-  if (hs.needs_lazy_wait) pending.clear();
+  if (hs.needs_lazy_wait) {  // the layers it waits for (a layer's copies have one event) are settled
+    std::vector<PendingCopy> rest;
+    for (auto &pc : pending)
+      if (!hs.wait_layer[pc.layer]) rest.push_back(pc);
+    pending.swap(rest);
+  }
   std::vector<int> src_at((size_t)hs.arena_pages, -1), dst_at((size_t)hs.host_pages, -1);
   for (size_t i = 0; i < pending.size(); ++i) {
     src_at[pending[i].src] = (int)i;

@@ -226,6 +226,13 @@ def test_steps_run_in_place_while_a_large_demotion_is_in_flight(zero_copy):
                 info = g.ctx.get_plan_info()
                 assert info["in_place_blocks"] == info["moved_to_host_blocks"] == 3 * int(np.ceil((lens + s) / 16).sum())
                 assert info["deferred_to_host_blocks"] == info["in_place_blocks"] - 12      # one page per block went at once
+            if switching and s == 3:                         # the same plan again, one token on: nothing moves, nothing waits
+                g.ctx.plan_load(w.req_ids, lens + s, x)
+                info = g.ctx.get_plan_info()
+                assert info["moved_to_host_blocks"] == info["moved_to_hbm_blocks"] == 0 and info["waited_for_deferred"] == 0
+                assert info["still_in_place_blocks"] == sum(
+                    int(np.ceil((lens[r] + s) / 16)) for r, rid in enumerate(w.req_ids) for l in range(L)
+                    if g.ctx.get_pages(int(rid), l)["tier"] == 2)
             g.ctx.step(q[s], k_new[s], v_new[s], outs[s])
             if switching and s >= 2:
                 in_place.append(sum(g.ctx.get_pages(int(rid), l)["tier"] == 2 for rid in w.req_ids for l in range(L)))

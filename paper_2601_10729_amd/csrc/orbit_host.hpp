@@ -215,7 +215,7 @@ class HostState {
   std::vector<uint8_t> lazy_src_mark_, lazy_dst_mark_;  // [arena_pages], [host_pages]: 0, or 1 + the layer of the copy
   int64_t lazy_src_top_ = 0;             // one past the highest marked HBM page
   bool lazy_marks_any_ = false;
-  bool needs_lazy_wait = false;          // verdict of the last successful plan_load: any layer's copies ...
+  bool needs_lazy_wait = false;          // finding of the last successful plan_load: any layer's copies ...
   std::vector<uint8_t> wait_layer;       // ... and which layers' [L]
   static_assert(ORBIT_MAX_LAYERS < 255, "a page mark holds layer + 1 in a byte");
   // [L] after the last plan load: the layer has an active host block that is not read in place and whose host run

@@ -1,6 +1,6 @@
 """Runs the load-only streaming probe (tests/stream_probe.hip, built by tests/build_probe.py) and records what
 HBM read rate the chip delivers for the attention kernel's address pattern and for its alternatives.  The
-numbers go to gpurun_out/stream_probe.txt; the assertions only say that the probe ran and that the ordering the
+numbers go to a text file in the run's output folder; the assertions only say that the probe ran and that the ordering the
 design relies on holds (heads of a block range on one XCD beat heads scattered over XCDs)."""
 import os
 import subprocess

@@ -24,7 +24,8 @@ def test_stream_probe_rates():
     for line in res.stdout.strip().splitlines():
         name, us, gbs = line.split()
         rates[name] = (float(us), float(gbs))
-    assert set(rates) == {"kernel-pattern", "heads-scattered", "plain-loads", "whole-blocks", "kernel-pattern-4096"}
+    assert set(rates) == {"kernel-pattern", "heads-scattered", "plain-loads", "whole-blocks", "kernel-pattern-4096", "depth-3",
+                          "head-pair", "head-quad", "head-quad-256", "head-quad-depth-3", "kv-adjacent"}
     for name, (us, gbs) in rates.items():
         assert 2000.0 < gbs < 8000.0, (name, gbs)              # plausible for 8 TB/s HBM3E, and below its peak
     assert rates["kernel-pattern"][1] > rates["heads-scattered"][1]

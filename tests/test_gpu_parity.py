@@ -790,3 +790,96 @@ def test_unsynchronised_switches_pauses_and_steps(seed):    # whose copies an ea
     a, b = run(True), run(False)
     assert torch.isfinite(a.float()).all()
     assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_unsynchronised_switches_with_moving_budgets_arrivals_and_departures(seed):
+    """As above, with what makes one plan load collide with the copies of another: byte budgets that move the staging
+    region up and down from switch to switch, a request that joins the batch while copies travel (its host runs may be
+    ones a departed request gave up a moment ago) and one that leaves.  No host-side wait anywhere in the switching run;
+    every step's output, request by request, equals that of a run that keeps everything resident and waits after
+    every call, bit for bit, and so does the KV read back at the end."""
+    h = _harness()
+    from paper_2601_10729_amd import orbit_plan_check
+    from workloads import gen_q_steps, gen_kv
+    rng = np.random.default_rng(9000 + seed)
+    B, L, S = 5, 6, 12
+    lens = [int(x) for x in rng.integers(2000, 24000, size=B)]
+    w = _custom(lens, L=L, steps=S, seed=50 + seed)
+    zero_copy = seed % 3 == 1
+    slots = 2
+    join_at, leave_at = int(rng.integers(2, 6)), int(rng.integers(6, 10))     # request B-1 joins, request 0 leaves
+    plans = [rng.integers(0, 2, size=(B, L)).astype(np.uint8) for _ in range(6)]
+    script = [(int(rng.integers(0, 3)), int(rng.integers(0, 6)), int(rng.integers(0, 400))) for _ in range(S)]
+    arena_pages = int(w.blocks(2 * S).sum()) * (L + 3)
+
+    def active(s):
+        return [r for r in range(B) if (r != B - 1 or s >= join_at) and (r != 0 or s < leave_at)]
+
+    def run(switching: bool):
+        first = list(range(B))   # the context starts with all five; the one that joins later is dropped before the first step
+        g = h.GpuRun(w, placement=plans[0] if switching else np.ones((B, L), np.uint8), prefetch_slots=slots,
+                     budget_pages=arena_pages, host_pages=int(w.blocks(2 * S).sum()) * L * 2, decode_window=S,
+                     max_tokens=int(w.ctx_len.max()) + 2 * S + 16, zero_copy=zero_copy and switching)
+        dev = g.dev
+        q = torch.stack([torch.stack([gen_q_steps(w.seed, l, int(rid), 0, S, w.n_q_heads, w.head_dim, dev)
+                                      for rid in w.req_ids], dim=1) for l in range(L)], dim=1).contiguous()   # [S][L][B]...
+        # every input of every step is made first (on torch's stream) and kept alive to the end: the library's
+        # streams are not torch's, and nothing below waits for them
+        grown = np.zeros(B, dtype=np.int64)                           # tokens appended so far, per request
+        steps, prompts = [], {}
+        for s in range(S):
+            act = active(s)
+            n_now = (w.ctx_len.astype(np.int64) + grown)[act]
+            kv1 = [[gen_kv(w.seed, l, int(w.req_ids[r]), int(w.ctx_len[r] + grown[r]), 1, w.n_kv_heads, w.head_dim, dev)
+                    for r in act] for l in range(L)]
+            kn = torch.stack([torch.stack([kv1[l][i][0][0] for i in range(len(act))]) for l in range(L)]).contiguous()
+            vn = torch.stack([torch.stack([kv1[l][i][1][0] for i in range(len(act))]) for l in range(L)]).contiguous()
+            # queries are indexed by how many tokens the request has generated, so that a latecomer and the others
+            # see the same values in both runs
+            qs = torch.stack([torch.stack([q[int(grown[r]), l, r] for r in act]) for l in range(L)]).contiguous()
+            o = torch.zeros((L, len(act), w.n_q_heads, w.head_dim), dtype=torch.bfloat16, device=dev)
+            steps.append((act, n_now, qs, kn, vn, o))
+            grown[act] += 1
+        for l in range(L):
+            prompts[l] = gen_kv(w.seed, l, int(w.req_ids[B - 1]), 0, int(w.ctx_len[B - 1]), w.n_kv_heads, w.head_dim, dev)
+        torch.cuda.synchronize()
+        prev = first
+        for s, (kind, pi, slack) in enumerate(script):
+            act, n_now, qs, kn, vn, o = steps[s]
+            if act != prev or (switching and kind >= 1):
+                pl = plans[pi][act] if switching else np.ones((len(act), L), np.uint8)
+                budget = None
+                if switching and kind == 2 and not zero_copy:          # a budget that just fits, plus a little
+                    need = orbit_plan_check(n_now, pl, 16, slots, S)[2]
+                    budget = min(need + slack, arena_pages) * w.page_bytes
+                g.ctx.plan_load(w.req_ids[act], n_now.astype(np.int32), pl, budget)
+                if B - 1 in act and B - 1 not in prev:                 # the newcomer's prompt
+                    for l in range(L):
+                        g.ctx.kv_fill(int(w.req_ids[B - 1]), l, 0, prompts[l][0], prompts[l][1])
+                prev = act
+            g.ctx.step(qs, kn, vn, o)
+            if not switching:
+                g.cs.synchronize()
+                g.xs.synchronize()
+        g.cs.synchronize()
+        g.xs.synchronize()
+        res = {s: steps[s][5].cpu() for s in range(S)}
+        if switching:
+            for r in prev:
+                n = int(w.ctx_len[r] + grown[r])
+                ko = torch.empty((n, w.n_kv_heads, w.head_dim), dtype=torch.bfloat16, device=dev)
+                vo = torch.empty_like(ko)
+                for l in (0, L - 1):
+                    kw, vw = gen_kv(w.seed, l, int(w.req_ids[r]), 0, n, w.n_kv_heads, w.head_dim, dev)
+                    torch.cuda.synchronize()
+                    g.ctx.kv_read(int(w.req_ids[r]), l, 0, n, ko, vo)
+                    g.cs.synchronize()
+                    assert torch.equal(ko, kw) and torch.equal(vo, vw), (r, l)
+        g.close()
+        return res
+
+    a, b = run(True), run(False)
+    for s in range(S):
+        assert torch.isfinite(a[s].float()).all(), s
+        assert torch.equal(a[s].view(torch.int16), b[s].view(torch.int16)), s

@@ -796,7 +796,8 @@ def test_unsynchronised_switches_pauses_and_steps(seed):    # whose copies an ea
 def test_unsynchronised_switches_with_moving_budgets_arrivals_and_departures(seed):
     """As above, with what makes one plan load collide with the copies of another: byte budgets that move the staging
     region up and down from switch to switch, a request that joins the batch while copies travel (its host runs may be
-    ones a departed request gave up a moment ago) and one that leaves.  No host-side wait anywhere in the switching run;
+    ones a departed request gave up a moment ago), one that leaves, and one that is paused, squeezed out of HBM by the
+    next plan's budget (its eviction is a deferred copy as well) and resumed a few steps later.  No host-side wait anywhere in the switching run;
     every step's output, request by request, equals that of a run that keeps everything resident and waits after
     every call, bit for bit, and so does the KV read back at the end."""
     h = _harness()
@@ -809,12 +810,14 @@ def test_unsynchronised_switches_with_moving_budgets_arrivals_and_departures(see
     zero_copy = seed % 3 == 1
     slots = 2
     join_at, leave_at = int(rng.integers(2, 6)), int(rng.integers(6, 10))     # request B-1 joins, request 0 leaves
+    pause_at, resume_at = int(rng.integers(1, 5)), int(rng.integers(5, 11))   # request 1 is paused in between
     plans = [rng.integers(0, 2, size=(B, L)).astype(np.uint8) for _ in range(6)]
     script = [(int(rng.integers(0, 3)), int(rng.integers(0, 6)), int(rng.integers(0, 400))) for _ in range(S)]
     arena_pages = int(w.blocks(2 * S).sum()) * (L + 3)
 
     def active(s):
-        return [r for r in range(B) if (r != B - 1 or s >= join_at) and (r != 0 or s < leave_at)]
+        return [r for r in range(B) if (r != B - 1 or s >= join_at) and (r != 0 or s < leave_at)
+                and (r != 1 or not pause_at <= s < resume_at)]
 
     def run(switching: bool):
         first = list(range(B))   # the context starts with all five; the one that joins later is dropped before the first step
@@ -847,11 +850,13 @@ def test_unsynchronised_switches_with_moving_budgets_arrivals_and_departures(see
         prev = first
         for s, (kind, pi, slack) in enumerate(script):
             act, n_now, qs, kn, vn, o = steps[s]
+            if s == pause_at:
+                g.ctx.request_pause(int(w.req_ids[1]))
             if act != prev or (switching and kind >= 1):
                 pl = plans[pi][act] if switching else np.ones((len(act), L), np.uint8)
                 budget = None
-                if switching and kind == 2 and not zero_copy:          # a budget that just fits, plus a little
-                    need = orbit_plan_check(n_now, pl, 16, slots, S)[2]
+                if switching and (kind == 2 or s == pause_at):         # a budget that just fits, plus a little
+                    need = orbit_plan_check(n_now, pl, 16, slots, S)[0 if zero_copy else 2]
                     budget = min(need + slack, arena_pages) * w.page_bytes
                 g.ctx.plan_load(w.req_ids[act], n_now.astype(np.int32), pl, budget)
                 if B - 1 in act and B - 1 not in prev:                 # the newcomer's prompt

@@ -202,14 +202,15 @@ int main(int argc, char **argv) {
   sh.slots = rnd(1, 3);
   sh.zero_copy = rnd(0, 3) == 0;
   HostState hs;
-  hs.init(sh, 3000, 3000);
+  const int arena_pages = rnd(0, 2) ? 3000 : rnd(600, 3000), host_pages = rnd(0, 2) ? 3000 : rnd(400, 3000);  // sometimes tight
+  hs.init(sh, arena_pages, host_pages);
   std::vector<int64_t> known_ids;
   std::vector<int32_t> known_len;
   int ok = 0, rejected = 0, not_waited = 0;
   std::vector<PendingCopy> pending;
   ContentModel content;
-  content.hbm.resize(3000);
-  content.host.resize(3000);
+  content.hbm.resize(arena_pages);
+  content.host.resize(host_pages);
   int kept_in_place = 0;
   for (int it = 0; it < rounds; ++it) {
     const int action = rnd(0, 9);

@@ -244,7 +244,18 @@ def resident_variant(run, n_steps=3):
     st = run.timed_with_stats(n_steps)
     launch_bytes = float((run.lengths() - (n_steps + 1) / 2.0).sum()) * w.kv_bytes_per_token_layer
     attn = float(st["attn_ms"].mean())
-    return {"ms_per_step": ms, "effective_kv_gbs": launch_bytes * w.n_layers / (ms * 1e-3) / 1e9,
+    # the same steps issued layer by layer, as a model would (orbit_decode_layer: append + attention in one launch)
+    run.drain()
+    k = min(n_steps, run.total_steps - run.step_no)
+    t0 = time.perf_counter()
+    for _ in range(k):
+        s = run.step_no
+        for l in range(w.n_layers):
+            run.g.ctx.decode_layer(l, run.q_all[s][l], run.k_all[s][l], run.v_all[s][l], run.out[l])
+        run.step_no += 1
+    run.drain()
+    layer_ms = (time.perf_counter() - t0) * 1e3 / k if k > 0 else None
+    return {"ms_per_step": ms, "ms_per_step_layer_calls": layer_ms, "effective_kv_gbs": launch_bytes * w.n_layers / (ms * 1e-3) / 1e9,
             "step_frac_of_hbm_peak": launch_bytes * w.n_layers / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
             "attention_gbs": launch_bytes / (attn * 1e-3) / 1e9,
             "attention_frac_of_hbm_peak": launch_bytes / (attn * 1e-3) / 1e9 / HBM_PEAK_GBS,
@@ -400,7 +411,7 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     K, W = args.steps, args.warmup
-    total_steps = 1 + W + 2 * K + 27     # first, warm-up, timed, event-timed, searched-plan, all-resident variants, switch back
+    total_steps = 1 + W + 2 * K + 30     # first, warm-up, timed, event-timed, searched-plan, all-resident variants, switch back
     n_req, n_layers = args.n_req, args.n_layers
     host_bytes = int(args.max_host_gib * (1 << 30))
     while True:

@@ -259,6 +259,19 @@ ORBIT_API int orbit_kv_prefetch(orbit_ctx *ctx, int32_t layer);
  * combine on compute_stream.  ORBIT_E_INVAL if any request of the plan holds no token. */
 ORBIT_API int orbit_decode_attention(orbit_ctx *ctx, int32_t layer, const void *q, void *out, float *out_f32);
 
+/* One layer of a decode step, as a model's layer calls it between its QKV projection and its output projection
+ * (Section 3, "Runtime Executor": layers run in order; Section 3.2: the new KV of an offloaded layer goes straight
+ * to the host): appends k_new, v_new (device [n_req][Hkv][D] bf16, plan order) to every request of `layer` and
+ * attends q over the grown cache, in ONE launch (the workgroup that owns the new token's position takes its row
+ * from k_new / v_new, attends to it and stores it into the resident page, or into the staging copy and the host
+ * run), where orbit_kv_append_batch + orbit_decode_attention take two and a separate pass over the token.  Results
+ * equal those of the two calls, and of orbit_step, bit for bit.  Prefetches the layer if needed (over the lengths
+ * before the new token); to run ahead, call orbit_kv_prefetch for the following layers first.  q, out, out_f32 as
+ * for orbit_decode_attention.  ORBIT_E_STATE, with no length changed, if any request has used up its decode window
+ * or the layer's staging range is still needed by a prefetched layer not yet attended. */
+ORBIT_API int orbit_decode_layer(orbit_ctx *ctx, int32_t layer, const void *q, const void *k_new, const void *v_new,
+                                 void *out, float *out_f32);
+
 /* For callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses
  * that forbid hipMalloc.  Same arguments, same work, same results (bit for bit) and same errors as
  * orbit_decode_attention, but the call allocates nothing (no device memory, no pinned memory; the

@@ -75,7 +75,7 @@ class orbit_slo_report(C.Structure):
 
 EXPORTS = ["orbit_create", "orbit_destroy", "orbit_last_error", "orbit_plan_check", "orbit_plan_load",
            "orbit_get_plan_info", "orbit_request_pause", "orbit_request_drop", "orbit_kv_fill", "orbit_kv_read", "orbit_kv_append", "orbit_kv_append_batch", "orbit_kv_prefetch",
-           "orbit_decode_attention", "orbit_decode_attention_static", "orbit_step", "orbit_get_pages", "orbit_get_work_items",
+           "orbit_decode_attention", "orbit_decode_layer", "orbit_decode_attention_static", "orbit_step", "orbit_get_pages", "orbit_get_work_items",
            "orbit_get_copy_schedule", "orbit_distance_options", "orbit_distance_pattern", "orbit_model_latency",
            "orbit_plan_search", "orbit_plan_search_staggered", "orbit_plan_search_or_pause", "orbit_planner_create", "orbit_planner_destroy", "orbit_planner_submit",
            "orbit_planner_poll", "orbit_deposit_create", "orbit_deposit_destroy", "orbit_deposit_push",
@@ -112,6 +112,7 @@ def lib() -> C.CDLL:
     L.orbit_kv_prefetch.argtypes = [vp, i32]
     L.orbit_decode_attention.argtypes = [vp, i32, vp, vp, vp]
     L.orbit_decode_attention_static.argtypes = [vp, i32, vp, vp, vp]
+    L.orbit_decode_layer.argtypes = [vp, i32, vp, vp, vp, vp, vp]
     L.orbit_step.argtypes = [vp, vp, vp, vp, vp, C.POINTER(orbit_step_stats)]
     L.orbit_get_pages.argtypes = [vp, i64, i32, i32p, i64p, i32p, i32p, i64]
     L.orbit_get_pages.restype = i64
@@ -462,6 +463,9 @@ class OrbitContext:
 
     def decode_attention(self, layer: int, q, out, out_f32=None):
         self._check(self._L.orbit_decode_attention(self._h, layer, _ptr(q), _ptr(out), _ptr(out_f32)))
+
+    def decode_layer(self, layer: int, q, k_new, v_new, out, out_f32=None):
+        self._check(self._L.orbit_decode_layer(self._h, layer, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), _ptr(out_f32)))
 
     def decode_attention_static(self, layer: int, q, out, out_f32=None):
         self._check(self._L.orbit_decode_attention_static(self._h, layer, _ptr(q), _ptr(out), _ptr(out_f32)))

@@ -1290,6 +1290,34 @@ int orbit_decode_attention(orbit_ctx *c, int32_t layer, const void *q, void *out
   return c ? set_err(c, ORBIT_E_NOMEM, std::string("host allocation failed: ") + e.what()) : ORBIT_E_NOMEM;
 }
 
+int orbit_decode_layer(orbit_ctx *c, int32_t layer, const void *q, const void *k_new, const void *v_new, void *out,
+                       float *out_f32) try {
+  int rc = check_layer(c, layer);
+  if (rc) return rc;
+  HostState &hs = c->hs;
+  if (hs.reqs.empty()) return set_err(c, ORBIT_E_STATE, "the plan has no request");
+  if (!c->host_only && (!q || !k_new || !v_new || !out)) return set_err(c, ORBIT_E_INVAL, "null argument");
+  for (const Req &rq : hs.reqs)  // all or nothing: checked before any length moves
+    if (rq.layers[layer].len / hs.sh.P >= rq.reserved)
+      return set_err(c, ORBIT_E_STATE, "decode window used up: a request needs a block the plan did not reserve");
+  c->timing = false;
+  const bool staged = hs.block_of_layer[layer] >= 0;
+  if (staged) {  // the layer's copies are issued over the lengths before the new token, which the launch itself adds
+    LiveBlock *lb = find_live(c, layer);
+    if (!lb || lb->consumed) {
+      rc = prefetch_impl(c, layer);
+      if (rc == 1) return set_err(c, ORBIT_E_STATE, "staging range still needed by a prefetched layer not yet attended");
+      if (rc) return rc;
+    }
+    if (!c->host_only) HIPCHECK(c, hipStreamWaitEvent(c->cs, c->ev_ready[layer], 0));
+  }
+  for (Req &rq : hs.reqs) rq.layers[layer].len += 1;
+  if (staged) find_live(c, layer)->consumed = true;
+  return attention_impl(c, layer, q, out, out_f32, true, (const uint16_t *)k_new, (const uint16_t *)v_new);
+} catch (const std::exception &e) {  // nothing may unwind through the C ABI
+  return c ? set_err(c, ORBIT_E_NOMEM, std::string("host allocation failed: ") + e.what()) : ORBIT_E_NOMEM;
+}
+
 int orbit_decode_attention_static(orbit_ctx *c, int32_t layer, const void *q, void *out, float *out_f32) try {
   int rc = check_layer(c, layer);
   if (rc) return rc;

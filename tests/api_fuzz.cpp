@@ -140,6 +140,11 @@ int main(int argc, char **argv) {
           const int rc = orbit_kv_prefetch(ctx, rnd(l, L - 1));
           CHECK(rc == ORBIT_OK || rc == ORBIT_E_STATE);  // E_STATE: range still needed by a prefetched layer
         }
+        if (rnd(0, 2) == 0) {  // append and attention in one call; refused (nothing changed) if its staging range is taken
+          const int rc = orbit_decode_layer(ctx, l, nullptr, nullptr, nullptr, nullptr, nullptr);
+          CHECK(rc == ORBIT_OK || rc == ORBIT_E_STATE);
+          if (rc == ORBIT_OK) continue;
+        }
         if (rnd(0, 1)) {
           CHECK(orbit_kv_append_batch(ctx, l, nullptr, nullptr) == ORBIT_OK);
         } else {

@@ -888,3 +888,63 @@ def test_unsynchronised_switches_with_moving_budgets_arrivals_and_departures(see
     for s in range(S):
         assert torch.isfinite(a[s].float()).all(), s
         assert torch.equal(a[s].view(torch.int16), b[s].view(torch.int16)), s
+
+
+@pytest.mark.parametrize("zero_copy", [False, True])
+def test_decode_layer_equals_step_and_the_two_call_path(zero_copy):
+    """orbit_decode_layer (append + attention of one layer in one launch, as a model's layer calls it) against
+    orbit_step and against orbit_kv_append_batch + orbit_decode_attention: outputs and the grown cache bit for bit,
+    with prefetches run ahead by hand, across a block boundary (17 -> 37 tokens) and a plan switch in the middle;
+    the last step is also checked against the oracle."""
+    h = _harness()
+    S = 20
+    lens = [17, 777, 2050, 5000]
+    pl = [[1, 0, 1], [0, 1, 0], [1, 1, 0], [0, 0, 1]]
+    w = _custom(lens, L=3, Hq=32, Hkv=8, placement=pl, steps=S)
+    pl2 = 1 - np.asarray(pl, dtype=np.uint8)
+
+    def run(mode):
+        g = h.GpuRun(w, prefetch_slots=2, zero_copy=zero_copy, decode_window=S,
+                     budget_pages=int(w.blocks(2 * S).sum()) * 5 + 16, host_pages=int(w.blocks(2 * S).sum()) * 4)
+        outs = []
+        for s in range(S):
+            if s == 9:
+                g.ctx.plan_load(w.req_ids, (w.ctx_len + s).astype(np.int32), pl2)
+            if mode == "step":
+                out, _ = g.step(s)
+            else:
+                q = g.q_all(s)
+                k_new, v_new = g.kv_new_all()
+                out = torch.empty((w.n_layers, w.n_req, w.n_q_heads, w.head_dim), dtype=torch.bfloat16, device=g.dev)
+                torch.cuda.synchronize()
+                for l in range(w.n_layers):
+                    if mode == "layer":
+                        if l + 1 < w.n_layers:
+                            g.ctx.kv_prefetch(l + 1)              # run ahead by one layer
+                        g.ctx.decode_layer(l, q[l], k_new[l], v_new[l], out[l])
+                    else:
+                        g.ctx.kv_append_batch(l, k_new[l], v_new[l])
+                        g.ctx.decode_attention(l, q[l], out[l])
+                g.cs.synchronize()
+                g.xs.synchronize()
+                g.len += 1
+            outs.append(out.cpu())
+        kv = [g.read_kv(r, l, 0, lens[r] + S) for r in range(4) for l in range(3)]
+        kv = [(k.cpu(), v.cpu()) for k, v in kv]
+        last = out
+        g.close()
+        return outs, kv, last
+
+    a, kva, _ = run("step")
+    b, kvb, last = run("layer")
+    c, kvc, _ = run("two calls")
+    for s in range(S):
+        assert torch.equal(a[s].view(torch.int16), b[s].view(torch.int16)), s
+        assert torch.equal(a[s].view(torch.int16), c[s].view(torch.int16)), s
+    for (ka, va), (kb, vb), (kc, vc) in zip(kva, kvb, kvc):
+        assert torch.equal(ka, kb) and torch.equal(va, vb) and torch.equal(ka, kc) and torch.equal(va, vc)
+    o = h.OracleRun(w, extra_tokens=S)
+    for _ in range(S):
+        o.append_all()
+    for l in range(3):
+        _check(last[l], None, o.attention(l, S - 1))

@@ -773,3 +773,20 @@ def test_a_plan_load_waits_for_earlier_deferred_copies_only_when_it_touches_thei
     assert c.get_plan_info()["waited_for_deferred"] == 0    # dropping alone touches nothing
     c.plan_load([2, 9], [160, 100], np.array([[1, 0, 1, 1], [0, 0, 0, 0]], dtype=np.uint8))
     assert c.get_plan_info()["waited_for_deferred"] == 1
+
+
+def test_decode_layer_moves_one_layers_lengths_and_respects_the_window():
+    L = 3
+    c = ctx(L=L, hbm_pages=500, window=2)
+    ids = [4, 5]
+    c.plan_load(ids, [30, 40], np.array([[1, 0, 1], [0, 1, 1]], dtype=np.uint8))
+    c.decode_layer(1, None, None, None, None)
+    assert [c.get_pages(4, l)["length"] for l in range(L)] == [30, 31, 30]
+    assert [c.get_pages(5, l)["length"] for l in range(L)] == [40, 41, 40]
+    c.decode_layer(1, None, None, None, None)              # 32 tokens fill the two blocks request 4 has reserved
+    with pytest.raises(OrbitError) as e:
+        c.decode_layer(1, None, None, None, None)
+    assert e.value.code == orbit.ORBIT_E_STATE
+    assert c.get_pages(4, 1)["length"] == 32 and c.get_pages(5, 1)["length"] == 42      # nothing moved
+    with pytest.raises(OrbitError):
+        c.decode_layer(7, None, None, None, None)          # no such layer

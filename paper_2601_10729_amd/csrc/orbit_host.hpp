@@ -211,7 +211,8 @@ class HostState {
   // Deferred copies of earlier plan loads may still be running when the next one comes.  It has to wait for them
   // only if it touches what they touch: it hands out an HBM page one of them still reads (to a block, or to the
   // staging region), or a host page one of them still writes (as part of a new or grown host run), or it reads
-  // such a host page.  The marks collect the pages of every deferred copy since the last such wait.
+  // such a host page.  The marks hold the pages of every deferred copy that no plan load has waited for yet; a
+  // wait is for the copies of whole layers (one event each), and takes those layers' marks away.
   std::vector<uint8_t> lazy_src_mark_, lazy_dst_mark_;  // [arena_pages], [host_pages]: 0, or 1 + the layer of the copy
   int64_t lazy_src_top_ = 0;             // one past the highest marked HBM page
   bool lazy_marks_any_ = false;

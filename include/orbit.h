@@ -266,7 +266,8 @@ ORBIT_API int orbit_decode_attention(orbit_ctx *ctx, int32_t layer, const void *
  * from k_new / v_new, attends to it and stores it into the resident page, or into the staging copy and the host
  * run), where orbit_kv_append_batch + orbit_decode_attention take two and a separate pass over the token.  Results
  * equal those of the two calls, and of orbit_step, bit for bit.  Prefetches the layer if needed (over the lengths
- * before the new token); to run ahead, call orbit_kv_prefetch for the following layers first.  q, out, out_f32 as
+ * before the new token); to run ahead, call orbit_kv_prefetch for this layer and then for the following ones
+ * before the call (in that order: a later layer may be given the staging range this one needs).  q, out, out_f32 as
  * for orbit_decode_attention.  ORBIT_E_STATE, with no length changed, if any request has used up its decode window
  * or the layer's staging range is still needed by a prefetched layer not yet attended. */
 ORBIT_API int orbit_decode_layer(orbit_ctx *ctx, int32_t layer, const void *q, const void *k_new, const void *v_new,

@@ -920,7 +920,8 @@ def test_decode_layer_equals_step_and_the_two_call_path(zero_copy):
                 for l in range(w.n_layers):
                     if mode == "layer":
                         if l + 1 < w.n_layers:
-                            g.ctx.kv_prefetch(l + 1)              # run ahead by one layer
+                            g.ctx.kv_prefetch(l)                  # run ahead by one layer: own copies first
+                            g.ctx.kv_prefetch(l + 1)
                         g.ctx.decode_layer(l, q[l], k_new[l], v_new[l], out[l])
                     else:
                         g.ctx.kv_append_batch(l, k_new[l], v_new[l])

@@ -34,7 +34,8 @@ def _oracle_layer(layer, rids, lens, step_no):
 
 @pytest.mark.parametrize("seed", range(4))
 def test_random_operation_sequences(seed, n_ops=36):
-    from paper_2601_10729_amd import OrbitContext, OrbitError, orbit_plan_check, ORBIT_E_CAPACITY, ORBIT_E_HOST_CAPACITY
+    from paper_2601_10729_amd import (OrbitContext, OrbitError, orbit_plan_check, ORBIT_E_CAPACITY, ORBIT_E_HOST_CAPACITY,
+                                      ORBIT_E_STATE)
     import harness as h
     rng = np.random.default_rng(500 + seed)
     dev = torch.device("cuda:0")
@@ -112,9 +113,18 @@ def test_random_operation_sequences(seed, n_ops=36):
             out = torch.empty((L, B, HQ, D), dtype=torch.bfloat16, device=dev)
             q, kn, vn = q.contiguous(), kn.contiguous(), vn.contiguous()
             sync()
-            how = rng.choice(["step", "prefetch first", "append first", "no prefetch"])
+            how = rng.choice(["step", "prefetch first", "append first", "no prefetch", "layer call"])
             if how == "step":
                 ctx.step(q, kn, vn, out)
+            elif how == "layer call":               # append and attention of a layer in one call, one layer run ahead
+                for layer in range(L):
+                    if layer + 1 < L and rng.random() < 0.5:
+                        ctx.kv_prefetch(layer)      # this layer's own copies first: the next one may want the same range
+                        try:
+                            ctx.kv_prefetch(layer + 1)
+                        except OrbitError as e:
+                            assert e.code == ORBIT_E_STATE, e
+                    ctx.decode_layer(layer, q[layer], kn[layer], vn[layer], out[layer])
             else:                                   # the same step through the per-layer calls, in varying order
                 for layer in range(L):
                     if how == "prefetch first":
